@@ -1,0 +1,110 @@
+"""Benchmark of the hot path on one MI355X.
+
+Workload: the K-async softmax-regression configuration the metric is quoted on (d=3072, 10 classes,
+N=50000 Gaussian-mixture samples, P=8 virtual workers, m=32, K=2, shifted-exponential delays (0.5, 1),
+lr=0.05, J=5000 updates), run as R independent replicas in one launch.  A step is one pass of the whole
+hot path: the schedule (delays, K-of-P selection, staleness) and all J updates (gather, gradients at
+stale parameters, aggregate, update) of every replica, with the data resident in HBM.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(X, y, spec, budget_s=12.0):
+    """The oracle, as it stands, on one host core, for a bounded number of updates."""
+    import oracle
+    tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", oracle.Dist(*spec), 0.05, seed=0)
+    t0 = time.perf_counter()
+    done = 0
+    while time.perf_counter() - t0 < budget_s and done < 5000:
+        tr.run(50)
+        done += 50
+    dt = time.perf_counter() - t0
+    return {"value": done * 2 / dt, "unit": "worker-gradients/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {done} of 5000 updates of replica 0 ({done * 2} worker-gradients), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--replicas", type=int, default=int(os.environ.get("SSGD_BENCH_REPLICAS", "40")))
+    ap.add_argument("--updates", type=int, default=5000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2003_10579_amd import ssgd, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    ssgd.lib()
+    P, K, m, d, C, N, J, R = 8, 2, 32, 3072, 10, 50000, args.updates, args.replicas
+    spec = ("shifted_exp", 0.5, 1.0)
+    X, y = synth.mixture_data(N, d, C, seed=0)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+
+    def timed(replicas, steps, warmup):
+        ctx = ssgd.Context("softmax", Xd, yd, P, K, m, "k_async", ssgd.delay_dist(*spec), 0.05, seed=0, classes=C,
+                           replicas=replicas)
+        ctx.reserve_trace((steps + warmup) * J)
+        for _ in range(warmup):
+            ctx.run(J)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        kms, kn = 0.0, 0
+        for _ in range(steps):
+            ctx.run(J)
+            ms, n = ctx.last_kernel_ms()
+            kms += ms * n
+            kn += n
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        loss = float(ctx.trace(0, ctx.updates - 100, 100)["loss"].mean())
+        ctx.close()
+        return dt, kms, kn, loss
+
+    dt, kms, kn, loss = timed(R, args.steps, args.warmup)
+    grads = R * J * K * args.steps
+    value = grads / dt
+    b_alg = m * (d + 1) * 4                      # sample rows + labels of one worker-gradient
+    per_launch_bytes = grads / kn * b_alg
+    achieved = per_launch_bytes / (kms / kn * 1e-3) / 1e9
+    dt1, _, _, _ = timed(1, 1, 1)
+    out = {
+        "metric": "worker-gradients/sec (K-async, d=3072) + % of HBM peak; MC trials/sec",
+        "value": value, "unit": "worker-gradients/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config 1: softmax regression K-async, d=3072, 10 classes, N=50000, P=8, m=32, K=2, "
+                               f"shifted-exp(0.5,1), lr=0.05, J={J}, {R} independent replicas per launch",
+                   "replicas": R, "updates_per_step": J, "final_loss_replica0": loss,
+                   "value_replicas_1": 1 * J * K / dt1},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "linear_cluster_kernel<4>", "launches": kn, "avg_launch_ms": kms / kn,
+                     "algorithmic_bytes_per_launch": per_launch_bytes},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(X, y, spec)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

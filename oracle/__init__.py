@@ -65,6 +65,7 @@ def lib():
         L.orc_round_bf16.argtypes = [C.c_float]
         L.orc_delay_from_bits.restype = C.c_float
         L.orc_delay_from_bits.argtypes = [C.POINTER(_Dist), C.c_uint32]
+        L.orc_delays_from_bits.argtypes = [C.POINTER(_Dist), C.c_void_p, C.c_int64, C.c_void_p]
         L.orc_delay.restype = C.c_float
         L.orc_delay.argtypes = [C.POINTER(_Dist), C.c_uint64, C.c_uint32, C.c_int32, C.c_int32,
                                 C.c_uint32, C.c_uint32, C.c_uint32]
@@ -140,9 +141,10 @@ class Dist:
         self.c = d
 
     def from_bits(self, bits):
-        bits = np.atleast_1d(np.asarray(bits, dtype=np.uint32))
-        f = lib().orc_delay_from_bits
-        return np.array([f(C.byref(self.c), int(b)) for b in bits], dtype=np.float32)
+        bits = np.ascontiguousarray(np.atleast_1d(bits), dtype=np.uint32)
+        out = np.zeros(bits.size, dtype=np.float32)
+        lib().orc_delays_from_bits(C.byref(self.c), bits.ctypes.data, bits.size, out.ctypes.data)
+        return out
 
 
 def delay(dist: Dist, seed, replica, P, table_ord, worker, ordinal, version):

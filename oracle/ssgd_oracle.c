@@ -165,6 +165,11 @@ float orc_delay_from_bits(const orc_dist *dist, uint32_t bits)
     }
 }
 
+void orc_delays_from_bits(const orc_dist *dist, const uint32_t *bits, int64_t n, float *out)
+{
+    for (int64_t q = 0; q < n; ++q) out[q] = orc_delay_from_bits(dist, bits[q]);
+}
+
 /* Delay of the `ordinal`-th mini-batch that `worker` starts after reading
  * parameter version `version`.  `table_ord` is the number of ordinals a TABLE
  * distribution reserves per (version, worker). */
@@ -744,7 +749,9 @@ void orc_get_workers(const orc_ctx *c, int64_t *tau, double *finish)
 /* Trial r: P fresh delays X(r,i).  For every K in [Kmin, Kmax] the chosen    */
 /* variant's event process is run for chain_len updates from that fresh start */
 /* and T_l = t_l - t_{l-1} is recorded.  The first delays of a trial are      */
-/* shared by all K; later ones are keyed by K as well.                        */
+/* shared by all K; later ones are keyed by K as well, and by the rank of the */
+/* finisher they replace (delays are i.i.d., so T_l depends on the multiset   */
+/* of finish times only, not on which worker holds which).                    */
 /*   K-sync        every update is a fresh start: T_l = K-th smallest of P    */
 /*   K-batch-sync  every update is a fresh start with immediate re-draws      */
 /*   K-async       contributors restart at t_l, the rest keep running         */
@@ -785,8 +792,10 @@ int orc_runtime_mc(int32_t variant, int32_t P, int32_t Kmin, int32_t Kmax, const
                         int32_t i = argmin_free(f, taken, P);
                         taken[i] = 1; who[a] = i; t_new = f[i];
                     }
+                    /* the a-th earliest finisher takes the a-th fresh delay of this update:
+                     * the process only depends on the multiset of finish times */
                     for (int32_t a = 0; a < K; ++a)
-                        f[who[a]] = t_new + (double)mc_delay(dist, seed, trial, P, (uint32_t)K, who[a], 0, l + 1);
+                        f[who[a]] = t_new + (double)mc_delay(dist, seed, trial, P, (uint32_t)K, a, 0, l + 1);
                 } else {
                     if (l > 0)
                         for (int32_t i = 0; i < P; ++i)
@@ -806,10 +815,10 @@ int orc_runtime_mc(int32_t variant, int32_t P, int32_t Kmin, int32_t Kmax, const
                             int32_t i = argmin_free(f, NULL, P);
                             last = f[i];
                             r[i] += 1;
-                            /* re-draws of the first update are keyed by K too, so
-                             * that they never collide with another K's chain */
+                            /* the a-th finished mini-batch is followed by the a-th re-draw
+                             * (ordinal 1 keeps these apart from the fresh delays) */
                             if (a + 1 < K)
-                                f[i] = f[i] + (double)mc_delay(dist, seed, trial, P, (uint32_t)K, i, r[i], l);
+                                f[i] = f[i] + (double)mc_delay(dist, seed, trial, P, (uint32_t)K, a, 1, l);
                         }
                         t_new = t + last;
                     }

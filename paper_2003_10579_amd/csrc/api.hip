@@ -1,0 +1,514 @@
+// C ABI of the library (see include/ssgd.h): argument checks, device state, and the
+// host loop that alternates schedule segments with gradient/update launches.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/ssgd.h"
+#include "common.hpp"
+#include "mlp.hpp"
+
+using namespace ssgd;
+
+namespace {
+
+thread_local std::string g_err;
+
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    hipError_t alloc(size_t n) {
+        bytes = n;
+        return hipMalloc(&p, n ? n : 1);
+    }
+    void release() { if (p) (void)hipFree(p); p = nullptr; }
+    template <class T> T* as() const { return reinterpret_cast<T*>(p); }
+};
+
+}  // namespace
+
+struct ssgd_ctx {
+    ssgd_model model{};
+    int32_t P = 0, K0 = 0, m = 0, mp = 0, variant = 0, R = 0;
+    ssgd_adasync ada{};
+    Dist dist{};
+    DevBuf table;
+    double lr = 0;
+    uint64_t seed = 0;
+    hipStream_t stream = nullptr;
+    int device = 0;
+    int64_t nw = 0;
+    int32_t Kcap = 0, S = 0, G = 0, nbw = 0, maxrows = 0, table_ord = 1;
+    int64_t j = 0;
+    int32_t win_cnt = 0;
+    bool broken = false;
+
+    Trace tr{};
+    DevBuf tr_t, tr_loss, tr_K, tr_sel, tr_tau, tr_ord;
+    WorkerState ws{};
+    DevBuf ws_finish, ws_tau, ws_ord, ws_clock, ws_curK, ws_winprev, ws_winidx, ws_F0, ws_intstart, ws_crossed, ws_ndone;
+    DevBuf params, park, park_small, zpart, arrive, abort_flag;
+    int resident_groups = 0;
+    size_t lds_bytes = 0;
+    MlpState* mlp = nullptr;
+
+    double last_ms = 0;
+    int64_t last_launches = 0;
+    std::string err;
+};
+
+namespace {
+
+}  // namespace
+namespace ssgd { void set_global_error(const std::string& msg) { g_err = msg; } }
+namespace {
+ssgd_status fail(ssgd_ctx* c, ssgd_status st, const std::string& msg) {
+    if (c) c->err = msg; else g_err = msg;
+    return st;
+}
+
+#define HIP_OK(c, call)                                                                      \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fail((c), e_ == hipErrorOutOfMemory ? SSGD_ENOMEM : SSGD_EDEVICE,          \
+                        std::string(#call) + ": " + hipGetErrorString(e_));                  \
+    } while (0)
+
+__global__ void init_workers_kernel(WorkerState ws, Dist dist, uint64_t seed, int P, int R, int K, int variant,
+                                    int table_ord) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < R) {
+        ws.clock[q] = 0.0; ws.curK[q] = K; ws.win_prev[q] = 0.0; ws.win_index[q] = 0; ws.F0[q] = -1.0;
+        ws.int_start[q] = 0; ws.crossed[q] = 0; ws.n_done[q] = 0;
+    }
+    if (q >= R * P) return;
+    const int rep = q / P, w = q % P;
+    ws.tau[q] = 0; ws.ord[q] = 0;
+    // all workers are launched afresh at time 0 (as in the proof of Lemma 4)
+    ws.finish[q] = (variant >= kAsync) ? (double)delay(dist, seed, kDelay, 0, rep, P, table_ord, w, 0, 0) : 0.0;
+}
+
+__global__ void debug_delay_kernel(Dist dist, const uint32_t* bits, int64_t n, float* out) {
+    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < n) out[q] = delay_from_bits(dist, bits[q]);
+}
+
+__global__ void debug_batch_kernel(uint64_t seed, uint32_t replica, uint32_t worker, uint32_t ordinal,
+                                   uint32_t version, int m, uint32_t N, uint32_t* out) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < m) out[s] = batch_index(seed, replica, worker, ordinal, version, (uint32_t)s, N);
+}
+
+bool dist_ok(const ssgd_delay_dist* d) {
+    if (!d) return false;
+    switch (d->kind) {
+    case SSGD_EXP: return d->rate > 0;
+    case SSGD_SHIFTED_EXP: return d->rate > 0 && d->shift >= 0;
+    case SSGD_PARETO: return d->alpha > 0 && d->scale > 0;
+    case SSGD_TABLE: return d->table != nullptr && d->table_len > 0;
+    default: return false;
+    }
+}
+
+// Host description -> device description; TABLE delays are copied into `table`.
+hipError_t make_dist(const ssgd_delay_dist* d, DevBuf* table, Dist* out) {
+    out->kind = d->kind;
+    out->shift = (float)d->shift; out->rate = (float)d->rate;
+    out->alpha = (float)d->alpha; out->scale = (float)d->scale;
+    out->table = nullptr; out->table_len = 0;
+    if (d->kind == SSGD_TABLE) {
+        hipError_t e = table->alloc(sizeof(float) * (size_t)d->table_len);
+        if (e != hipSuccess) return e;
+        e = hipMemcpy(table->p, d->table, sizeof(float) * (size_t)d->table_len, hipMemcpyHostToDevice);
+        if (e != hipSuccess) return e;
+        out->table = table->as<float>();
+        out->table_len = d->table_len;
+    }
+    return hipSuccess;
+}
+
+ssgd_status grow_trace(ssgd_ctx* c, int64_t need) {
+    if (need <= c->tr.cap) return SSGD_OK;
+    int64_t cap = std::max<int64_t>(need, std::max<int64_t>(256, 2 * c->tr.cap));
+    const int64_t R = c->R, W = c->Kcap, old = c->tr.cap, used = c->j;
+    DevBuf nt, nl, nk, ns, na, no;
+    HIP_OK(c, nt.alloc(sizeof(double) * R * cap));
+    HIP_OK(c, nl.alloc(sizeof(float) * R * cap));
+    HIP_OK(c, nk.alloc(sizeof(int32_t) * R * cap));
+    HIP_OK(c, ns.alloc(sizeof(int32_t) * R * cap * W));
+    HIP_OK(c, na.alloc(sizeof(int32_t) * R * cap * W));
+    HIP_OK(c, no.alloc(sizeof(int32_t) * R * cap * W));
+    if (used > 0) {
+        HIP_OK(c, hipStreamSynchronize(c->stream));
+        for (int64_t r = 0; r < R; ++r) {
+            HIP_OK(c, hipMemcpy(nt.as<double>() + r * cap, c->tr.t + r * old, sizeof(double) * used, hipMemcpyDeviceToDevice));
+            HIP_OK(c, hipMemcpy(nl.as<float>() + r * cap, c->tr.loss + r * old, sizeof(float) * used, hipMemcpyDeviceToDevice));
+            HIP_OK(c, hipMemcpy(nk.as<int32_t>() + r * cap, c->tr.K + r * old, sizeof(int32_t) * used, hipMemcpyDeviceToDevice));
+            HIP_OK(c, hipMemcpy(ns.as<int32_t>() + r * cap * W, c->tr.sel + r * old * W, sizeof(int32_t) * used * W, hipMemcpyDeviceToDevice));
+            HIP_OK(c, hipMemcpy(na.as<int32_t>() + r * cap * W, c->tr.tau + r * old * W, sizeof(int32_t) * used * W, hipMemcpyDeviceToDevice));
+            HIP_OK(c, hipMemcpy(no.as<int32_t>() + r * cap * W, c->tr.ord + r * old * W, sizeof(int32_t) * used * W, hipMemcpyDeviceToDevice));
+        }
+    }
+    c->tr_t.release(); c->tr_loss.release(); c->tr_K.release(); c->tr_sel.release(); c->tr_tau.release(); c->tr_ord.release();
+    c->tr_t = nt; c->tr_loss = nl; c->tr_K = nk; c->tr_sel = ns; c->tr_tau = na; c->tr_ord = no;
+    c->tr.t = nt.as<double>(); c->tr.loss = nl.as<float>(); c->tr.K = nk.as<int32_t>();
+    c->tr.sel = ns.as<int32_t>(); c->tr.tau = na.as<int32_t>(); c->tr.ord = no.as<int32_t>();
+    c->tr.cap = cap;
+    return SSGD_OK;
+}
+
+int chunks_for(int n_rec, int mp) {
+    if (mp <= 64) { const int rpc = 64 / mp; return (n_rec + rpc - 1) / rpc; }
+    return n_rec * ((mp + 63) / 64);
+}
+
+ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out,
+                               std::vector<std::pair<hipEvent_t, hipEvent_t>>* events) {
+    const int per_launch = std::max(1, c->resident_groups / c->G);
+    for (int r0 = 0; r0 < c->R; r0 += per_launch) {
+        LinArgs a{};
+        a.kind = c->model.kind; a.d = c->model.d; a.C = (c->model.kind == SSGD_LSQ) ? 1 : c->model.classes;
+        a.m = c->m; a.mp = c->mp; a.P = c->P; a.variant = c->variant;
+        a.X = c->model.X; a.y = c->model.y; a.N = (uint32_t)c->model.N;
+        a.lr = (float)c->lr; a.seed = c->seed;
+        a.G = c->G; a.S = c->S;
+        a.replica0 = r0; a.replicas = std::min(per_launch, c->R - r0);
+        a.tr = c->tr;
+        a.v0 = v0; a.nsteps = n;
+        a.params = c->params.as<float>(); a.park = c->park.as<float>(); a.park_small = c->park_small.as<float>();
+        a.zpart = c->zpart.as<float>(); a.maxrows = c->maxrows;
+        a.arrive = c->arrive.as<unsigned long long>(); a.arrive_base = (unsigned long long)v0;
+        a.abort_flag = c->abort_flag.as<int32_t>();
+        a.spin_limit = 4000000u;
+        if (const char* e = getenv("SSGD_SPIN_LIMIT")) a.spin_limit = (uint32_t)strtoul(e, nullptr, 10);
+        a.agg_out = agg_out;
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (events) {
+            HIP_OK(c, hipEventCreate(&e0)); HIP_OK(c, hipEventCreate(&e1));
+            HIP_OK(c, hipEventRecord(e0, c->stream));
+        }
+        HIP_OK(c, launch_linear(a, c->nbw, c->stream));
+        if (events) { HIP_OK(c, hipEventRecord(e1, c->stream)); events->push_back({e0, e1}); }
+    }
+    return SSGD_OK;
+}
+
+ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
+    if (c->broken) return fail(c, SSGD_ESTATE, "context is unusable after a device error");
+    if (J < 0) return fail(c, SSGD_EINVAL, "J must be >= 0");
+    HIP_OK(c, hipSetDevice(c->device));
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+    c->last_ms = 0; c->last_launches = 0;
+    int64_t remaining = J;
+    while (remaining > 0) {
+        int64_t seg = remaining;
+        if (c->ada.mode == 1) seg = std::min<int64_t>(seg, c->ada.window - c->win_cnt);
+        if (c->model.kind == SSGD_MLP2) seg = std::min<int64_t>(seg, 4096);
+        ssgd_status st = grow_trace(c, c->j + seg);
+        if (st != SSGD_OK) return st;
+
+        SchedArgs sa{};
+        sa.tr = c->tr; sa.ws = c->ws; sa.dist = c->dist; sa.seed = c->seed; sa.P = c->P; sa.variant = c->variant;
+        sa.table_ord = c->table_ord; sa.replica0 = 0; sa.j0 = c->j; sa.count = seg;
+        sa.interval_t = (c->ada.mode >= 2) ? c->ada.interval_t : 0.0;
+        launch_schedule(sa, c->R, c->stream);
+        HIP_OK(c, hipGetLastError());
+        if (c->ada.mode >= 2) {
+            int64_t nd = 0;
+            HIP_OK(c, hipMemcpyAsync(&nd, c->ws.n_done, sizeof(nd), hipMemcpyDeviceToHost, c->stream));
+            HIP_OK(c, hipStreamSynchronize(c->stream));
+            seg = nd;
+        }
+        if (c->model.kind == SSGD_MLP2) {
+            std::string msg;
+            hipError_t e = mlp_run_segment(c->mlp, c->tr, c->ws, c->j, seg, agg_out, c->stream, &c->last_ms, &c->last_launches, &msg);
+            if (e != hipSuccess) { c->broken = true; return fail(c, SSGD_EDEVICE, "mlp segment: " + msg); }
+        } else {
+            st = run_segment_linear(c, c->j, seg, agg_out, &events);
+            if (st != SSGD_OK) { c->broken = true; return st; }
+        }
+        c->j += seg;
+        remaining -= seg;
+        if (c->ada.mode != 0) {
+            AdaArgs aa{};
+            aa.tr = c->tr; aa.ws = c->ws; aa.mode = c->ada.mode; aa.K0 = c->ada.K0; aa.Kmax = c->ada.Kmax;
+            aa.window = c->ada.window; aa.P = c->P; aa.rel_tol = c->ada.rel_tol; aa.j_end = c->j;
+            aa.window_closed = 0;
+            if (c->ada.mode == 1) {
+                c->win_cnt += (int32_t)seg;
+                if (c->win_cnt == c->ada.window) { aa.window_closed = 1; c->win_cnt = 0; }
+            }
+            launch_adasync(aa, c->R, c->stream);
+            HIP_OK(c, hipGetLastError());
+        }
+    }
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    for (auto& ev : events) {
+        float ms = 0;
+        if (hipEventElapsedTime(&ms, ev.first, ev.second) == hipSuccess) { c->last_ms += ms; c->last_launches += 1; }
+        (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second);
+    }
+    int32_t aborted = 0;
+    HIP_OK(c, hipMemcpy(&aborted, c->abort_flag.p, sizeof(aborted), hipMemcpyDeviceToHost));
+    if (aborted) {
+        c->broken = true;
+        return fail(c, SSGD_EDEVICE, "cluster exchange timed out: the workgroups of a replica were not co-resident");
+    }
+    return SSGD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m, int32_t variant,
+                        const ssgd_delay_dist* dist, double lr, uint64_t seed, int32_t replicas,
+                        const ssgd_adasync* adasync, void* hip_stream, ssgd_ctx** out) {
+    if (!model || !out) return fail(nullptr, SSGD_EINVAL, "model and out must not be null");
+    if (!dist_ok(dist)) return fail(nullptr, SSGD_EINVAL, "invalid delay distribution");
+    if (!model->X || !model->y || model->N < 1 || model->N >= (1ll << 32) || model->d < 1)
+        return fail(nullptr, SSGD_EINVAL, "invalid data set description");
+    if (variant < SSGD_K_SYNC || variant > SSGD_K_BATCH_ASYNC) return fail(nullptr, SSGD_EINVAL, "unknown variant");
+    if (variant == SSGD_K_BATCH_ASYNC) return fail(nullptr, SSGD_EINVAL, "K-batch-async is not built yet");
+    if (P < 1 || P > kMaxWorkers || K < 1 || m < 1 || m > 65535 || replicas < 1 || !(lr >= 0))
+        return fail(nullptr, SSGD_EINVAL, "P, K, m, replicas or lr out of range");
+    ssgd_adasync ada{};
+    ada.mode = 0; ada.K0 = K; ada.Kmax = K; ada.window = 0;
+    if (adasync && adasync->mode != 0) {
+        ada = *adasync;
+        if (ada.mode < 1 || ada.mode > 3 || ada.Kmax < K || ada.K0 < 1) return fail(nullptr, SSGD_EINVAL, "invalid adasync block");
+        if (ada.mode == 1 && ada.window < 1) return fail(nullptr, SSGD_EINVAL, "adasync window must be >= 1");
+        if (ada.mode >= 2 && (!(ada.interval_t > 0) || replicas != 1)) return fail(nullptr, SSGD_EINVAL, "adasync modes 2, 3 need interval_t > 0 and replicas == 1");
+        if (ada.mode == 3 && ada.K0 >= P) return fail(nullptr, SSGD_EINVAL, "adasync mode 3 needs K0 < P");
+    }
+    const int32_t Kcap = ada.Kmax;
+    if ((variant == SSGD_K_SYNC || variant == SSGD_K_ASYNC) && Kcap > P) return fail(nullptr, SSGD_EINVAL, "K must not exceed P");
+    if (Kcap > kMaxWorkers) return fail(nullptr, SSGD_EINVAL, "K must not exceed 256");
+    if (model->kind == SSGD_LSQ) {
+        if (model->bf16) return fail(nullptr, SSGD_EINVAL, "bf16 is for the MLP only");
+    } else if (model->kind == SSGD_SOFTMAX) {
+        if (model->classes < 2 || model->classes > kClassPad || model->bf16) return fail(nullptr, SSGD_EINVAL, "softmax needs 2..16 classes, bf16 = 0");
+    } else if (model->kind == SSGD_MLP2) {
+        if (model->classes < 2 || model->classes > kClassPad || model->hidden < 64 || model->hidden % 64 || model->d % 32 || replicas != 1)
+            return fail(nullptr, SSGD_EINVAL, "MLP needs 2..16 classes, hidden % 64 == 0, d % 32 == 0, replicas == 1");
+        if (variant != SSGD_K_ASYNC && variant != SSGD_K_SYNC) return fail(nullptr, SSGD_EINVAL, "MLP supports K-sync and K-async");
+    } else {
+        return fail(nullptr, SSGD_EINVAL, "unknown model kind");
+    }
+
+    ssgd_ctx* c = new (std::nothrow) ssgd_ctx();
+    if (!c) return fail(nullptr, SSGD_ENOMEM, "host allocation failed");
+    auto bail = [&](ssgd_status st, const std::string& msg) { ssgd_destroy(c); return fail(nullptr, st, msg); };
+#define HIP_C(call)                                                                                     \
+    do {                                                                                                \
+        hipError_t e_ = (call);                                                                         \
+        if (e_ != hipSuccess)                                                                           \
+            return bail(e_ == hipErrorOutOfMemory ? SSGD_ENOMEM : SSGD_EDEVICE, std::string(#call) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+    c->model = *model; c->P = P; c->K0 = K; c->m = m; c->mp = (m + 3) / 4 * 4; c->variant = variant; c->R = replicas;
+    c->ada = ada; c->lr = lr; c->seed = seed; c->stream = (hipStream_t)hip_stream; c->Kcap = Kcap;
+    c->table_ord = (variant == SSGD_K_BATCH_SYNC || variant == SSGD_K_BATCH_ASYNC) ? Kcap + 1 : 1;
+    HIP_C(hipGetDevice(&c->device));
+    HIP_C(make_dist(dist, &c->table, &c->dist));
+    const int64_t R = replicas;
+    if (model->kind == SSGD_LSQ) c->nw = model->d;
+    else if (model->kind == SSGD_SOFTMAX) c->nw = (int64_t)model->classes * model->d + model->classes;
+    else c->nw = (int64_t)model->hidden * model->d + model->hidden + (int64_t)model->classes * model->hidden + model->classes;
+
+    HIP_C(c->ws_finish.alloc(sizeof(double) * R * P)); HIP_C(c->ws_tau.alloc(sizeof(int32_t) * R * P));
+    HIP_C(c->ws_ord.alloc(sizeof(int32_t) * R * P)); HIP_C(c->ws_clock.alloc(sizeof(double) * R));
+    HIP_C(c->ws_curK.alloc(sizeof(int32_t) * R)); HIP_C(c->ws_winprev.alloc(sizeof(double) * R));
+    HIP_C(c->ws_winidx.alloc(sizeof(int64_t) * R)); HIP_C(c->ws_F0.alloc(sizeof(double) * R));
+    HIP_C(c->ws_intstart.alloc(sizeof(int64_t) * R)); HIP_C(c->ws_crossed.alloc(sizeof(int32_t) * R));
+    HIP_C(c->ws_ndone.alloc(sizeof(int64_t) * R));
+    c->ws.finish = c->ws_finish.as<double>(); c->ws.tau = c->ws_tau.as<int32_t>(); c->ws.ord = c->ws_ord.as<int32_t>();
+    c->ws.clock = c->ws_clock.as<double>(); c->ws.curK = c->ws_curK.as<int32_t>(); c->ws.win_prev = c->ws_winprev.as<double>();
+    c->ws.win_index = c->ws_winidx.as<int64_t>(); c->ws.F0 = c->ws_F0.as<double>(); c->ws.int_start = c->ws_intstart.as<int64_t>();
+    c->ws.crossed = c->ws_crossed.as<int32_t>(); c->ws.n_done = c->ws_ndone.as<int64_t>();
+    {
+        const int n = (int)std::max<int64_t>(R * P, R);
+        hipLaunchKernelGGL(init_workers_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->ws, c->dist, seed, P,
+                           (int)R, K, variant, c->table_ord);
+        HIP_C(hipGetLastError());
+    }
+    c->tr.Kcap = Kcap; c->tr.cap = 0;
+    HIP_C(c->abort_flag.alloc(sizeof(int32_t)));
+    HIP_C(hipMemsetAsync(c->abort_flag.p, 0, sizeof(int32_t), c->stream));
+
+    if (model->kind == SSGD_MLP2) {
+        std::string msg;
+        hipError_t e = mlp_create(&c->mlp, *model, P, m, variant, Kcap, lr, seed, c->stream, &msg);
+        if (e != hipSuccess) return bail(e == hipErrorOutOfMemory ? SSGD_ENOMEM : SSGD_EDEVICE, "mlp_create: " + msg);
+    } else {
+        const int d = model->d;
+        c->nbw = d <= 64 ? 1 : (d <= 128 ? 2 : 4);
+        if (const char* e = getenv("SSGD_NBW")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->nbw = v; }
+        const int SL = 64 * c->nbw;
+        c->G = (d + SL - 1) / SL;
+        const bool async = variant == SSGD_K_ASYNC;
+        c->S = async ? P : Kcap;
+        const int C = model->kind == SSGD_LSQ ? 1 : model->classes;
+        c->maxrows = 64 * chunks_for(async ? std::max(P, Kcap) : Kcap, c->mp);
+        c->lds_bytes = linear_lds_bytes(c->nbw, C, c->S);
+        if (c->lds_bytes > 160 * 1024) return bail(SSGD_EINVAL, "too many gradient slots for the LDS of one workgroup");
+        c->resident_groups = linear_max_resident_groups(c->nbw, c->lds_bytes);
+        if (c->resident_groups < c->G) return bail(SSGD_EINVAL, "d is too large for a co-resident cluster of workgroups");
+        HIP_C(c->params.alloc(sizeof(float) * R * c->nw));
+        HIP_C(hipMemsetAsync(c->params.p, 0, sizeof(float) * R * c->nw, c->stream));
+        const size_t park_n = (size_t)R * c->G * c->S * 16 * SL;
+        HIP_C(c->park.alloc(sizeof(float) * park_n));
+        HIP_C(hipMemsetAsync(c->park.p, 0, sizeof(float) * park_n, c->stream));
+        HIP_C(c->park_small.alloc(sizeof(float) * R * c->G * c->S * 17));
+        HIP_C(hipMemsetAsync(c->park_small.p, 0, sizeof(float) * R * c->G * c->S * 17, c->stream));
+        HIP_C(c->zpart.alloc(sizeof(float) * R * 2 * c->G * c->maxrows * 16));
+        HIP_C(c->arrive.alloc(sizeof(unsigned long long) * R));
+        HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned long long) * R, c->stream));
+    }
+    HIP_C(hipStreamSynchronize(c->stream));
+#undef HIP_C
+    *out = c;
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_run(ssgd_ctx* ctx, int64_t J) {
+    if (!ctx) return fail(nullptr, SSGD_EINVAL, "null context");
+    return run_updates(ctx, J, nullptr);
+}
+
+ssgd_status ssgd_reserve_trace(ssgd_ctx* ctx, int64_t updates) {
+    if (!ctx) return fail(nullptr, SSGD_EINVAL, "null context");
+    if (updates < 0) return fail(ctx, SSGD_EINVAL, "updates must be >= 0");
+    HIP_OK(ctx, hipSetDevice(ctx->device));
+    return grow_trace(ctx, ctx->j + updates);
+}
+
+ssgd_status ssgd_step(ssgd_ctx* ctx, float* agg_grad_out) {
+    if (!ctx) return fail(nullptr, SSGD_EINVAL, "null context");
+    return run_updates(ctx, 1, agg_grad_out);
+}
+
+int64_t ssgd_param_count(const ssgd_ctx* ctx) { return ctx ? ctx->nw : -1; }
+int64_t ssgd_updates_done(const ssgd_ctx* ctx) { return ctx ? ctx->j : -1; }
+int32_t ssgd_trace_width(const ssgd_ctx* ctx) { return ctx ? ctx->Kcap : -1; }
+
+int32_t ssgd_current_K(const ssgd_ctx* ctx, int32_t replica) {
+    if (!ctx || replica < 0 || replica >= ctx->R) return -1;
+    int32_t K = -1;
+    if (hipSetDevice(ctx->device) != hipSuccess) return -1;
+    if (hipMemcpy(&K, ctx->ws.curK + replica, sizeof(K), hipMemcpyDeviceToHost) != hipSuccess) return -1;
+    return K;
+}
+
+ssgd_status ssgd_get_trace(ssgd_ctx* c, int32_t replica, int64_t from, int64_t n, double* t, float* loss,
+                           int32_t* K, int32_t* sel, int32_t* staleness, int32_t* ordinal) {
+    if (!c) return fail(nullptr, SSGD_EINVAL, "null context");
+    if (replica < 0 || replica >= c->R || from < 0 || n < 0 || from + n > c->j) return fail(c, SSGD_EINVAL, "trace range out of bounds");
+    if (n == 0) return SSGD_OK;
+    HIP_OK(c, hipSetDevice(c->device));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    const int64_t cap = c->tr.cap, W = c->Kcap, base = (int64_t)replica * cap + from;
+    if (t) HIP_OK(c, hipMemcpy(t, c->tr.t + base, sizeof(double) * n, hipMemcpyDeviceToHost));
+    if (loss) HIP_OK(c, hipMemcpy(loss, c->tr.loss + base, sizeof(float) * n, hipMemcpyDeviceToHost));
+    if (K) HIP_OK(c, hipMemcpy(K, c->tr.K + base, sizeof(int32_t) * n, hipMemcpyDeviceToHost));
+    if (sel) HIP_OK(c, hipMemcpy(sel, c->tr.sel + base * W, sizeof(int32_t) * n * W, hipMemcpyDeviceToHost));
+    if (ordinal) HIP_OK(c, hipMemcpy(ordinal, c->tr.ord + base * W, sizeof(int32_t) * n * W, hipMemcpyDeviceToHost));
+    if (staleness) {
+        HIP_OK(c, hipMemcpy(staleness, c->tr.tau + base * W, sizeof(int32_t) * n * W, hipMemcpyDeviceToHost));
+        for (int64_t q = 0; q < n; ++q)
+            for (int64_t l = 0; l < W; ++l) {
+                int32_t& v = staleness[q * W + l];
+                if (v >= 0) v = (int32_t)(from + q) - v;   // j - tau
+            }
+    }
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_get_params(ssgd_ctx* c, int32_t replica, float* w_out) {
+    if (!c || !w_out) return fail(c, SSGD_EINVAL, "null argument");
+    if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
+    HIP_OK(c, hipSetDevice(c->device));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    const float* src = c->model.kind == SSGD_MLP2 ? mlp_params(c->mlp) : c->params.as<float>() + (int64_t)replica * c->nw;
+    HIP_OK(c, hipMemcpy(w_out, src, sizeof(float) * c->nw, hipMemcpyDeviceToHost));
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_set_params(ssgd_ctx* c, int32_t replica, const float* w_in) {
+    if (!c || !w_in) return fail(c, SSGD_EINVAL, "null argument");
+    if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
+    HIP_OK(c, hipSetDevice(c->device));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    float* dst = c->model.kind == SSGD_MLP2 ? mlp_params(c->mlp) : c->params.as<float>() + (int64_t)replica * c->nw;
+    HIP_OK(c, hipMemcpy(dst, w_in, sizeof(float) * c->nw, hipMemcpyHostToDevice));
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_force_K(ssgd_ctx* c, int32_t K) {
+    if (!c) return fail(nullptr, SSGD_EINVAL, "null context");
+    if (K < 1 || K > c->Kcap) return fail(c, SSGD_EINVAL, "K out of range");
+    HIP_OK(c, hipSetDevice(c->device));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    std::vector<int32_t> ks(c->R, K);
+    HIP_OK(c, hipMemcpy(c->ws.curK, ks.data(), sizeof(int32_t) * c->R, hipMemcpyHostToDevice));
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_debug_delays(const ssgd_delay_dist* dist, const uint32_t* bits, int64_t n, float* out) {
+    if (!dist_ok(dist) || dist->kind == SSGD_TABLE || !bits || !out || n < 0) return fail(nullptr, SSGD_EINVAL, "invalid argument");
+    if (n == 0) return SSGD_OK;
+    DevBuf b, o, tbl;
+    Dist dd;
+    ssgd_ctx* c = nullptr;
+    HIP_OK(c, make_dist(dist, &tbl, &dd));
+    HIP_OK(c, b.alloc(sizeof(uint32_t) * n));
+    HIP_OK(c, o.alloc(sizeof(float) * n));
+    HIP_OK(c, hipMemcpy(b.p, bits, sizeof(uint32_t) * n, hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(debug_delay_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, nullptr, dd, b.as<uint32_t>(), n, o.as<float>());
+    HIP_OK(c, hipGetLastError());
+    HIP_OK(c, hipMemcpy(out, o.p, sizeof(float) * n, hipMemcpyDeviceToHost));
+    b.release(); o.release(); tbl.release();
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_debug_batch(uint64_t seed, uint32_t replica, uint32_t worker, uint32_t ordinal, uint32_t version,
+                             int32_t m, int64_t N, uint32_t* out) {
+    if (!out || m < 1 || N < 1 || N >= (1ll << 32)) return fail(nullptr, SSGD_EINVAL, "invalid argument");
+    DevBuf o;
+    ssgd_ctx* c = nullptr;
+    HIP_OK(c, o.alloc(sizeof(uint32_t) * m));
+    hipLaunchKernelGGL(debug_batch_kernel, dim3((m + 255) / 256), dim3(256), 0, nullptr, seed, replica, worker, ordinal, version, m, (uint32_t)N, o.as<uint32_t>());
+    HIP_OK(c, hipGetLastError());
+    HIP_OK(c, hipMemcpy(out, o.p, sizeof(uint32_t) * m, hipMemcpyDeviceToHost));
+    o.release();
+    return SSGD_OK;
+}
+
+const char* ssgd_last_error(const ssgd_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+ssgd_status ssgd_last_kernel_ms(const ssgd_ctx* ctx, double* avg_ms, int64_t* launches) {
+    if (!ctx) return SSGD_EINVAL;
+    if (avg_ms) *avg_ms = ctx->last_launches ? ctx->last_ms / (double)ctx->last_launches : 0.0;
+    if (launches) *launches = ctx->last_launches;
+    return SSGD_OK;
+}
+
+void ssgd_destroy(ssgd_ctx* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    if (c->stream || true) (void)hipStreamSynchronize(c->stream);
+    if (c->mlp) mlp_destroy(c->mlp);
+    DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,
+                      &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx, &c->ws_F0,
+                      &c->ws_intstart, &c->ws_crossed, &c->ws_ndone, &c->params, &c->park, &c->park_small, &c->zpart,
+                      &c->arrive, &c->abort_flag};
+    for (DevBuf* b : bufs) b->release();
+    delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,22 @@
+// Two-layer ReLU network (bf16 MFMA contractions, fp32 accumulation): host entry points.
+#pragma once
+#include <string>
+
+#include "../../include/ssgd.h"
+#include "common.hpp"
+
+namespace ssgd {
+
+struct MlpState;
+
+hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int variant, int Kcap, double lr,
+                      uint64_t seed, hipStream_t stream, std::string* msg);
+// Runs updates [v0, v0+n) whose schedule is already in the trace.
+hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n, float* agg_out,
+                           hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg);
+float* mlp_params(MlpState* s);
+void mlp_destroy(MlpState* s);
+
+void set_global_error(const std::string& msg);
+
+}  // namespace ssgd
