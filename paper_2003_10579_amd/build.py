@@ -11,6 +11,8 @@ SOURCES = ["api.hip", "schedule.hip", "linear.hip", "mlp.hip", "mc.hip"]
 HEADERS = ["common.hpp", "rng.hpp", "mlp.hpp", os.path.join("..", "..", "include", "ssgd.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# event-process arithmetic (clock sums, AdaSync rule) must round like plain IEEE operations
+NO_CONTRACT = {"schedule.hip": ["-ffp-contract=off"], "mc.hip": ["-ffp-contract=off"], "api.hip": ["-ffp-contract=off"]}
 
 
 def hipcc() -> str:
@@ -39,7 +41,8 @@ def build(force: bool = True, jobs: int = 5) -> str:
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objs.append(obj)
-        procs.append((src, subprocess.Popen([hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])))
+        extra = NO_CONTRACT.get(src, [])
+        procs.append((src, subprocess.Popen([hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])))
         if len(procs) >= jobs:
             name, p = procs.pop(0)
             if p.wait() != 0:

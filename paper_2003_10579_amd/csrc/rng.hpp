@@ -4,8 +4,10 @@
 // Every draw is a pure function of (seed, stream, aux, replica, worker, ordinal,
 // version) through Philox4x32-10 (Salmon et al., SC'11), so kernels may evaluate
 // them in any order.  The delay is an fp32 value defined by a fixed sequence of
-// correctly rounded single-precision operations (__f*_rn never fuse), which makes
-// it reproducible bit for bit by any IEEE-754 implementation.
+// correctly rounded single-precision operations, which makes it reproducible bit for
+// bit by any IEEE-754 implementation; every function that takes part switches
+// floating-point contraction off, because the compiler would otherwise fuse the
+// multiply-add pairs (the __fmul_rn / __fadd_rn wrappers do not prevent that).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -48,53 +50,67 @@ __device__ __forceinline__ u32x4 draw(uint64_t seed, uint32_t stream, uint32_t a
 
 // (top 23 bits + 1/2) / 2^23: strictly inside (0, 1), all steps exact.
 __device__ __forceinline__ float uniform_open(uint32_t bits) {
-    return __fmul_rn(__fadd_rn((float)(bits >> 9), 0.5f), 0x1p-23f);
+#pragma clang fp contract(off)
+    const float h = (float)(bits >> 9) + 0.5f;
+    return h * 0x1p-23f;
 }
 
 // -ln(u), u a normal float in (0,1): ln m = 2 atanh((m-1)/(m+1)) on m in (sqrt(1/2), sqrt(2)],
 // odd series to the 9th power, plus e*ln2 with ln2 in a short high and a low part.
 __device__ __forceinline__ float neg_log(float u) {
+#pragma clang fp contract(off)
     const uint32_t b = __float_as_uint(u);
     int e = (int)(b >> 23) - 127;
     float m = __uint_as_float((b & 0x007FFFFFu) | 0x3F800000u);
-    if (m > 1.41421354f) { m = __fmul_rn(m, 0.5f); e += 1; }
-    const float s = __fdiv_rn(__fadd_rn(m, -1.0f), __fadd_rn(m, 1.0f));
-    const float s2 = __fmul_rn(s, s);
+    if (m > 1.41421354f) { m = m * 0.5f; e += 1; }
+    const float num = m - 1.0f, den = m + 1.0f;
+    const float s = num / den;
+    const float s2 = s * s;
     float p = 0.222222224f;
-    p = __fadd_rn(__fmul_rn(p, s2), 0.285714298f);
-    p = __fadd_rn(__fmul_rn(p, s2), 0.400000006f);
-    p = __fadd_rn(__fmul_rn(p, s2), 0.666666687f);
-    p = __fadd_rn(__fmul_rn(p, s2), 2.0f);
-    const float r = __fmul_rn(p, s);
+    p = p * s2; p = p + 0.285714298f;
+    p = p * s2; p = p + 0.400000006f;
+    p = p * s2; p = p + 0.666666687f;
+    p = p * s2; p = p + 2.0f;
+    const float r = p * s;
     const float ef = (float)e;
-    const float ln = __fadd_rn(__fmul_rn(ef, 0.693359375f), __fadd_rn(r, __fmul_rn(ef, -2.12194440e-4f)));
+    const float hi = ef * 0.693359375f;
+    const float lo = ef * -2.12194440e-4f;
+    const float t = r + lo;
+    const float ln = hi + t;
     return -ln;
 }
 
 // exp(y), y >= 0: y = n ln2 + r, degree-7 Taylor polynomial, scale through the exponent field.
 __device__ __forceinline__ float exp_nonneg(float y) {
-    const float th = __fadd_rn(__fmul_rn(y, 1.44269502f), 0.5f);
+#pragma clang fp contract(off)
+    const float t = y * 1.44269502f;
+    const float th = t + 0.5f;
     if (!(th < 128.0f)) return __uint_as_float(0x7F800000u);
     const int n = (int)th;
     const float nf = (float)n;
-    float r = __fadd_rn(y, -__fmul_rn(nf, 0.693359375f));
-    r = __fadd_rn(r, -__fmul_rn(nf, -2.12194440e-4f));
+    const float a = nf * 0.693359375f;
+    float r = y - a;
+    const float c = nf * -2.12194440e-4f;
+    r = r - c;
     float p = 1.98412701e-4f;
-    p = __fadd_rn(__fmul_rn(p, r), 1.38888892e-3f);
-    p = __fadd_rn(__fmul_rn(p, r), 8.33333377e-3f);
-    p = __fadd_rn(__fmul_rn(p, r), 4.16666679e-2f);
-    p = __fadd_rn(__fmul_rn(p, r), 0.166666672f);
-    p = __fadd_rn(__fmul_rn(p, r), 0.5f);
-    p = __fadd_rn(__fmul_rn(p, r), 1.0f);
-    p = __fadd_rn(__fmul_rn(p, r), 1.0f);
-    return __fmul_rn(p, __uint_as_float((uint32_t)(n + 127) << 23));
+    p = p * r; p = p + 1.38888892e-3f;
+    p = p * r; p = p + 8.33333377e-3f;
+    p = p * r; p = p + 4.16666679e-2f;
+    p = p * r; p = p + 0.166666672f;
+    p = p * r; p = p + 0.5f;
+    p = p * r; p = p + 1.0f;
+    p = p * r; p = p + 1.0f;
+    return p * __uint_as_float((uint32_t)(n + 127) << 23);
 }
 
 __device__ __forceinline__ float delay_from_bits(const Dist& d, uint32_t bits) {
+#pragma clang fp contract(off)
     const float E = neg_log(uniform_open(bits));
-    if (d.kind == 0) return __fdiv_rn(E, d.rate);
-    if (d.kind == 1) return __fadd_rn(d.shift, __fdiv_rn(E, d.rate));
-    return __fmul_rn(d.scale, exp_nonneg(__fdiv_rn(E, d.alpha)));
+    if (d.kind == 0) return E / d.rate;
+    if (d.kind == 1) { const float q = E / d.rate; return d.shift + q; }
+    const float q = E / d.alpha;
+    const float x = exp_nonneg(q);
+    return d.scale * x;
 }
 
 // Delay of the ordinal-th mini-batch that `worker` starts after reading `version`.

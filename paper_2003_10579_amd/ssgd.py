@@ -49,12 +49,24 @@ class AdaSync(C.Structure):
 _lib = None
 
 
+def _preload_hip_runtime():
+    """PyTorch ships its own HIP runtime; the library must bind to that copy (one runtime per
+    process), so it is loaded first, by path, whether or not torch has been imported yet."""
+    import importlib.util
+    spec = importlib.util.find_spec("torch")
+    if spec is not None and spec.origin:
+        cand = os.path.join(os.path.dirname(spec.origin), "lib", "libamdhip64.so")
+        if os.path.exists(cand):
+            C.CDLL(cand, mode=C.RTLD_GLOBAL)
+
+
 def lib():
     """Load the built library; there is no fallback when it is missing."""
     global _lib
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is not built: run `python -m paper_2003_10579_amd.build`")
+        _preload_hip_runtime()
         L = C.CDLL(_LIB_PATH)
         L.ssgd_create.argtypes = [C.POINTER(ModelDesc), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                   C.POINTER(DelayDist), C.c_double, C.c_uint64, C.c_int32, C.POINTER(AdaSync),

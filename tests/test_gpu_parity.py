@@ -114,27 +114,37 @@ def test_schedule_table_ties_and_dead_worker(ssgd, oracle, torch_cuda):
 
 # ------------------------------------------------------------------------------- training parity
 
-def _run_pair(ssgd, oracle, torch, kind, X, y, P, K, m, variant, spec, lr, J, seed=0, classes=1, check_steps=40,
-              replicas=1, replica=0):
+def _run_pair(ssgd, oracle, torch, kind, X, y, P, K, m, variant, spec, lr, J, seed=0, classes=1, check_steps=40):
+    """Per-step averaged gradients (teacher-forced from the oracle's iterate where the variant keeps no
+    in-flight gradients, i.e. the sync variants; free-running otherwise), then a free run of J updates
+    for the trace and the final parameters."""
     gd, od = dist_pair(ssgd, oracle, spec)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
-    ctx = ssgd.Context(kind, Xd, yd, P, K, m, variant, gd, lr, seed=seed, classes=classes, replicas=replicas)
-    tr = oracle.Trainer(oracle.Model(kind, X, y, classes=classes), P, K, m, variant, od, lr, seed=seed, replica=replica)
+    mk_ctx = lambda: ssgd.Context(kind, Xd, yd, P, K, m, variant, gd, lr, seed=seed, classes=classes)
+    mk_orc = lambda: oracle.Trainer(oracle.Model(kind, X, y, classes=classes), P, K, m, variant, od, lr, seed=seed)
+    ctx, tr = mk_ctx(), mk_orc()
     agg = torch.zeros(ctx.nw, dtype=torch.float32, device="cuda")
+    forced = variant in ("k_sync", "k_batch_sync")
     worst = 0.0
     for j in range(min(check_steps, J)):
-        ctx.step(agg if replica == 0 else None)
-        g = tr.step()
-        if replica == 0:
-            worst = max(worst, rel(agg.cpu().numpy(), g))
-    if J > check_steps:
+        if forced:
+            ctx.set_params(tr.params())
+        ctx.step(agg)
+        worst = max(worst, rel(agg.cpu().numpy(), tr.step()))
+    if forced:
+        ctx.close()
+        ctx, tr = mk_ctx(), mk_orc()
+        ctx.run(J)
+        tr.run(J)
+    elif J > check_steps:
         ctx.run(J - check_steps)
         tr.run(J - check_steps)
-    gt, ot = ctx.trace(replica), tr.trace()
+    gt, ot = ctx.trace(), tr.trace()
     assert_trace_equal(gt, ot)
+    pr = rel(ctx.params(), tr.params())
+    print(f"worst per-step gradient error {worst:.3e}, parameter error after {J} updates {pr:.3e}")
     assert worst <= GRAD_TOL, worst
     assert np.allclose(gt["loss"], ot["loss"], rtol=2e-4, atol=1e-6)
-    pr = rel(ctx.params(replica), tr.params())
     assert pr <= PARAM_TOL, pr
     ctx.close()
     return worst, pr
