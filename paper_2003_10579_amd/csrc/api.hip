@@ -51,7 +51,7 @@ struct ssgd_ctx {
     DevBuf tr_t, tr_loss, tr_K, tr_sel, tr_tau, tr_ord;
     WorkerState ws{};
     DevBuf ws_finish, ws_tau, ws_ord, ws_clock, ws_curK, ws_winprev, ws_winidx, ws_F0, ws_intstart, ws_crossed, ws_ndone;
-    DevBuf params, park, park_small, zpart, arrive, abort_flag;
+    DevBuf params, park, park_small, zpart, arrive, abort_flag, xcc_ids, prof;
     int resident_groups = 0;
     size_t lds_bytes = 0;
     MlpState* mlp = nullptr;
@@ -187,6 +187,10 @@ ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_ou
         a.spin_limit = 4000000u;
         if (const char* e = getenv("SSGD_SPIN_LIMIT")) a.spin_limit = (uint32_t)strtoul(e, nullptr, 10);
         a.agg_out = agg_out;
+        a.xcc_ids = c->xcc_ids.as<int32_t>();
+        a.allow_fast = 1;
+        if (const char* e = getenv("SSGD_EXCHANGE")) a.allow_fast = (strcmp(e, "fenced") == 0) ? 0 : 1;
+        a.prof = c->prof.as<unsigned long long>();
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (events) {
             HIP_OK(c, hipEventCreate(&e0)); HIP_OK(c, hipEventCreate(&e1));
@@ -367,6 +371,12 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         HIP_C(c->park_small.alloc(sizeof(float) * R * c->G * c->S * 17));
         HIP_C(hipMemsetAsync(c->park_small.p, 0, sizeof(float) * R * c->G * c->S * 17, c->stream));
         HIP_C(c->zpart.alloc(sizeof(float) * R * 2 * c->G * c->maxrows * 16));
+        HIP_C(c->xcc_ids.alloc(sizeof(int32_t) * R * c->G));
+        HIP_C(hipMemsetAsync(c->xcc_ids.p, 0xFF, sizeof(int32_t) * R * c->G, c->stream));
+        if (getenv("SSGD_PHASE_PROFILE")) {
+            HIP_C(c->prof.alloc(sizeof(unsigned long long) * R * c->G * 8));
+            HIP_C(hipMemsetAsync(c->prof.p, 0, sizeof(unsigned long long) * R * c->G * 8, c->stream));
+        }
         HIP_C(c->arrive.alloc(sizeof(unsigned long long) * R));
         HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned long long) * R, c->stream));
     }
@@ -501,12 +511,23 @@ ssgd_status ssgd_last_kernel_ms(const ssgd_ctx* ctx, double* avg_ms, int64_t* la
 void ssgd_destroy(ssgd_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
-    if (c->stream || true) (void)hipStreamSynchronize(c->stream);
+    (void)hipStreamSynchronize(c->stream);
+    if (c->prof.p) {
+        // diagnostics requested through SSGD_PHASE_PROFILE: mean shader-clock cycles per phase and update
+        std::vector<unsigned long long> h((size_t)c->R * c->G * 8);
+        if (hipMemcpy(h.data(), c->prof.p, h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost) == hipSuccess && c->j > 0) {
+            double tot[8] = {0};
+            for (size_t q = 0; q < h.size(); ++q) tot[q % 8] += (double)h[q];
+            fprintf(stderr, "ssgd phase profile (cycles per update per workgroup):");
+            for (int q = 0; q < 7; ++q) fprintf(stderr, " p%d=%.0f", q, tot[q] / ((double)c->R * c->G * (double)c->j));
+            fprintf(stderr, "\n");
+        }
+    }
     if (c->mlp) mlp_destroy(c->mlp);
     DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,
                       &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx, &c->ws_F0,
                       &c->ws_intstart, &c->ws_crossed, &c->ws_ndone, &c->params, &c->park, &c->park_small, &c->zpart,
-                      &c->arrive, &c->abort_flag};
+                      &c->arrive, &c->abort_flag, &c->xcc_ids, &c->prof};
     for (DevBuf* b : bufs) b->release();
     delete c;
 }

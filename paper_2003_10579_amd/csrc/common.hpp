@@ -86,6 +86,9 @@ struct LinArgs {
     int32_t* abort_flag;
     uint32_t spin_limit;
     float* agg_out;          // nullable: averaged gradient of the last update of replica 0
+    int32_t* xcc_ids;        // [R][G] XCD each workgroup of a cluster runs on (checked on the device)
+    int32_t allow_fast;      // 1: exchange through the shared L2 once a cluster is known to sit on one XCD
+    unsigned long long* prof;   // nullable diagnostics: [R][G][8] shader-clock cycles spent per phase
 };
 int linear_max_resident_groups(int nbw, size_t lds_bytes);
 size_t linear_lds_bytes(int nbw, int C, int S);
