@@ -40,7 +40,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--replicas", type=int, default=int(os.environ.get("SSGD_BENCH_REPLICAS", "40")))
+    ap.add_argument("--replicas", type=int, default=int(os.environ.get("SSGD_BENCH_REPLICAS", "42")))
     ap.add_argument("--updates", type=int, default=5000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()

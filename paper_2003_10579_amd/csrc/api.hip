@@ -169,7 +169,9 @@ int chunks_for(int n_rec, int mp) {
 
 ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out,
                                std::vector<std::pair<hipEvent_t, hipEvent_t>>* events) {
-    const int per_launch = std::max(1, c->resident_groups / c->G);
+    // a cluster stays on one XCD (block ids congruent modulo 8), so the resident slots count per XCD
+    const int per_launch = std::max(1, 8 * ((c->resident_groups / 8) / c->G));
+    HIP_OK(c, hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * 2 * c->R, c->stream));
     for (int r0 = 0; r0 < c->R; r0 += per_launch) {
         LinArgs a{};
         a.kind = c->model.kind; a.d = c->model.d; a.C = (c->model.kind == SSGD_LSQ) ? 1 : c->model.classes;
@@ -182,7 +184,7 @@ ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_ou
         a.v0 = v0; a.nsteps = n;
         a.params = c->params.as<float>(); a.park = c->park.as<float>(); a.park_small = c->park_small.as<float>();
         a.zpart = c->zpart.as<float>(); a.maxrows = c->maxrows;
-        a.arrive = c->arrive.as<unsigned long long>(); a.arrive_base = (unsigned long long)v0;
+        a.arrive = c->arrive.as<unsigned int>();
         a.abort_flag = c->abort_flag.as<int32_t>();
         a.spin_limit = 4000000u;
         if (const char* e = getenv("SSGD_SPIN_LIMIT")) a.spin_limit = (uint32_t)strtoul(e, nullptr, 10);
@@ -374,11 +376,11 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         HIP_C(c->xcc_ids.alloc(sizeof(int32_t) * R * c->G));
         HIP_C(hipMemsetAsync(c->xcc_ids.p, 0xFF, sizeof(int32_t) * R * c->G, c->stream));
         if (getenv("SSGD_PHASE_PROFILE")) {
-            HIP_C(c->prof.alloc(sizeof(unsigned long long) * R * c->G * 8));
-            HIP_C(hipMemsetAsync(c->prof.p, 0, sizeof(unsigned long long) * R * c->G * 8, c->stream));
+            HIP_C(c->prof.alloc(sizeof(unsigned long long) * R * c->G * 20));
+            HIP_C(hipMemsetAsync(c->prof.p, 0, sizeof(unsigned long long) * R * c->G * 20, c->stream));
         }
-        HIP_C(c->arrive.alloc(sizeof(unsigned long long) * R));
-        HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned long long) * R, c->stream));
+        HIP_C(c->arrive.alloc(sizeof(unsigned int) * 2 * R));
+        HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * 2 * R, c->stream));
     }
     HIP_C(hipStreamSynchronize(c->stream));
 #undef HIP_C
@@ -514,12 +516,12 @@ void ssgd_destroy(ssgd_ctx* c) {
     (void)hipStreamSynchronize(c->stream);
     if (c->prof.p) {
         // diagnostics requested through SSGD_PHASE_PROFILE: mean shader-clock cycles per phase and update
-        std::vector<unsigned long long> h((size_t)c->R * c->G * 8);
+        std::vector<unsigned long long> h((size_t)c->R * c->G * 20);
         if (hipMemcpy(h.data(), c->prof.p, h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost) == hipSuccess && c->j > 0) {
-            double tot[8] = {0};
-            for (size_t q = 0; q < h.size(); ++q) tot[q % 8] += (double)h[q];
+            double tot[20] = {0};
+            for (size_t q = 0; q < h.size(); ++q) tot[q % 20] += (double)h[q];
             fprintf(stderr, "ssgd phase profile (cycles per update per workgroup):");
-            for (int q = 0; q < 7; ++q) fprintf(stderr, " p%d=%.0f", q, tot[q] / ((double)c->R * c->G * (double)c->j));
+            for (int q = 0; q < 20; ++q) fprintf(stderr, " p%d=%.0f", q, tot[q] / ((double)c->R * c->G * (double)c->j));
             fprintf(stderr, "\n");
         }
     }

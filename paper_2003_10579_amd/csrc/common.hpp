@@ -81,8 +81,7 @@ struct LinArgs {
     float* park_small;       // [R][G][S][17]: bias gradient (16) and mean loss (1) of every slot
     float* zpart;            // [R][2][G][maxrows][16] partial logits exchanged inside a cluster
     int32_t maxrows;
-    unsigned long long* arrive;   // [R] monotone arrival counters of the cluster barrier
-    unsigned long long arrive_base;
+    unsigned int* arrive;    // [R][2] arrival counters of the cluster exchange, zero at launch
     int32_t* abort_flag;
     uint32_t spin_limit;
     float* agg_out;          // nullable: averaged gradient of the last update of replica 0
