@@ -43,6 +43,8 @@ struct ssgd_ctx {
     int device = 0;
     int64_t nw = 0;
     int32_t Kcap = 0, S = 0, G = 0, nbw = 0, maxrows = 0, table_ord = 1;
+    int tile_resident_groups = 0, cu_count = 0;
+    LinArgs lin{};
     int64_t j = 0;
     int32_t win_cnt = 0;
     bool broken = false;
@@ -167,40 +169,80 @@ int chunks_for(int n_rec, int mp) {
     return n_rec * ((mp + 63) / 64);
 }
 
-ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out,
-                               std::vector<std::pair<hipEvent_t, hipEvent_t>>* events) {
+// One launch per group of co-resident replicas; `tile` selects the single-tile steady-state kernel.
+ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, bool tile,
+                         std::vector<std::pair<hipEvent_t, hipEvent_t>>* events) {
     // a cluster stays on one XCD (block ids congruent modulo 8), so the resident slots count per XCD
-    const int per_launch = std::max(1, 8 * ((c->resident_groups / 8) / c->G));
-    HIP_OK(c, hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * 2 * c->R, c->stream));
+    const int resident = tile ? c->tile_resident_groups : c->resident_groups;
+    const int per_launch = std::max(1, 8 * ((resident / 8) / c->G));
+    HIP_OK(c, hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * c->R, c->stream));
+    if (getenv("SSGD_DEBUG"))
+        fprintf(stderr, "ssgd launch: v0=%lld n=%lld tile=%d resident=%d per_launch=%d R=%d\n", (long long)v0, (long long)n,
+                (int)tile, resident, per_launch, c->R);
     for (int r0 = 0; r0 < c->R; r0 += per_launch) {
-        LinArgs a{};
-        a.kind = c->model.kind; a.d = c->model.d; a.C = (c->model.kind == SSGD_LSQ) ? 1 : c->model.classes;
-        a.m = c->m; a.mp = c->mp; a.P = c->P; a.variant = c->variant;
-        a.X = c->model.X; a.y = c->model.y; a.N = (uint32_t)c->model.N;
-        a.lr = (float)c->lr; a.seed = c->seed;
-        a.G = c->G; a.S = c->S;
+        LinArgs a = c->lin;
         a.replica0 = r0; a.replicas = std::min(per_launch, c->R - r0);
         a.tr = c->tr;
         a.v0 = v0; a.nsteps = n;
-        a.params = c->params.as<float>(); a.park = c->park.as<float>(); a.park_small = c->park_small.as<float>();
-        a.zpart = c->zpart.as<float>(); a.maxrows = c->maxrows;
-        a.arrive = c->arrive.as<unsigned int>();
-        a.abort_flag = c->abort_flag.as<int32_t>();
-        a.spin_limit = 4000000u;
-        if (const char* e = getenv("SSGD_SPIN_LIMIT")) a.spin_limit = (uint32_t)strtoul(e, nullptr, 10);
         a.agg_out = agg_out;
-        a.xcc_ids = c->xcc_ids.as<int32_t>();
-        a.allow_fast = 1;
-        if (const char* e = getenv("SSGD_EXCHANGE")) a.allow_fast = (strcmp(e, "fenced") == 0) ? 0 : 1;
-        a.prof = c->prof.as<unsigned long long>();
+        a.pair_cus = 0; a.pair_layers = 0;
+        if (tile && a.replicas == per_launch && c->cu_count % 8 == 0 && resident % c->cu_count == 0 && !getenv("SSGD_NO_PAIRING")) {
+            a.pair_cus = c->cu_count / 8;
+            a.pair_layers = resident / c->cu_count;
+            // the dealt-out layout must hold as many clusters per XCD as the consecutive one
+            const int nb = a.pair_cus / c->G, Lr = a.pair_cus - nb * c->G;
+            if (8 * (nb * a.pair_layers + (Lr * a.pair_layers) / c->G) < a.replicas) { a.pair_cus = 0; a.pair_layers = 0; }
+        }
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (events) {
             HIP_OK(c, hipEventCreate(&e0)); HIP_OK(c, hipEventCreate(&e1));
             HIP_OK(c, hipEventRecord(e0, c->stream));
         }
-        HIP_OK(c, launch_linear(a, c->nbw, c->stream));
+        HIP_OK(c, tile ? launch_linear_tile(a, c->stream) : launch_linear(a, c->nbw, c->stream));
         if (events) { HIP_OK(c, hipEventRecord(e1, c->stream)); events->push_back({e0, e1}); }
     }
+    return SSGD_OK;
+}
+
+ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out,
+                               std::vector<std::pair<hipEvent_t, hipEvent_t>>* events) {
+    LinArgs& a = c->lin;
+    a.kind = c->model.kind; a.d = c->model.d; a.C = (c->model.kind == SSGD_LSQ) ? 1 : c->model.classes;
+    a.m = c->m; a.mp = c->mp; a.P = c->P; a.variant = c->variant;
+    a.X = c->model.X; a.y = c->model.y; a.N = (uint32_t)c->model.N;
+    a.lr = (float)c->lr; a.seed = c->seed;
+    a.G = c->G; a.S = c->S;
+    a.tr = c->tr;
+    a.params = c->params.as<float>(); a.park = c->park.as<float>(); a.park_small = c->park_small.as<float>();
+    a.zpart = c->zpart.as<float>(); a.maxrows = c->maxrows;
+    a.arrive = c->arrive.as<unsigned int>();
+    a.abort_flag = c->abort_flag.as<int32_t>();
+    a.spin_limit = 4000000u;
+    if (const char* e = getenv("SSGD_SPIN_LIMIT")) a.spin_limit = (uint32_t)strtoul(e, nullptr, 10);
+    a.xcc_ids = c->xcc_ids.as<int32_t>();
+    a.allow_fast = 1;
+    if (const char* e = getenv("SSGD_EXCHANGE")) a.allow_fast = (strcmp(e, "fenced") == 0) ? 0 : 1;
+    a.prof = c->prof.as<unsigned long long>();
+    a.tune = 0;
+    if (const char* e = getenv("SSGD_TUNE")) a.tune = atoi(e);
+    a.agg_out = agg_out;
+
+    // The steady-state kernel runs the steps whose mini-batches fit one tile; step 0 of K-async
+    // (all P workers start) and every other shape go through the general kernel.
+    bool tile = c->nbw == 4 && c->tile_resident_groups >= c->G;
+    if (const char* e = getenv("SSGD_KERNEL")) tile = tile && strcmp(e, "general") != 0;
+    int64_t head = 0;
+    if (tile) {
+        a.v0 = v0;
+        if (c->variant == SSGD_K_ASYNC && v0 == 0) { head = 1; a.v0 = 1; }
+        tile = linear_tile_supports(a, c->Kcap);
+    }
+    if (!tile) return launch_steps(c, v0, n, agg_out, false, events);
+    if (head > 0) {
+        ssgd_status st = launch_steps(c, v0, std::min(head, n), agg_out, false, events);
+        if (st != SSGD_OK) return st;
+    }
+    if (n > head) return launch_steps(c, v0 + head, n - head, agg_out, true, events);
     return SSGD_OK;
 }
 
@@ -365,6 +407,9 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         if (c->lds_bytes > 160 * 1024) return bail(SSGD_EINVAL, "too many gradient slots for the LDS of one workgroup");
         c->resident_groups = linear_max_resident_groups(c->nbw, c->lds_bytes);
         if (c->resident_groups < c->G) return bail(SSGD_EINVAL, "d is too large for a co-resident cluster of workgroups");
+        { hipDeviceProp_t prop; HIP_C(hipGetDeviceProperties(&prop, c->device)); c->cu_count = prop.multiProcessorCount; }
+        if (c->nbw == 4 && C <= 15 && linear_tile_lds_bytes(C, c->S) <= 160 * 1024)
+            c->tile_resident_groups = linear_tile_resident_groups(linear_tile_lds_bytes(C, c->S));
         HIP_C(c->params.alloc(sizeof(float) * R * c->nw));
         HIP_C(hipMemsetAsync(c->params.p, 0, sizeof(float) * R * c->nw, c->stream));
         const size_t park_n = (size_t)R * c->G * c->S * 16 * SL;
@@ -379,8 +424,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
             HIP_C(c->prof.alloc(sizeof(unsigned long long) * R * c->G * 20));
             HIP_C(hipMemsetAsync(c->prof.p, 0, sizeof(unsigned long long) * R * c->G * 20, c->stream));
         }
-        HIP_C(c->arrive.alloc(sizeof(unsigned int) * 2 * R));
-        HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * 2 * R, c->stream));
+        HIP_C(c->arrive.alloc(sizeof(unsigned int) * kArriveStride * R));
+        HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * R, c->stream));
     }
     HIP_C(hipStreamSynchronize(c->stream));
 #undef HIP_C
@@ -524,6 +569,19 @@ void ssgd_destroy(ssgd_ctx* c) {
             for (int q = 0; q < 20; ++q) fprintf(stderr, " p%d=%.0f", q, tot[q] / ((double)c->R * c->G * (double)c->j));
             fprintf(stderr, "\n");
         }
+    }
+    if (c->xcc_ids.p && getenv("SSGD_DEBUG")) {
+        // placement of the last launch: XCD, shader engine and CU of every workgroup of the first clusters
+        std::vector<int32_t> h((size_t)c->R * c->G);
+        if (hipMemcpy(h.data(), c->xcc_ids.p, h.size() * sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess)
+            for (int r = 0; r < c->R; ++r) {
+                fprintf(stderr, "ssgd placement replica %d:", r);
+                for (int g = 0; g < c->G; ++g) {
+                    const int v = h[(size_t)r * c->G + g], hw = v >> 8;
+                    fprintf(stderr, " x%d.se%d.cu%d", v & 0xFF, (hw >> 13) & 7, (hw >> 8) & 15);
+                }
+                fprintf(stderr, "\n");
+            }
     }
     if (c->mlp) mlp_destroy(c->mlp);
     DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,

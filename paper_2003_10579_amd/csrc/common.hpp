@@ -12,6 +12,8 @@ enum ModelKind : int32_t { kLsq = 0, kSoftmax = 1, kMlp2 = 2 };
 
 constexpr int kMaxWorkers = 256;   // four workers per lane of one wavefront
 constexpr int kClassPad = 16;      // MFMA tile height that holds the class dimension
+constexpr int kArriveStride = 64;  // 32-bit words between the arrival counters of two replicas
+constexpr int kArriveFast = 32;
 
 // Per-update records written by the schedule kernel (one row per update).
 struct Trace {
@@ -77,20 +79,32 @@ struct LinArgs {
     Trace tr;
     int64_t v0, nsteps;
     float* params;           // [R][nw], standard layout
-    float* park;             // [R][G][S][16][threads] parked per-slot gradients (thread-owned layout)
+    float* park;             // [R][G][S][4][threads][4] parked per-slot gradients: class own_cls + vv, 4 columns of the owner thread
     float* park_small;       // [R][G][S][17]: bias gradient (16) and mean loss (1) of every slot
     float* zpart;            // [R][2][G][maxrows][16] partial logits exchanged inside a cluster
     int32_t maxrows;
-    unsigned int* arrive;    // [R][2] arrival counters of the cluster exchange, zero at launch
+    unsigned int* arrive;    // [R][kArriveStride] arrival counters of the cluster exchange, zero at launch:
+                             // word 0 fenced exchanges, word kArriveFast shared-L2 exchanges (a cache line each)
     int32_t* abort_flag;
     uint32_t spin_limit;
     float* agg_out;          // nullable: averaged gradient of the last update of replica 0
     int32_t* xcc_ids;        // [R][G] XCD each workgroup of a cluster runs on (checked on the device)
     int32_t allow_fast;      // 1: exchange through the shared L2 once a cluster is known to sit on one XCD
-    unsigned long long* prof;   // nullable diagnostics: [R][G][8] shader-clock cycles spent per phase
+    int32_t tune;            // experiment knobs of the steady-state kernel (0 = defaults)
+    // Steady-state kernel, full launches only: CUs per XCD and resident workgroups per CU.  When set, the
+    // workgroup slots of an XCD are dealt out so that the clusters that share CUs share all of them in pairs
+    // (0: clusters take consecutive slots).
+    int32_t pair_cus, pair_layers;
+    unsigned long long* prof;   // nullable diagnostics: [R][G][20] shader-clock cycles spent per phase
 };
 int linear_max_resident_groups(int nbw, size_t lds_bytes);
 size_t linear_lds_bytes(int nbw, int C, int S);
 hipError_t launch_linear(const LinArgs& a, int nbw, hipStream_t s);
+// Single-tile steady-state kernel (256 columns per workgroup, same state layout as launch_linear with nbw = 4).
+// max_records: the most mini-batches any step of the segment computes.
+bool linear_tile_supports(const LinArgs& a, int max_records);
+size_t linear_tile_lds_bytes(int C, int S);
+int linear_tile_resident_groups(size_t lds_bytes);
+hipError_t launch_linear_tile(const LinArgs& a, hipStream_t s);
 
 }  // namespace ssgd

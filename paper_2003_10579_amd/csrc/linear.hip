@@ -106,7 +106,7 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
     float* park = a.park + ((int64_t)rep * G + slice) * S * 16 * NTC;
     float* small_g = a.park_small + ((int64_t)rep * G + slice) * S * 17;
     float* zpart = a.zpart + (int64_t)rep * 2 * G * a.maxrows * 16;
-    unsigned int* arrive = a.arrive + 2 * rep;     // [0] fenced exchanges, [1] shared-L2 exchanges of this launch
+    unsigned int* arrive = a.arrive + kArriveStride * rep;   // fenced exchanges; word kArriveFast: shared-L2 exchanges
     int32_t* xcc_ids = a.xcc_ids + (int64_t)rep * G;
     const float inv_m = 1.0f / (float)m;
     const int nquad = (C + 3) / 4;       // 4-class groups that carry data
@@ -429,13 +429,13 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
     // write through to the L2; the arrival counter is an L2 atomic.  Otherwise ("fenced"):
     // plain accesses ordered by agent-scope release / acquire.
     const __amdgpu_buffer_rsrc_t zrsrc = make_rsrc(zpart, (uint32_t)(2u * G * a.maxrows * 16u * sizeof(float)));
-    const __amdgpu_buffer_rsrc_t crsrc = make_rsrc(arrive, 8u);
+    const __amdgpu_buffer_rsrc_t crsrc = make_rsrc(arrive, kArriveStride * 4u);
     // parked gradients of this workgroup: plane e of slot s at byte ((s*16 + e)*NTC + tid)*4.  Lanes whose
     // classes do not exist use an offset past the end: such loads return zero and such stores are dropped.
     const __amdgpu_buffer_rsrc_t prsrc = make_rsrc(park, (uint32_t)S * 16u * NTC * 4u);
     int pk_off[4];
 #pragma unroll
-    for (int vv = 0; vv < 4; ++vv) pk_off[vv] = (own_cls + vv < C) ? (vv * 4 * NTC + tid) * 4 : (int)0x80000000;
+    for (int vv = 0; vv < 4; ++vv) pk_off[vv] = (own_cls + vv < C) ? (vv * NTC + tid) * 16 : (int)0x80000000;
     uint32_t n_fenced = 0, n_fast = 0;       // exchanges of each kind so far in this launch
 
     unsigned long long ph[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, tprev = 0;
@@ -515,7 +515,7 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
         // ---- phase 2: exchange inside the cluster
         __syncthreads();                                    // S: every thread's exchange stores have completed
         if (G > 1 && tid == 0) {
-            if (fast) (void)__builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, crsrc, 4, 0, 0);
+            if (fast) (void)__builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, crsrc, kArriveFast * 4, 0, 0);
             else __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         }
         mark(1);
@@ -526,12 +526,12 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
             // all 16 planes are loaded without a branch (planes of unused classes hold zeros), so that the
             // loads are issued back to back instead of one predicated block and one wait per element
             const int soff = __builtin_amdgcn_readfirstlane(slot) * 16 * NTC * 4;
-            float pv[16];
+            f32x4 pv[4];
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                pv[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(prsrc, pk_off[e >> 2] + (e & 3) * NTC * 4, soff, 0));
+            for (int vv = 0; vv < 4; ++vv)
+                pv[vv] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(prsrc, pk_off[vv], soff, 0));
 #pragma unroll
-            for (int e = 0; e < 16; ++e) gsum[e] += pv[e];
+            for (int e = 0; e < 16; ++e) gsum[e] += pv[e >> 2][e & 3];
             if (bias_owner) {
 #pragma unroll
                 for (int vv = 0; vv < 4; ++vv) bg[vv] += small[slot * 17 + own_cls + vv];
@@ -543,7 +543,7 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
             const uint32_t target = (fast ? n_fast + 1u : n_fenced + 1u) * (uint32_t)G;
             uint32_t spins = 0;
             for (;;) {
-                const uint32_t got = fast ? __builtin_amdgcn_raw_buffer_load_b32(crsrc, 4, 0, kCoherentLoad)
+                const uint32_t got = fast ? __builtin_amdgcn_raw_buffer_load_b32(crsrc, kArriveFast * 4, 0, kCoherentLoad)
                                           : __hip_atomic_load(arrive, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
                 asm volatile("" ::: "memory");   // the load is repeated every turn
                 if ((int32_t)(got - target) >= 0) break;
@@ -720,20 +720,20 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
                     }
                 } else {
                     const int soff = __builtin_amdgcn_readfirstlane(slot) * 16 * NTC * 4;
-                    float old[16];
+                    f32x4 old[4];
                     if (!first) {
 #pragma unroll
-                        for (int e = 0; e < 16; ++e)
-                            old[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(prsrc, pk_off[e >> 2] + (e & 3) * NTC * 4, soff, 0));
+                        for (int vv = 0; vv < 4; ++vv)
+                            old[vv] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(prsrc, pk_off[vv], soff, 0));
                     }
 #pragma unroll
-                    for (int vv = 0; vv < 4; ++vv)
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            float g = acc[c][vv];
-                            if (!first) g += old[vv * 4 + c];
-                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, g), prsrc, pk_off[vv] + c * NTC * 4, soff, 0);
-                        }
+                    for (int vv = 0; vv < 4; ++vv) {
+                        f32x4 g = {acc[0][vv], acc[1][vv], acc[2][vv], acc[3][vv]};
+                        if (!first) g += old[vv];
+                        // the slot offset goes into the vector offset: a 16-byte buffer store whose scalar offset is a
+                        // register has lost data here when the next instruction rewrote its source registers
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, g), prsrc, pk_off[vv] + soff, 0, 0);
+                    }
                     if (bias_owner) {
 #pragma unroll
                         for (int vv = 0; vv < 4; ++vv) {

@@ -50,11 +50,10 @@ struct Lds {
     float* ylab;      // [64]
     float* bias;      // [16]
     float* small;     // [S][17]   bias gradient and mean loss of every parked slot
-    int* ctl;         // [8]: 0 stop, 1 exchange through the shared L2, 2 cluster shares an XCD, 3 K, 4 records
-    int* s_sel;       // [KC] consume list of update v: slot
-    int* s_tau;       // [KC]                          version read
-    int* s_slot;      // [KC] compute list of v: slot of record r
-    int* s_fresh;     // [KC]                    record r is consumed by update v itself
+    int* ctl;         // [8]: 0 stop, 1 exchange through the shared L2, 2 cluster shares an XCD, 3 exchanges seen by wave 0,
+                      //      4 K, 5 records, 6 parked gradients that update v consumes
+    int* s_stale;     // [KC] slots of those parked gradients, in the order of the consume list
+    int* s_rec;       // [KC] compute list of v: slot of record r; bit 16: consumed by update v itself
 };
 
 __device__ __forceinline__ Lds carve(unsigned char* smem, int C, int S) {
@@ -65,12 +64,10 @@ __device__ __forceinline__ Lds carve(unsigned char* smem, int C, int S) {
     l.rowid = reinterpret_cast<uint32_t*>(l.zbuf + ROWS * 16);
     l.ylab = reinterpret_cast<float*>(l.rowid + ROWS);
     l.bias = l.ylab + ROWS;
-    l.small = l.bias + 16;
-    l.ctl = reinterpret_cast<int*>(l.small + S * 17);
-    l.s_sel = l.ctl + 8;
-    l.s_tau = l.s_sel + KC;
-    l.s_slot = l.s_tau + KC;
-    l.s_fresh = l.s_slot + KC;
+    l.ctl = reinterpret_cast<int*>(l.bias + 16);      // 16-byte aligned: words 4..7 are read as one vector
+    l.s_stale = l.ctl + 8;
+    l.s_rec = l.s_stale + KC;
+    l.small = reinterpret_cast<float*>(l.s_rec + KC);
     return l;
 }
 
@@ -86,8 +83,18 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     // consecutive block ids go to different XCDs: all slices of one cluster take block ids that
     // are congruent modulo 8 and share one L2
     const int xcd = blockIdx.x & 7, slot_in_xcd = blockIdx.x >> 3;
-    const int cluster = (slot_in_xcd / a.G) * 8 + xcd;
-    const int slice = slot_in_xcd % a.G;
+    int pos = slot_in_xcd / a.G, slice = slot_in_xcd % a.G;
+    if (a.pair_cus > 0) {
+        // The dispatcher hands the first pair_cus slots of an XCD to distinct CUs and the next pair_cus slots
+        // to the same CUs again.  A cluster takes G CUs of one such layer, so the clusters on those G CUs
+        // share them with each other only and run in alternation; the CUs left over hold one more cluster.
+        const int L = a.pair_cus, layers = a.pair_layers;
+        const int layer = slot_in_xcd / L, cu = slot_in_xcd % L;
+        const int nb = L / a.G, Lr = L - nb * a.G;
+        if (cu < nb * a.G) { pos = (cu / a.G) * layers + layer; slice = cu % a.G; }
+        else { const int rem = (cu - nb * a.G) + layer * Lr; pos = nb * layers + rem / a.G; slice = rem % a.G; }
+    }
+    const int cluster = pos * 8 + xcd;
     if (cluster >= a.replicas) return;
     const int rep = a.replica0 + cluster;
 
@@ -128,14 +135,14 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         f32x4 pref[LLOADS];
         uint32_t row_id = kNoRow;
         float row_lab = 0.0f;
-        int n_K = 0, n_nrec = 0, n_sel = 0, n_tau = -1, n_slot = 0, n_fresh = 0;
+        int n_K = 0, n_nrec = 0, n_nstale = 0, n_stale = 0, n_stale_pos = KC, n_rec_word = 0;
         int q_sel = -1, q_tau = -1, q_ord = 0;   // lane l: entry l of the consume list of a later version, in flight
         int cur_sel = -1;                        // consume list of the version before the one being prepared
 
-        unsigned long long lph[4] = {0, 0, 0, 0}, lprev = 0;
+        uint32_t lph[4] = {0, 0, 0, 0}, lprev = 0;
         const bool lprof = PROF && tid == NTC;
         auto lmark = [&](int q) {
-            if constexpr (PROF) { if (lprof) { const unsigned long long now = clock64(); lph[q] += now - lprev; lprev = now; } }
+            if constexpr (PROF) { if (lprof) { const uint32_t now = (uint32_t)clock64(); lph[q] += now - lprev; lprev = now; } }
         };
 
         auto issue_lists = [&](int64_t ver) {
@@ -158,10 +165,13 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 for (int l = 0; l < K; ++l)
                     if (__builtin_amdgcn_readlane(l_tau, l) == (int32_t)ver && __builtin_amdgcn_readlane(l_sel, l) == rec_slot) fr = 1;
             n_K = K; n_nrec = nrec;
-            n_tau = (lane < K) ? l_tau : -1;
-            n_sel = (lane < K) ? (async ? l_sel : lane) : 0;
-            n_slot = (lane < nrec) ? rec_slot : 0;
-            n_fresh = (lane < nrec) ? fr : 0;
+            // parked gradients that update ver consumes: entries whose version is older, compacted
+            const bool is_stale = lane < K && l_tau != (int32_t)ver;
+            const unsigned long long smask = __ballot(is_stale);
+            n_nstale = __popcll(smask);
+            n_stale = async ? l_sel : lane;
+            n_stale_pos = is_stale ? __popcll(smask & ((1ull << lane) - 1ull)) : KC;
+            n_rec_word = (lane < nrec) ? (rec_slot | (fr << 16)) : 0;
             const int worker = __shfl(rec_worker, r_of, 64);
             const int ordinal = async ? 0 : __shfl(l_ord, r_of, 64);
             row_id = kNoRow;
@@ -175,7 +185,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             cur_sel = l_sel;
             // The lists are consumed before the gathers are issued: the gathers are the youngest
             // vector-memory operations of this wave until the tile is published.
-            asm volatile("" : "+v"(n_sel), "+v"(n_tau), "+v"(n_slot), "+v"(n_fresh), "+v"(cur_sel), "+v"(row_id) : : "memory");
+            asm volatile("" : "+v"(n_stale), "+v"(n_stale_pos), "+v"(n_rec_word), "+v"(cur_sel), "+v"(row_id) : : "memory");
             if (more) issue_lists(ver + 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -183,7 +193,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 // rows without a sample read row 0; their delta is zero
                 uint32_t id = (uint32_t)__builtin_amdgcn_readlane((int)row_id, lw + 4 * i);
                 id = (id == kNoRow) ? 0u : id;
-                pref[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[i & 3], (int)(id * row_bytes), kStream));
+                pref[i] = (a.tune & 2) ? __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[i & 3], (int)(id * row_bytes), 0))
+                                       : __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[i & 3], (int)(id * row_bytes), kStream));
             }
         };
         auto publish = [&]() {
@@ -191,9 +202,34 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             for (int i = 0; i < LLOADS; ++i) *reinterpret_cast<f32x4*>(my_tile + 4 * i * SL) = pref[i];
             if (lw == 0) {
                 L.rowid[lane] = row_id; L.ylab[lane] = row_lab;
-                if (lane == 0) { L.ctl[3] = n_K; L.ctl[4] = n_nrec; }
-                if (lane < KC) { L.s_sel[lane] = n_sel; L.s_tau[lane] = n_tau; L.s_slot[lane] = n_slot; L.s_fresh[lane] = n_fresh; }
+                if (lane == 0) { L.ctl[4] = n_K; L.ctl[5] = n_nrec; L.ctl[6] = n_nstale; }
+                if (n_stale_pos < KC) L.s_stale[n_stale_pos] = n_stale;
+                if (lane < KC) L.s_rec[lane] = n_rec_word;
             }
+        };
+
+        // Loader wave 0, between D and B: the column sums of the delta tile per record, i.e. the bias
+        // gradient (classes 0..C-1) and the mean mini-batch loss (class 15), summed over the consume
+        // list of update v like the weight gradients; then the bias step and the loss record.
+        auto bias_and_loss = [&](int64_t v) {
+            const int Kv = __builtin_amdgcn_readfirstlane(L.ctl[4]);
+            const int n_rec = __builtin_amdgcn_readfirstlane(L.ctl[5]);
+            const int n_st = __builtin_amdgcn_readfirstlane(L.ctl[6]);
+            const int c = lane & 15, grp = lane >> 4;
+            const int sidx = (c == 15) ? 16 : c;          // the slot record keeps the loss in word 16
+            float tot = 0.0f;
+            for (int i = 0; i < n_st; ++i) tot += L.small[__builtin_amdgcn_readfirstlane(L.s_stale[i]) * 17 + sidx];
+            for (int r = 0; r < n_rec; ++r) {
+                float part = 0.0f;
+                for (int row = r * mp + grp; row < (r + 1) * mp; row += 4) part += L.zbuf[row * 16 + c];
+                part += __shfl_xor(part, 16, 64);
+                part += __shfl_xor(part, 32, 64);
+                const int word = __builtin_amdgcn_readfirstlane(L.s_rec[r]);
+                if ((word >> 16) != 0) tot += part;
+                else if (lane < 16) L.small[(word & 0xFFFF) * 17 + sidx] = part;
+            }
+            if (KIND == kSoftmax && lane < C) L.bias[lane] -= (a.lr / (float)Kv) * tot;
+            if (lane == 15 && slice == 0) a.tr.loss[(int64_t)rep * cap + v] = tot * (1.0f / (float)Kv);
         };
 
         lds_barrier();                               // the compute waves have set up the control words
@@ -202,7 +238,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         issue_lists(a.v0);
         prepare(a.v0, a.nsteps > 1);
         for (int64_t step = 0; step < a.nsteps; ++step) {
-            if constexpr (PROF) { if (lprof) lprev = clock64(); }
+            if constexpr (PROF) { if (lprof) lprev = (uint32_t)clock64(); }
             publish();
             lmark(0);
             lds_barrier();                           // TU
@@ -210,14 +246,16 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             lmark(1);
             lds_barrier();                           // D
             if (L.ctl[0] != 0) return;
+            if (lw == 0) bias_and_loss(a.v0 + step);
             lmark(2);
             lds_barrier();                           // B
             lmark(3);
         }
         if constexpr (PROF) {
             if (lprof)
-                for (int q = 0; q < 4; ++q) a.prof[((int64_t)rep * G + slice) * 20 + 12 + q] += lph[q];
+                for (int q = 0; q < 4; ++q) a.prof[((int64_t)rep * G + slice) * 20 + 16 + q] += lph[q];
         }
+        lds_barrier();                               // the compute waves' last LDS writes
         return;
     }
 
@@ -227,7 +265,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     float* park = a.park + ((int64_t)rep * G + slice) * S * 16 * NTC;
     float* small_g = a.park_small + ((int64_t)rep * G + slice) * S * 17;
     float* zpart = a.zpart + (int64_t)rep * 2 * G * a.maxrows * 16;
-    unsigned int* arrive = a.arrive + 2 * rep;     // [0] fenced exchanges, [1] shared-L2 exchanges of this launch
+    unsigned int* arrive = a.arrive + kArriveStride * rep;   // fenced exchanges; word kArriveFast: shared-L2 exchanges
     const float inv_m = 1.0f / (float)m;
     const int nquad = (C + 3) / 4;
 
@@ -235,8 +273,6 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     const int own_ch = 16 * wave + (lane & 15);
     const int own_col = col0 + 4 * own_ch;
     const int own_cls = 4 * (lane >> 4);
-    const bool bias_owner = wave == 0 && (lane & 15) == 0;
-    const bool loss_owner = tid == 48;             // class 15 of the delta tile carries the row losses
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int cls = own_cls + v;
@@ -253,24 +289,37 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         L.ctl[0] = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         L.ctl[1] = 0;   // fenced until the cluster is known to share an XCD
         L.ctl[2] = 0;
-        const int my_xcc = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xF);   // XCC_ID
-        __hip_atomic_store(a.xcc_ids + (int64_t)rep * G + slice, my_xcc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        L.ctl[3] = 0;
+        // XCC_ID in the low byte (what the same-XCD check compares); HW_ID (CU, shader engine) above it, for diagnostics
+        const int my_xcc = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xF);
+        const int hw_id = (int)__builtin_amdgcn_s_getreg((15 << 11) | 4);
+        __hip_atomic_store(a.xcc_ids + (int64_t)rep * G + slice, my_xcc | (hw_id << 8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (L.ctl[0] != 0) return;
 
     const __amdgpu_buffer_rsrc_t zrsrc = make_rsrc(zpart, (uint32_t)(2u * G * a.maxrows * 16u * sizeof(float)));
-    const __amdgpu_buffer_rsrc_t crsrc = make_rsrc(arrive, 8u);
-    // parked gradients of this workgroup: plane e = 4 vv + c of slot s at float (s*16 + e)*NTC + tid
+    const __amdgpu_buffer_rsrc_t crsrc = make_rsrc(arrive, kArriveStride * 4u);
+    // parked gradients of this workgroup: class own_cls + vv of slot s, 4 columns: 16 bytes at ((s*4 + vv)*NTC + tid)*16
     const __amdgpu_buffer_rsrc_t prsrc = make_rsrc(park, (uint32_t)S * 16u * NTC * 4u);
     int pk_off[4];
 #pragma unroll
-    for (int vv = 0; vv < 4; ++vv) pk_off[vv] = (own_cls + vv < C) ? (vv * 4 * NTC + tid) * 4 : kOutOfRange;
+    for (int vv = 0; vv < 4; ++vv) pk_off[vv] = (own_cls + vv < C) ? (vv * NTC + tid) * 16 : kOutOfRange;
     // forward: rows 16 wave .. 16 wave + 15; row / class index of this lane in the MFMA operands
     const int f_row = 16 * wave + (lane & 15);
-    const int f_cls = lane & 15;
-    const float* const f_x = L.tile + f_row * SL;
-    const float* const f_w = L.wlds + f_cls * SL;
+    // lanes of classes that do not exist read the last class: their logits are never used
+    const int f_key = min(lane & 15, C - 1);
+    // k-block s covers 16-byte chunks 4 s + lane/16 of the row; with the swizzle key split as
+    // key = 4 k2 + k0 its position is 16 (s / 4) + 4 ((s % 4) ^ k2) + ((lane / 16) ^ k0): four base
+    // addresses per operand, the rest is a constant offset
+    const float* f_xa[4];
+    const float* f_wa[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int kx = f_row & 15;
+        f_xa[j] = L.tile + f_row * SL + ((4 * (j ^ (kx >> 2)) + ((lane >> 4) ^ (kx & 3))) << 2);
+        f_wa[j] = L.wlds + f_key * SL + ((4 * (j ^ (f_key >> 2)) + ((lane >> 4) ^ (f_key & 3))) << 2);
+    }
     // exchange: this lane's 16 bytes (4 classes of one row) inside one slice's block
     const int z_store = (f_row * 16 + 4 * (lane >> 4)) * 4;
     const int z_store_off = ((lane >> 4) < nquad) ? z_store : kOutOfRange;
@@ -279,101 +328,128 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     const int slice_bytes = a.maxrows * 16 * 4;
 
     uint32_t n_fenced = 0, n_fast = 0;       // exchanges of each kind so far in this launch
-    unsigned long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tprev = 0;
+    uint32_t ph[14] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, tprev = 0;   // 32-bit cycle counts: fewer registers
     const bool profiling = PROF && tid == 0;
     auto mark = [&](int phase) {
-        if constexpr (PROF) { if (profiling) { const unsigned long long now = clock64(); ph[phase] += now - tprev; tprev = now; } }
+        if constexpr (PROF) { if (profiling) { const uint32_t now = (uint32_t)clock64(); ph[phase] += now - tprev; tprev = now; } }
     };
 
     for (int64_t step = 0; step < a.nsteps; ++step) {
         const int64_t v = a.v0 + step;
-        if constexpr (PROF) { if (profiling) tprev = clock64(); }
+        if constexpr (PROF) { if (profiling) tprev = (uint32_t)clock64(); }
         lds_barrier();                                      // TU
         mark(0);
         const bool fast = L.ctl[1] != 0;
-        const int Kv = __builtin_amdgcn_readfirstlane(L.ctl[3]);
-        const int n_rec = __builtin_amdgcn_readfirstlane(L.ctl[4]);
+        const int4 ctl4 = *reinterpret_cast<const int4*>(L.ctl + 4);
+        const int2 st01 = *reinterpret_cast<const int2*>(L.s_stale);
+        const int Kv = __builtin_amdgcn_readfirstlane(ctl4.x);
+        const int n_rec = __builtin_amdgcn_readfirstlane(ctl4.y);
+        const int n_stale = __builtin_amdgcn_readfirstlane(ctl4.z);
         const int par = (int)(step & 1);
+        // An opaque zero: addresses built from it are recomputed every step instead of being kept in
+        // registers across the whole loop (they would be spilled to scratch memory).
+        int opq = 0;
+        asm volatile("" : "+s"(opq));
 
-        // ---- partial logits of rows 16 wave ..: D[class][row] += W[class][k] X[row][k] over this slice
+        // ---- partial logits of rows 16 wave ..: D[class][row] += W[class][k] X[row][k] over this slice;
+        //      the operands of the next k-block are read from LDS before the MFMAs of this one are issued
         {
             f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
+            f32x4 wv = *reinterpret_cast<const f32x4*>(f_wa[0]);
+            f32x4 xv = *reinterpret_cast<const f32x4*>(f_xa[0]);
+#pragma unroll
             for (int s = 0; s < SL / 16; ++s) {
-                const int ch = 4 * s + (lane >> 4);
-                f32x4 wv = {0.f, 0.f, 0.f, 0.f};
-                if (f_cls < C) wv = *reinterpret_cast<const f32x4*>(f_w + ((ch ^ f_cls) << 2));
-                const f32x4 xv = *reinterpret_cast<const f32x4*>(f_x + ((ch ^ (f_row & 15)) << 2));
+                f32x4 wn = wv, xn = xv;
+                if (s + 1 < SL / 16) {
+                    wn = *reinterpret_cast<const f32x4*>(f_wa[(s + 1) & 3] + ((s + 1) >> 2) * 64);
+                    xn = *reinterpret_cast<const f32x4*>(f_xa[(s + 1) & 3] + ((s + 1) >> 2) * 64);
+                }
+                __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs
                 acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.x, xv.x, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.y, xv.y, acc1, 0, 0, 0);
                 acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.z, xv.z, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.w, xv.w, acc1, 0, 0, 0);
+                wv = wn; xv = xn;
             }
             const f32x4 out = acc0 + acc1;   // classes 4*(lane/16)+0..3 of row f_row
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, out), zrsrc, z_store_off,
-                                                   (par * G + slice) * slice_bytes, 0);
+            mark(8);
+            // 16-byte buffer stores carry their whole offset in the vector register: with the scalar offset in a
+            // register, such a store has lost data here when the next instruction rewrote its source registers
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, out), zrsrc,
+                                                   z_store_off + (par * G + slice) * slice_bytes, 0, 0);
         }
+        // ---- the part of update v that earlier steps parked: the first two such gradients are fetched
+        //      while the exchange stores are on their way
+        auto park_load = [&](int slot, f32x4 (&pv)[4]) {
+            // classes that do not exist are out of range and read as zero
+            const int soff = __builtin_amdgcn_readfirstlane(slot) * 16 * NTC * 4;
+#pragma unroll
+            for (int vv = 0; vv < 4; ++vv)
+                pv[vv] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(prsrc, pk_off[vv], soff, 0));
+        };
+        f32x4 pva[4], pvb[4];
+#pragma unroll
+        for (int vv = 0; vv < 4; ++vv) { pva[vv] = f32x4{0.f, 0.f, 0.f, 0.f}; pvb[vv] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        if (n_stale > 0) park_load(st01.x, pva);
+        if (n_stale > 1) park_load(st01.y, pvb);
+        mark(9);
         // ---- arrival: this wave's stores are in the L2 (shared-L2 mode) or released to the device
         if (fast) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the stores have been acknowledged
-            if (lane == 0) (void)__builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, crsrc, 4, 0, 0);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the stores have been acknowledged by the L2
+            mark(10);
+            if (lane == 0) (void)__builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, crsrc, kArriveFast * 4, 0, 0);
         } else {
             if (lane == 0) __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         }
         mark(1);
 
-        // ---- while the other slices arrive: the part of update v that earlier steps parked
-        float gsum[16];
-        float bg[4] = {0.f, 0.f, 0.f, 0.f};
-        float lsum = 0.0f;
+        float gsum[16];          // this thread's part of sum_l g_l: gsum[4 vv + c]
 #pragma unroll
-        for (int e = 0; e < 16; ++e) gsum[e] = 0.0f;
-        for (int l = 0; l < Kv; ++l) {
-            if (L.s_tau[l] == (int32_t)v) continue;
-            const int slot = __builtin_amdgcn_readfirstlane(L.s_sel[l]);
-            const int soff = slot * 16 * NTC * 4;
-            float pv[16];
+        for (int e = 0; e < 16; ++e) gsum[e] = pva[e >> 2][e & 3] + pvb[e >> 2][e & 3];
+        for (int i = 2; i < n_stale; ++i) {     // further parked gradients (K > 2)
+            park_load(L.s_stale[i], pva);
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                pv[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(prsrc, pk_off[e >> 2], soff + (e & 3) * NTC * 4, 0));
-#pragma unroll
-            for (int e = 0; e < 16; ++e) gsum[e] += pv[e];
-            if (bias_owner) {
-#pragma unroll
-                for (int vv = 0; vv < 4; ++vv) bg[vv] += L.small[slot * 17 + own_cls + vv];
-                if (loss_owner) lsum += L.small[slot * 17 + 16];
-            }
+            for (int e = 0; e < 16; ++e) gsum[e] += pva[e >> 2][e & 3];
         }
         mark(2);
 
-        // ---- every wave polls the counter itself: all 4 G waves of the cluster have arrived
+        // ---- wave 0 polls the counter in the L2 (all 4 G compute waves of the cluster have arrived) and
+        //      relays the result through an LDS word, which the other waves poll
         {
             const uint32_t target = (fast ? n_fast + 1u : n_fenced + 1u) * (uint32_t)(4 * G);
-            uint32_t spins = 0;
-            for (;;) {
-                uint32_t got = fast ? __builtin_amdgcn_raw_buffer_load_b32(crsrc, 4, 0, kAgentLoad)
-                                    : __hip_atomic_load(arrive, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                asm volatile("" ::: "memory");   // the load is repeated every turn
-                got = (uint32_t)__builtin_amdgcn_readfirstlane((int)got);
-                if ((int32_t)(got - target) >= 0) break;
-                __builtin_amdgcn_s_sleep(1);
-                ++spins;
-                if (spins > a.spin_limit ||
-                    ((spins & 63u) == 0 && __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                    if (lane == 0) {
-                        __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        L.ctl[0] = 1;
+            const int want = (int)(n_fast + n_fenced + 1u);
+            if (wave == 0) {
+                uint32_t spins = 0;
+                for (;;) {
+                    uint32_t got = fast ? __builtin_amdgcn_raw_buffer_load_b32(crsrc, kArriveFast * 4, 0, kAgentLoad)
+                                        : __hip_atomic_load(arrive, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                    asm volatile("" ::: "memory");   // the load is repeated every turn
+                    got = (uint32_t)__builtin_amdgcn_readfirstlane((int)got);
+                    if ((int32_t)(got - target) >= 0) break;
+                    if (a.tune & 1) __builtin_amdgcn_s_sleep(2); else __builtin_amdgcn_s_sleep(8);
+                    ++spins;
+                    if (spins > a.spin_limit ||
+                        ((spins & 63u) == 0 && __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                        if (lane == 0) {
+                            __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            L.ctl[0] = 1;
+                        }
+                        break;
                     }
-                    break;
                 }
+                if (lane == 0) __hip_atomic_store(&L.ctl[3], want, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            } else {
+                while (__builtin_amdgcn_readfirstlane(__hip_atomic_load(&L.ctl[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) < want)
+                    __builtin_amdgcn_s_sleep(1);
+                if (!fast) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             }
             if (!fast && a.allow_fast && tid == 0) {
                 // first exchange of the launch: do all slices of this cluster share an XCD (one L2)?
                 const int32_t* ids = a.xcc_ids + (int64_t)rep * G;
                 int same = 1;
-                const int mine = __hip_atomic_load(ids + slice, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int mine = __hip_atomic_load(ids + slice, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xFF;
                 for (int g = 0; g < G; ++g)
-                    if (__hip_atomic_load(ids + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != mine) same = 0;
+                    if ((__hip_atomic_load(ids + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xFF) != mine) same = 0;
                 L.ctl[2] = same;
             }
             if (fast) ++n_fast; else ++n_fenced;
@@ -436,8 +512,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                     dl[e] = (ok && 4 * z_qd + e < C) ? pr * inv_m : 0.0f;
                 }
             }
-            // the unused class 15 carries the row loss, so that one contraction with a column of ones
-            // yields the bias gradient and the loss sum
+            // the unused class 15 carries the row loss: the column sums of the delta tile (taken by a
+            // loader wave) then hold the bias gradient and the loss sum
             if (z_qd == 3) dl.w = loss * inv_m;
             *reinterpret_cast<f32x4*>(L.zbuf + z_row * 16 + 4 * z_qd) = dl;
         }
@@ -445,64 +521,74 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         if (L.ctl[0] != 0) return;   // uniform: every thread reads the same LDS word
         mark(5);
 
-        // ---- per record: the gradient slice delta^T X; wave 0 also contracts delta with a column of
-        //      ones, which gives the bias gradient and (class 15) the loss sum
-        for (int r = 0; r < n_rec; ++r) {
-            const int slot = __builtin_amdgcn_readfirstlane(L.s_slot[r]);
-            const bool is_fresh = __builtin_amdgcn_readfirstlane(L.s_fresh[r]) != 0;
-            f32x4 acc[4], accb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-            auto contract = [&](float dv, const f32x4& xv) {
-                acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, xv.x, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, xv.y, acc[1], 0, 0, 0);
-                acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, xv.z, acc[2], 0, 0, 0);
-                acc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, xv.w, acc[3], 0, 0, 0);
-                if (wave == 0) accb = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, 1.0f, accb, 0, 0, 0);
-            };
-            int ks = r * mp / 4;
-            const int ks_end = ks + mp / 4;
-            for (; ks + 4 <= ks_end; ks += 4) {     // operands of four steps are read before their MFMAs
-                float dv[4];
-                f32x4 xv[4];
+        // ---- per record: the gradient slice delta^T X, in groups of four k-steps (16 rows); the operands
+        //      of the next group are read from LDS before the MFMAs of this one are issued
+        {
+            const int kpr = mp >> 2;               // k-steps per record
+            const int ngrp = (kpr + 3) >> 2;       // groups per record
+            const int b_lo = lane >> 4, b_cls = lane & 15;
+            auto load_group = [&](int r, int g, float (&dv)[4], f32x4 (&xv)[4]) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int row = 4 * (ks + u) + (lane >> 4);
-                    dv[u] = L.zbuf[row * 16 + (lane & 15)];
+                    const int k = 4 * g + u;
+                    const int row = r * mp + 4 * min(k, kpr - 1) + b_lo;
+                    dv[u] = L.zbuf[row * 16 + b_cls];   // k-steps past the record are masked when they are used
                     xv[u] = *reinterpret_cast<const f32x4*>(L.tile + row * SL + ((own_ch ^ (row & 15)) << 2));
                 }
+            };
+            f32x4 acc[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) contract(dv[u], xv[u]);
-            }
-            for (; ks < ks_end; ++ks) {
-                const int row = 4 * ks + (lane >> 4);
-                const float dv = L.zbuf[row * 16 + (lane & 15)];
-                const f32x4 xv = *reinterpret_cast<const f32x4*>(L.tile + row * SL + ((own_ch ^ (row & 15)) << 2));
-                contract(dv, xv);
-            }
-            if (is_fresh) {
+            for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+            auto contract = [&](int g, const float (&dv)[4], const f32x4 (&xv)[4]) {
 #pragma unroll
-                for (int vv = 0; vv < 4; ++vv)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) gsum[vv * 4 + c] += acc[c][vv];
-                if (bias_owner) {
-#pragma unroll
-                    for (int vv = 0; vv < 4; ++vv) bg[vv] += accb[vv];
-                    if (loss_owner) lsum += accb[3];
+                for (int u = 0; u < 4; ++u) {
+                    const float da = (4 * g + u < kpr) ? dv[u] : 0.0f;   // k-steps past the record contribute nothing
+                    acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(da, xv[u].x, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(da, xv[u].y, acc[1], 0, 0, 0);
+                    acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(da, xv[u].z, acc[2], 0, 0, 0);
+                    acc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(da, xv[u].w, acc[3], 0, 0, 0);
                 }
-            } else {
-                const int soff = slot * 16 * NTC * 4;
+            };
+            // record r is complete: add it to the aggregate of update v, or park it in its slot
+            auto finish = [&](int r) {
+                if constexpr (PROF) { asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])); mark(11); }
+                const int word = __builtin_amdgcn_readfirstlane(L.s_rec[r]);
+                if ((word >> 16) != 0) {
 #pragma unroll
-                for (int vv = 0; vv < 4; ++vv)
+                    for (int vv = 0; vv < 4; ++vv)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, acc[c][vv]), prsrc, pk_off[vv],
-                                                              soff + c * NTC * 4, 0);
-                if (bias_owner) {
+                        for (int c = 0; c < 4; ++c) gsum[vv * 4 + c] += acc[c][vv];
+                } else {
+                    const int soff = (word & 0xFFFF) * 16 * NTC * 4;
 #pragma unroll
-                    for (int vv = 0; vv < 4; ++vv) L.small[slot * 17 + own_cls + vv] = accb[vv];
-                    if (loss_owner) L.small[slot * 17 + 16] = accb[3];
+                    for (int vv = 0; vv < 4; ++vv) {
+                        const f32x4 gv = {acc[0][vv], acc[1][vv], acc[2][vv], acc[3][vv]};
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, gv), prsrc, pk_off[vv] + soff, 0, 0);
+                    }
                 }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+                mark(12);
+            };
+            // the operands of the next group are read into a second register set before the MFMAs of this one
+            float dv[4];
+            f32x4 xv[4];
+            int r = opq, g = 0;
+            if (n_rec > 0) load_group(r, 0, dv, xv);
+            while (r < n_rec) {
+                int rn = r, gn = g + 1;
+                if (gn == ngrp) { gn = 0; rn = r + 1; }
+                float dn[4];
+                f32x4 xn[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { dn[u] = dv[u]; xn[u] = xv[u]; }
+                if (rn < n_rec) load_group(rn, gn, dn, xn);
+                __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs
+                contract(g, dv, xv);
+                if (rn != r) finish(r);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { dv[u] = dn[u]; xv[u] = xn[u]; }
+                r = rn; g = gn;
             }
         }
         mark(6);
@@ -510,23 +596,18 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         // ---- update v: each compute thread owns its weights; nobody reads them before TU
         {
             const float scale = a.lr / (float)Kv;
-            const float invK = 1.0f / (float)Kv;
+            int och = own_ch, ocl = own_cls;
+            asm volatile("" : "+v"(och), "+v"(ocl));   // the four addresses below are rebuilt here, not kept across the loop
 #pragma unroll
             for (int vv = 0; vv < 4; ++vv) {
-                const int cls = own_cls + vv;
+                const int cls = ocl + vv;
                 if (cls < C) {
-                    f32x4* wp = reinterpret_cast<f32x4*>(L.wlds + cls * SL + ((own_ch ^ cls) << 2));
+                    f32x4* wp = reinterpret_cast<f32x4*>(L.wlds + cls * SL + ((och ^ cls) << 2));
                     f32x4 w = *wp;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) w[c] -= scale * gsum[vv * 4 + c];
                     *wp = w;
                 }
-            }
-            if (loss_owner && slice == 0) a.tr.loss[(int64_t)rep * cap + v] = lsum * invK;
-            if (KIND == kSoftmax && bias_owner) {
-#pragma unroll
-                for (int vv = 0; vv < 4; ++vv)
-                    if (own_cls + vv < C) L.bias[own_cls + vv] -= scale * bg[vv];
             }
             if (tid == 0 && L.ctl[2] != 0) L.ctl[1] = 1;   // later exchanges of this launch use the shared L2
         }
@@ -534,11 +615,9 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     }
     if constexpr (PROF) {
         if (profiling)
-            for (int q = 0; q < 8; ++q) a.prof[((int64_t)rep * G + slice) * 20 + q] += ph[q];
+            for (int q = 0; q < 14; ++q) a.prof[((int64_t)rep * G + slice) * 20 + q] += ph[q];
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();   // compute waves only would do, but every wave of the workgroup counts
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    lds_barrier();
 
     // ---- leave the state in HBM for the next launch
 #pragma unroll
@@ -561,14 +640,15 @@ hipError_t launch_k(const LinArgs& a, size_t lds, hipStream_t s) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const int groups = (a.replicas + 7) / 8;
-    hipLaunchKernelGGL((linear_tile_kernel<KIND, PROF>), dim3(groups * 8 * a.G), dim3(512), lds, s, a);
+    const int blocks = a.pair_cus > 0 ? 8 * a.pair_cus * a.pair_layers : groups * 8 * a.G;
+    hipLaunchKernelGGL((linear_tile_kernel<KIND, PROF>), dim3(blocks), dim3(512), lds, s, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
 size_t linear_tile_lds_bytes(int C, int S) {
-    const size_t words = (size_t)ROWS * SL + (size_t)C * SL + ROWS * 16 + 2 * ROWS + 16 + (size_t)S * 17 + 8 + 4 * KC;
+    const size_t words = (size_t)ROWS * SL + (size_t)C * SL + ROWS * 16 + 2 * ROWS + 16 + 8 + 2 * KC + (size_t)S * 17;
     return sizeof(float) * words;
 }
 
