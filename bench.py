@@ -35,12 +35,40 @@ def cpu_baseline(X, y, spec, budget_s=12.0):
             "sample": f"first {done} of 5000 updates of replica 0 ({done * 2} worker-gradients), {dt:.1f} s"}
 
 
+def measured_traffic(replicas, updates):
+    """HBM bytes per launch of the dominant kernel, from the committed counter summary (two rocprofv3 --pmc
+    runs of this script, scaled by a copy kernel); None when the summary was taken in another launch shape."""
+    path = os.path.join(ROOT, "profiles", "linear_tile_kernel_config1_hbm_traffic.txt")
+    try:
+        rec = {}
+        with open(path) as f:
+            for line in f:
+                if line.startswith("bench:"):
+                    k, v = line[len("bench:"):].split("=")
+                    rec[k.strip()] = float(v)
+        if int(rec["replicas"]) == replicas and int(rec["updates_per_launch"]) == updates:
+            return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
+
+def mc_rate(ssgd):
+    """Monte-Carlo runtime estimator (config 3 shape: P=128, every K, K-async chains of 8 updates, Exp(1))."""
+    dist = ssgd.delay_dist("exp", 1.0)
+    ssgd.runtime_mc("k_async", 128, 1, 128, dist, 2000, 8, seed=1)
+    trials = 100000
+    t0 = time.perf_counter()
+    ssgd.runtime_mc("k_async", 128, 1, 128, dist, trials, 8, seed=1)
+    return trials / (time.perf_counter() - t0)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--replicas", type=int, default=int(os.environ.get("SSGD_BENCH_REPLICAS", "42")))
+    ap.add_argument("--replicas", type=int, default=int(os.environ.get("SSGD_BENCH_REPLICAS", "40")))
     ap.add_argument("--updates", type=int, default=5000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -98,9 +126,11 @@ def main():
                    "value_replicas_1": 1 * J * K / dt1},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "linear_cluster_kernel<4>", "launches": kn, "avg_launch_ms": kms / kn,
+                     "kernel": "linear_tile_kernel<softmax>", "launches": kn, "avg_launch_ms": kms / kn,
                      "algorithmic_bytes_per_launch": per_launch_bytes},
     }
+    out["roofline"]["traffic"] = measured_traffic(R, J)
+    out["config"]["mc_trials_per_s"] = mc_rate(ssgd)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(X, y, spec)
     print(json.dumps(out))
