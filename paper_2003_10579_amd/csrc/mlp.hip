@@ -1,15 +1,521 @@
+// Two-layer ReLU network with a softmax output (the AdaSync experiment's model
+// class, Sec. 5 / Algorithm 1 runs K-async SGD with a changing K): per-worker
+// mini-batch gradients at possibly stale parameters, the K-gradient aggregate and
+// the parameter-server update (Sec. 2.2, Eq. (3)).
+//
+// A worker's gradient is linear in two small factors, so what is kept per worker
+// from the moment it starts (at the parameters it read) until an update consumes
+// it is: its mini-batch rows in bf16, in both orientations; delta1 = back-propagated
+// error of the hidden layer, scaled by 1/m and rounded to bf16, transposed; and
+// the small second-layer gradients.  The first-layer gradient of an update,
+//     sum over the K consumed workers of  delta1_l^T X_l    (hidden x d),
+// is then one bf16 MFMA contraction over K*m rows whose epilogue applies it to the
+// fp32 master weights and refreshes their bf16 copy; no first-layer gradient is ever
+// stored.  Per update v:
+//   gather    rows of the workers that start at version v -> bf16 (row-major and transposed)
+//   forward   Z1 = X W1^T + b1 on the MFMA units (bf16 in, fp32 accumulate), H = relu(Z1) in fp32
+//   layer 2   Z2 = H W2^T + b2, softmax, delta2, loss, delta1 = (W2^T delta2) * [H > 0] in fp32
+//   consume   W1 -= lr/K * sum_l delta1_l^T X_l (MFMA), then b1, W2, b2 and the loss record
 #include "mlp.hpp"
 
+#include <cmath>
+#include <vector>
+
 namespace ssgd {
-struct MlpState { int unused; };
-hipError_t mlp_create(MlpState**, const ssgd_model&, int, int, int, int, double, uint64_t, hipStream_t, std::string* msg) {
-    if (msg) *msg = "not built yet";
-    return hipErrorNotSupported;
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int MP = 64;         // rows kept per worker (m <= 64; the rest is zero)
+constexpr int BT = 128;        // output tile of the contraction kernel
+constexpr int KT = 64;         // contraction depth per stage
+constexpr int LDT = KT + 8;    // padded LDS row (bf16 elements): 144 bytes, keeps 16-byte reads conflict-poor
+
+// round to nearest even, as a 16-bit pattern; infinities and NaNs are truncated
+__device__ __forceinline__ unsigned short bf16_bits(float x) {
+    uint32_t b = __float_as_uint(x);
+    if ((b & 0x7F800000u) != 0x7F800000u) b += 0x7FFFu + ((b >> 16) & 1u);
+    return (unsigned short)(b >> 16);
 }
-hipError_t mlp_run_segment(MlpState*, const Trace&, const WorkerState&, int64_t, int64_t, float*, hipStream_t, double*, int64_t*, std::string* msg) {
-    if (msg) *msg = "not built yet";
-    return hipErrorNotSupported;
+__device__ __forceinline__ float bf16_round(float x) { return __uint_as_float((uint32_t)bf16_bits(x) << 16); }
+
+struct MlpArgs {
+    int32_t d, H, C, P, m, variant, Kcap;
+    const float* X;
+    const int32_t* y;
+    uint32_t N;
+    uint64_t seed;
+    Trace tr;
+    int64_t v;
+    int32_t nrec, Kv;
+    float lr;
+    float* params;             // W1[H][d], b1[H], W2[C][H], b2[C]
+    unsigned short* w1r;       // bf16 copy of W1
+    float* w2r;                // W2 rounded to bf16, kept as fp32
+    unsigned short* xb;        // [S][MP][d]   bf16 rows of the slot's mini-batch
+    unsigned short* xbt;       // [S][d][MP]   the same, transposed
+    float* hbuf;               // [S][MP][H]   hidden activations
+    unsigned short* d1t;       // [S][H][MP]   delta1 / m in bf16, transposed
+    float* gb1;                // [S][H]       sum over the mini-batch of delta1
+    float* gw2;                // [S][C][H]    sum of delta2 (x) h
+    float* gb2;                // [S][16]      sum of delta2
+    float* loss;               // [S]          sum of the sample losses
+    int32_t* ylab;             // [S][MP]      labels (-1: no sample)
+    float* agg_out;            // nullable
+};
+
+// worker and mini-batch ordinal of record r of the compute list of version v, and its slot
+__device__ __forceinline__ void record_of(const MlpArgs& a, int r, int& worker, int& ordinal, int& slot) {
+    if (a.variant == kAsync) {
+        worker = (a.v == 0) ? r : a.tr.sel[(a.v - 1) * a.tr.Kcap + r];
+        ordinal = 0;
+        slot = worker;
+    } else {
+        worker = a.tr.sel[a.v * a.tr.Kcap + r];
+        ordinal = a.tr.ord[a.v * a.tr.Kcap + r];
+        slot = r;
+    }
 }
-float* mlp_params(MlpState*) { return nullptr; }
-void mlp_destroy(MlpState*) {}
+__device__ __forceinline__ int consumed_slot(const MlpArgs& a, int l) {
+    return a.variant == kAsync ? a.tr.sel[a.v * a.tr.Kcap + l] : l;
+}
+
+// ---- gather: one workgroup per (record, block of 128 columns) ---------------------------------
+__global__ __launch_bounds__(256) void mlp_gather_kernel(MlpArgs a) {
+    __shared__ unsigned short tr_tile[128][MP + 2];
+    __shared__ uint32_t ids[MP];
+    const int r = blockIdx.x, cb = blockIdx.y, tid = threadIdx.x;
+    int worker, ordinal, slot;
+    record_of(a, r, worker, ordinal, slot);
+    if (tid < MP) {
+        uint32_t id = 0xFFFFFFFFu;
+        if (tid < a.m) id = batch_index(a.seed, 0u, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)tid, a.N);
+        ids[tid] = id;
+        if (cb == 0) a.ylab[slot * MP + tid] = (id == 0xFFFFFFFFu) ? -1 : a.y[id];
+    }
+    __syncthreads();
+    // 64 rows x 128 columns: thread -> (row = tid / 4 + 64 * pass?, ...): 32 float4 per row, 8 rows per pass
+    const int c4 = tid & 31, r0 = tid >> 5;
+    for (int s = r0; s < MP; s += 8) {
+        const uint32_t id = ids[s];
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (id != 0xFFFFFFFFu) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.X + (int64_t)id * a.d + cb * 128 + 4 * c4));
+        unsigned short b[4] = {bf16_bits(v.x), bf16_bits(v.y), bf16_bits(v.z), bf16_bits(v.w)};
+        unsigned short* dst = a.xb + ((int64_t)slot * MP + s) * a.d + cb * 128 + 4 * c4;
+        *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)b[0] | ((uint32_t)b[1] << 16), (uint32_t)b[2] | ((uint32_t)b[3] << 16));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) tr_tile[4 * c4 + q][s] = b[q];
+    }
+    __syncthreads();
+    // transposed copy: column c of the block, 64 samples = 128 bytes; 8 threads per column, 16 bytes each
+    for (int q = tid; q < 128 * 8; q += 256) {
+        const int c = q >> 3, part = q & 7;
+        u16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = tr_tile[c][8 * part + e];
+        *reinterpret_cast<u16x8*>(a.xbt + ((int64_t)slot * a.d + cb * 128 + c) * MP + 8 * part) = v;
+    }
+}
+
+// ---- contraction: C[M x N] = sum over stages of A_stage[M x 64] B_stage[N x 64]^T, bf16 MFMA ----
+// FWD: rows = (record, sample) of the compute list, columns = hidden units, depth = d.
+// BWD: rows = hidden units, columns = input features, depth = 64 samples of every consumed slot.
+template <bool FWD>
+__global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+    unsigned short* As = lds;                       // [2][BT][LDT]
+    unsigned short* Bs = lds + 2 * BT * LDT;        // [2][BT][LDT]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bm = blockIdx.x, bn = blockIdx.y;
+    const int d = a.d, H = a.H;
+    const int stages = FWD ? d / KT : a.Kv;
+
+    // global -> LDS: 128 rows x 8 chunks of 16 bytes per operand; thread -> chunk tid % 8 of rows tid / 8 + 32 i
+    const int lchunk = tid & 7, lrow = tid >> 3;
+    int slot_of_pair[2] = {0, 0};
+    if (FWD) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int r = 2 * bm + q;
+            int worker = 0, ordinal = 0, slot = 0;
+            if (r < a.nrec) record_of(a, r, worker, ordinal, slot);
+            slot_of_pair[q] = slot;
+        }
+    }
+    auto a_ptr = [&](int row, int stage) -> const unsigned short* {
+        if (FWD) {
+            const int slot = slot_of_pair[row >> 6];
+            return a.xb + ((int64_t)slot * MP + (row & 63)) * d + stage * KT;
+        }
+        return a.d1t + ((int64_t)consumed_slot(a, stage) * H + bm * BT + row) * MP;
+    };
+    auto b_ptr = [&](int row, int stage) -> const unsigned short* {
+        if (FWD) return a.w1r + (int64_t)(bn * BT + row) * d + stage * KT;
+        return a.xbt + ((int64_t)consumed_slot(a, stage) * d + bn * BT + row) * MP;
+    };
+    u16x8 ra[4], rb[4];
+    auto fetch = [&](int stage) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = lrow + 32 * i;
+            ra[i] = *reinterpret_cast<const u16x8*>(a_ptr(row, stage) + 8 * lchunk);
+            rb[i] = *reinterpret_cast<const u16x8*>(b_ptr(row, stage) + 8 * lchunk);
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = lrow + 32 * i;
+            *reinterpret_cast<u16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = ra[i];
+            *reinterpret_cast<u16x8*>(Bs + (buf * BT + row) * LDT + 8 * lchunk) = rb[i];
+        }
+    };
+
+    // wave (wm, wn) computes a 64 x 64 block as 2 x 2 MFMA tiles of 32 x 32
+    const int wm = wave >> 1, wn = wave & 1;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int st = 0; st < stages; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < stages) fetch(st + 1);
+#pragma unroll
+        for (int kk = 0; kk < KT / 16; ++kk) {
+            bf16x8 fa[2], fb[2];
+            // operand layout of the 32x32x16 MFMA: lane -> row lane % 32, depth 8 (lane / 32) .. + 7
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8*>(As + (buf * BT + wm * 64 + i * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8*>(Bs + (buf * BT + wn * 64 + j * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (st + 1 < stages) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    // result layout: element e of lane -> row 8 (e / 4) + 4 (lane / 32) + e % 4, column lane % 32
+    const float scale = a.lr / (float)a.Kv;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const int col = wn * 64 + j * 32 + (lane & 31);
+                const float v = acc[i][j][e];
+                if (FWD) {
+                    const int r = 2 * bm + (row >> 6);
+                    if (r < a.nrec) {
+                        const int n = bn * BT + col;
+                        const float z = v + a.params[(int64_t)H * d + n];
+                        a.hbuf[((int64_t)slot_of_pair[row >> 6] * MP + (row & 63)) * H + n] = z > 0.0f ? z : 0.0f;
+                    }
+                } else {
+                    const int64_t q = (int64_t)(bm * BT + row) * d + bn * BT + col;
+                    const float w = a.params[q] - scale * v;
+                    a.params[q] = w;
+                    a.w1r[q] = bf16_bits(w);
+                    if (a.agg_out) a.agg_out[q] = v / (float)a.Kv;
+                }
+            }
+}
+
+// ---- layer 2, softmax, delta2, delta1: one workgroup per record --------------------------------
+__global__ __launch_bounds__(256) void mlp_layer2_kernel(MlpArgs a) {
+    __shared__ float d2s[MP][16];
+    __shared__ float red[MP];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    const int H = a.H, C = a.C, m = a.m;
+    int worker, ordinal, slot;
+    record_of(a, r, worker, ordinal, slot);
+    const float* hrow = a.hbuf + (int64_t)slot * MP * H;
+    const float* b2 = a.params + (int64_t)H * a.d + H + (int64_t)C * H;
+    // phase 1: four threads per row, each a quarter of the hidden units
+    {
+        const int s = tid >> 2, qd = tid & 3;
+        float z[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) z[c] = 0.0f;
+        const int per = H / 4;
+        for (int j = qd * per; j < (qd + 1) * per; ++j) {
+            const float h = hrow[(int64_t)s * H + j];
+#pragma unroll
+            for (int c = 0; c < 16; ++c)
+                if (c < C) z[c] += a.w2r[c * H + j] * h;
+        }
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            z[c] += __shfl_xor(z[c], 1, 64);
+            z[c] += __shfl_xor(z[c], 2, 64);
+        }
+        const int lab = a.ylab[slot * MP + s];
+        const bool ok = s < m && lab >= 0;
+        float zmax = -3.0e38f;
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+            if (c < C) { z[c] += b2[c]; zmax = fmaxf(zmax, z[c]); }
+        float den = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+            if (c < C) den += expf(z[c] - zmax);
+        float ls = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            float dv = 0.0f;
+            if (c < C && ok) {
+                dv = expf(z[c] - zmax) / den - (c == lab ? 1.0f : 0.0f);
+                if (c == lab) ls = -(z[c] - zmax - logf(den));
+            }
+            if (qd == 0) d2s[s][c] = dv;
+        }
+        if (qd == 0) red[s] = ok ? ls : 0.0f;
+    }
+    __syncthreads();
+    if (tid < 16) {
+        float sum = 0.0f;
+        for (int s = 0; s < MP; ++s) sum += d2s[s][tid];
+        a.gb2[slot * 16 + tid] = sum;
+    }
+    if (tid == 16) {
+        float sum = 0.0f;
+        for (int s = 0; s < MP; ++s) sum += red[s];
+        a.loss[slot] = sum;
+    }
+    // phase 2: one thread per hidden unit (H / 256 units each): delta1 over the rows, second-layer gradient
+    const float inv_m = 1.0f / (float)m;
+    for (int j = tid; j < H; j += 256) {
+        float w2c[16], gw[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) { w2c[c] = (c < C) ? a.w2r[c * H + j] : 0.0f; gw[c] = 0.0f; }
+        float g1 = 0.0f;
+        unsigned short* dst = a.d1t + ((int64_t)slot * H + j) * MP;
+        for (int s0 = 0; s0 < MP; s0 += 8) {
+            u16x8 pack;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int s = s0 + e;
+                const float h = hrow[(int64_t)s * H + j];
+                float d1 = 0.0f;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) {
+                    const float dv = d2s[s][c];
+                    d1 += w2c[c] * dv;
+                    gw[c] += dv * h;
+                }
+                if (!(h > 0.0f)) d1 = 0.0f;
+                g1 += d1;
+                pack[e] = bf16_bits(d1 * inv_m);
+            }
+            *reinterpret_cast<u16x8*>(dst + s0) = pack;
+        }
+        a.gb1[slot * H + j] = g1;
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+            if (c < C) a.gw2[((int64_t)slot * C + c) * H + j] = gw[c];
+    }
+}
+
+// ---- the small parameters of update v, and its loss record ------------------------------------
+__global__ __launch_bounds__(256) void mlp_small_update_kernel(MlpArgs a) {
+    const int H = a.H, C = a.C, d = a.d;
+    const float invKm = 1.0f / ((float)a.Kv * (float)a.m);
+    float* b1 = a.params + (int64_t)H * d;
+    float* W2 = b1 + H;
+    float* b2 = W2 + (int64_t)C * H;
+    const int total = H + C * H + C + 1;
+    for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < total; q += gridDim.x * blockDim.x) {
+        float sum = 0.0f;
+        for (int l = 0; l < a.Kv; ++l) {
+            const int slot = consumed_slot(a, l);
+            if (q < H) sum += a.gb1[slot * H + q];
+            else if (q < H + C * H) sum += a.gw2[(int64_t)slot * C * H + (q - H)];
+            else if (q < H + C * H + C) sum += a.gb2[slot * 16 + (q - H - C * H)];
+            else sum += a.loss[slot];
+        }
+        const float g = sum * invKm;
+        if (q < H) { b1[q] -= a.lr * g; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = g; }
+        else if (q < H + C * H) {
+            const float w = W2[q - H] - a.lr * g;
+            W2[q - H] = w;
+            a.w2r[q - H] = bf16_round(w);
+            if (a.agg_out) a.agg_out[(int64_t)H * d + q] = g;
+        } else if (q < H + C * H + C) { b2[q - H - C * H] -= a.lr * g; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = g; }
+        else a.tr.loss[a.v] = g;
+    }
+}
+
+__global__ void mlp_refresh_kernel(const float* params, unsigned short* w1r, float* w2r, int64_t n1, int64_t off2, int64_t n2) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; q < n1; q += stride) w1r[q] = bf16_bits(params[q]);
+    for (int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; q < n2; q += stride) w2r[q] = bf16_round(params[off2 + q]);
+}
+
+// W1, W2 uniform on (-1/sqrt(fan_in), 1/sqrt(fan_in)) from the INIT stream, biases zero
+__global__ void mlp_init_kernel(float* params, uint64_t seed, int64_t nw, int64_t n1, int64_t off2, int64_t n2, float bound1, float bound2) {
+#pragma clang fp contract(off)
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; q < nw; q += stride) {
+        float w = 0.0f;
+        const bool in1 = q < n1, in2 = q >= off2 && q < off2 + n2;
+        if (in1 || in2) {
+            const u32x4 b = draw(seed, kInit, (uint32_t)((q >> 2) >> 32), 0u, 0u, 0u, (uint32_t)(q >> 2));
+            const uint32_t word = (q & 2) ? ((q & 1) ? b.w : b.z) : ((q & 1) ? b.y : b.x);
+            const float u = uniform_open(word);
+            float v = u + u;
+            v = v - 1.0f;
+            w = v * (in1 ? bound1 : bound2);
+        }
+        params[q] = w;
+    }
+}
+
+struct DevMem {
+    void* p = nullptr;
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 16); }
+    void release() { if (p) (void)hipFree(p); p = nullptr; }
+};
+
+}  // namespace
+
+struct MlpState {
+    MlpArgs a{};
+    int S = 0;
+    int64_t nw = 0;
+    int prevK = 0;          // size of the consume list of the last update run (records of the next K-async step)
+    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, loss, ylab;
+    hipStream_t stream = nullptr;
+};
+
+hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int variant, int Kcap, double lr,
+                      uint64_t seed, hipStream_t stream, std::string* msg) {
+    auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
+    if (!model.bf16) return fail(hipErrorInvalidValue, "the MLP runs with bf16 operands only (model.bf16 = 1)");
+    if (m > MP) return fail(hipErrorInvalidValue, "the MLP keeps at most 64 rows per mini-batch");
+    if (model.hidden % BT || model.d % BT) return fail(hipErrorInvalidValue, "the MLP needs hidden % 128 == 0 and d % 128 == 0");
+    if (model.classes > 16) return fail(hipErrorInvalidValue, "at most 16 classes");
+    MlpState* s = new MlpState();
+    s->stream = stream;
+    MlpArgs& a = s->a;
+    a.d = model.d; a.H = model.hidden; a.C = model.classes; a.P = P; a.m = m; a.variant = variant; a.Kcap = Kcap;
+    a.X = model.X; a.y = (const int32_t*)model.y; a.N = (uint32_t)model.N; a.seed = seed; a.lr = (float)lr;
+    s->S = (variant == kAsync) ? P : Kcap;
+    const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
+    s->nw = off2 + n2 + a.C;
+    const size_t S = (size_t)s->S;
+    hipError_t e;
+#define TRY(x) do { e = (x); if (e != hipSuccess) { mlp_destroy(s); return fail(e, #x); } } while (0)
+    TRY(s->params.alloc(sizeof(float) * s->nw));
+    TRY(s->w1r.alloc(2 * (size_t)n1));
+    TRY(s->w2r.alloc(sizeof(float) * n2));
+    TRY(s->xb.alloc(2 * S * MP * a.d));
+    TRY(s->xbt.alloc(2 * S * MP * a.d));
+    TRY(s->hbuf.alloc(sizeof(float) * S * MP * a.H));
+    TRY(s->d1t.alloc(2 * S * MP * a.H));
+    TRY(s->gb1.alloc(sizeof(float) * S * a.H));
+    TRY(s->gw2.alloc(sizeof(float) * S * a.C * a.H));
+    TRY(s->gb2.alloc(sizeof(float) * S * 16));
+    TRY(s->loss.alloc(sizeof(float) * S));
+    TRY(s->ylab.alloc(sizeof(int32_t) * S * MP));
+    TRY(hipMemsetAsync(s->xb.p, 0, 2 * S * MP * a.d, stream));
+    TRY(hipMemsetAsync(s->xbt.p, 0, 2 * S * MP * a.d, stream));
+    TRY(hipMemsetAsync(s->hbuf.p, 0, sizeof(float) * S * MP * a.H, stream));
+    TRY(hipMemsetAsync(s->d1t.p, 0, 2 * S * MP * a.H, stream));
+    TRY(hipMemsetAsync(s->gb1.p, 0, sizeof(float) * S * a.H, stream));
+    TRY(hipMemsetAsync(s->gw2.p, 0, sizeof(float) * S * a.C * a.H, stream));
+    TRY(hipMemsetAsync(s->gb2.p, 0, sizeof(float) * S * 16, stream));
+    TRY(hipMemsetAsync(s->loss.p, 0, sizeof(float) * S, stream));
+    TRY(hipMemsetAsync(s->ylab.p, 0xFF, sizeof(int32_t) * S * MP, stream));
+    a.params = (float*)s->params.p; a.w1r = (unsigned short*)s->w1r.p; a.w2r = (float*)s->w2r.p;
+    a.xb = (unsigned short*)s->xb.p; a.xbt = (unsigned short*)s->xbt.p; a.hbuf = (float*)s->hbuf.p;
+    a.d1t = (unsigned short*)s->d1t.p; a.gb1 = (float*)s->gb1.p; a.gw2 = (float*)s->gw2.p; a.gb2 = (float*)s->gb2.p;
+    a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p;
+    const float bound1 = (float)(1.0 / sqrt((double)a.d)), bound2 = (float)(1.0 / sqrt((double)a.H));
+    hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
+    TRY(hipGetLastError());
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            4 * BT * LDT * 2));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            4 * BT * LDT * 2));
+#undef TRY
+    *out = s;
+    return hipSuccess;
+}
+
+hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n, float* agg_out,
+                           hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg) {
+    auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
+    MlpArgs a = s->a;
+    a.tr = tr;
+    a.agg_out = agg_out;
+    const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
+    // the parameters may have been set from outside since the last segment
+    hipLaunchKernelGGL(mlp_refresh_kernel, dim3(1024), dim3(256), 0, stream, a.params, a.w1r, a.w2r, n1, off2, n2);
+    // K is constant inside a segment; it is read back once
+    std::vector<int32_t> Ks((size_t)n);
+    hipError_t e = hipMemcpyAsync(Ks.data(), tr.K + v0, sizeof(int32_t) * n, hipMemcpyDeviceToHost, stream);
+    if (e != hipSuccess) return fail(e, "reading K of the segment");
+    e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(e, "reading K of the segment");
+    int32_t prevK = 0;
+    if (a.variant == kAsync && v0 > 0) {
+        e = hipMemcpy(&prevK, tr.K + (v0 - 1), sizeof(int32_t), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(e, "reading K of the previous update");
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    (void)hipEventCreate(&e0); (void)hipEventCreate(&e1);
+    (void)hipEventRecord(e0, stream);
+    const size_t lds = 4 * BT * LDT * 2;
+    for (int64_t q = 0; q < n; ++q) {
+        a.v = v0 + q;
+        a.Kv = Ks[(size_t)q];
+        a.nrec = (a.variant == kAsync) ? (a.v == 0 ? a.P : (q == 0 ? prevK : Ks[(size_t)q - 1])) : a.Kv;
+        if (a.Kv < 1 || a.Kv > a.Kcap || a.nrec < 0 || a.nrec > a.P) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return fail(hipErrorInvalidValue, "inconsistent K in the trace"); }
+        if (a.nrec > 0) {
+            hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(mlp_contract_kernel<true>, dim3((a.nrec + 1) / 2, a.H / BT), dim3(256), lds, stream, a);
+            hipLaunchKernelGGL(mlp_layer2_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
+        }
+        hipLaunchKernelGGL(mlp_contract_kernel<false>, dim3(a.H / BT, a.d / BT), dim3(256), lds, stream, a);
+        hipLaunchKernelGGL(mlp_small_update_kernel, dim3(24), dim3(256), 0, stream, a);
+        if (launches) *launches += 1;
+    }
+    (void)hipEventRecord(e1, stream);
+    e = hipStreamSynchronize(stream);
+    float ms = 0.0f;
+    if (e == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms_accum) *ms_accum += ms;
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail(e, "running the segment");
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(e, "launching the segment");
+    (void)ws;
+    return hipSuccess;
+}
+
+float* mlp_params(MlpState* s) { return s ? (float*)s->params.p : nullptr; }
+
+void mlp_destroy(MlpState* s) {
+    if (!s) return;
+    DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->loss, &s->ylab};
+    for (DevMem* b : bufs) b->release();
+    delete s;
+}
+
 }  // namespace ssgd

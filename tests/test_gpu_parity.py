@@ -353,3 +353,85 @@ def test_mc_closed_forms_at_scale(ssgd, torch_cuda):
     s = ssgd.runtime_mc("k_async", P, 1, P, ssgd.delay_dist("shifted_exp", 0.2, 1.0), n, L, seed=2)
     assert np.all(np.abs(s["mean"][:, 0] - (0.2 + H)) <= 5 * np.sqrt(V / n))
     assert np.all(s["mean"][:, 1:] <= (0.2 + H)[:, None] + 5 * np.sqrt(s["var"][:, 1:] / n))
+
+
+# ---------------------------------------------------------------------------------------------
+# Two-layer ReLU network (bf16 operands, fp32 accumulation).  Tolerances: the oracle accumulates the
+# bf16 products in fp64, the MFMA units in fp32 (relative 1e-6 per dot product of length d); what makes
+# the difference visible are decisions taken on those sums -- a hidden unit whose pre-activation is
+# within that error of zero switches its ReLU mask, and a delta1 value within it of a bf16 rounding
+# boundary moves by one bf16 ulp (2^-8 relative) -- each a rare, isolated change of one entry.
+MLP_GRAD_TOL = 2e-3
+MLP_PARAM_TOL = 2e-3
+
+
+def _mlp_pair(ssgd, oracle, torch, X, y, P, K, m, variant, spec, lr, classes, hidden, seed=0, adasync=None):
+    gd, od = dist_pair(ssgd, oracle, spec)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    ctx = ssgd.Context("mlp2", Xd, yd, P, K, m, variant, gd, lr, seed=seed, classes=classes, hidden=hidden, bf16=1,
+                       adasync=adasync)
+    tr = oracle.Trainer(oracle.Model("mlp2", X, y, classes=classes, hidden=hidden, bf16=1), P, K, m, variant, od, lr,
+                        seed=seed, adasync=adasync)
+    return ctx, tr
+
+
+def test_mlp_initial_parameters_bit_exact(ssgd, oracle, torch_cuda):
+    X, y = synth.mixture_data(600, 256, 5, seed=2)
+    ctx, tr = _mlp_pair(ssgd, oracle, torch_cuda, X, y, 4, 2, 16, "k_sync", ("exp", 1.0), 0.05, 5, 128, seed=11)
+    assert np.array_equal(ctx.params(), tr.params())
+    ctx.close()
+
+
+@pytest.mark.parametrize("variant,P,K,m,d,classes,hidden", [
+    ("k_sync", 4, 2, 64, 256, 10, 128),
+    ("k_sync", 6, 3, 20, 128, 3, 256),        # m < 64: zero rows in every block
+    ("k_async", 6, 2, 32, 384, 10, 128),
+])
+def test_mlp_gradients_teacher_forced(ssgd, oracle, torch_cuda, variant, P, K, m, d, classes, hidden):
+    """Every update's averaged gradient against the oracle's.  K-sync is teacher-forced (the oracle's iterate is
+    loaded before each step); K-async runs free, its in-flight factors depend on earlier iterates."""
+    torch = torch_cuda
+    X, y = synth.mixture_data(2000, d, classes, seed=4)
+    ctx, tr = _mlp_pair(ssgd, oracle, torch, X, y, P, K, m, variant, ("shifted_exp", 0.5, 1.0), 0.05, classes, hidden, seed=5)
+    agg = torch.zeros(ctx.nw, dtype=torch.float32, device="cuda")
+    worst = 0.0
+    for j in range(25):
+        if variant == "k_sync":
+            ctx.set_params(tr.params())
+        ctx.step(agg)
+        worst = max(worst, rel(agg.cpu().numpy(), tr.step()))
+    print(f"worst per-step MLP gradient error {worst:.3e}")
+    assert worst <= MLP_GRAD_TOL, worst
+    assert_trace_equal(ctx.trace(), tr.trace())
+    ctx.close()
+
+
+def test_mlp_kasync_training_run(ssgd, oracle, torch_cuda):
+    """Scaled copy of config 4 (d=512, hidden 128, 10 classes, P=32, m=64, K=4): 150 updates free-running."""
+    X, y = synth.mixture_data(4000, 512, 10, seed=6)
+    ctx, tr = _mlp_pair(ssgd, oracle, torch_cuda, X, y, 32, 4, 64, "k_async", ("shifted_exp", 0.5, 1.0), 0.05, 10, 128, seed=1)
+    ctx.run(150)
+    tr.run(150)
+    assert_trace_equal(ctx.trace(), tr.trace())
+    pr = rel(ctx.params(), tr.params())
+    print(f"MLP parameter error after 150 updates {pr:.3e}")
+    assert pr <= MLP_PARAM_TOL, pr
+    assert np.allclose(ctx.trace()["loss"], tr.trace()["loss"], rtol=5e-3, atol=1e-4)
+    ctx.close()
+
+
+def test_mlp_adasync_plateau_doubling(ssgd, oracle, torch_cuda):
+    """AdaSync on the MLP (config 4's controller, scaled: windows of 20 updates, K 2 -> 16, P=16): K changes
+    at the same updates as in the oracle, and the schedule stays bit-exact through the changes."""
+    X, y = synth.mixture_data(3000, 256, 10, seed=8)
+    ada = dict(mode=1, K0=2, Kmax=16, window=20, rel_tol=0.01)
+    ctx, tr = _mlp_pair(ssgd, oracle, torch_cuda, X, y, 16, 2, 32, "k_async", ("shifted_exp", 0.5, 1.0), 0.05, 10, 128,
+                        seed=2, adasync=ada)
+    ctx.run(160)
+    tr.run(160)
+    g, o = ctx.trace(), tr.trace()
+    assert np.array_equal(g["K"], o["K"]), (g["K"], o["K"])
+    assert len(set(g["K"].tolist())) >= 2      # K did change
+    assert_trace_equal(g, o)
+    assert rel(ctx.params(), tr.params()) <= 5e-3
+    ctx.close()
