@@ -30,7 +30,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int MP = 64;         // rows kept per worker (m <= 64; the rest is zero)
-constexpr int BT = 128;        // output tile of the contraction kernel
 constexpr int KT = 64;         // contraction depth per stage
 constexpr int LDT = KT + 8;    // padded LDS row (bf16 elements): 144 bytes, keeps 16-byte reads conflict-poor
 
@@ -62,6 +61,7 @@ struct MlpArgs {
     float* gb1;                // [S][H]       sum over the mini-batch of delta1
     float* gw2;                // [S][C][H]    sum of delta2 (x) h
     float* gb2;                // [S][16]      sum of delta2
+    float* d2;                 // [S][MP][16]  delta2 of every row
     float* loss;               // [S]          sum of the sample losses
     int32_t* ylab;             // [S][MP]      labels (-1: no sample)
     float* agg_out;            // nullable
@@ -123,8 +123,13 @@ __global__ __launch_bounds__(256) void mlp_gather_kernel(MlpArgs a) {
 // ---- contraction: C[M x N] = sum over stages of A_stage[M x 64] B_stage[N x 64]^T, bf16 MFMA ----
 // FWD: rows = (record, sample) of the compute list, columns = hidden units, depth = d.
 // BWD: rows = hidden units, columns = input features, depth = 64 samples of every consumed slot.
-template <bool FWD>
+// BT x BT output tile per workgroup (128: four waves of 64 x 64; 64: four waves of 32 x 32, for launches
+// that would otherwise leave most CUs idle).
+template <bool FWD, int BT>
 __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
+    constexpr int WT = BT / 2;          // rows and columns per wave
+    constexpr int NF = WT / 32;         // 32 x 32 MFMA tiles per wave and dimension
+    constexpr int LP = BT / 32;         // 16-byte loads per thread, operand and stage
     extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
     unsigned short* As = lds;                       // [2][BT][LDT]
     unsigned short* Bs = lds + 2 * BT * LDT;        // [2][BT][LDT]
@@ -133,33 +138,31 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     const int d = a.d, H = a.H;
     const int stages = FWD ? d / KT : a.Kv;
 
-    // global -> LDS: 128 rows x 8 chunks of 16 bytes per operand; thread -> chunk tid % 8 of rows tid / 8 + 32 i
+    // global -> LDS: BT rows x 8 chunks of 16 bytes per operand; thread -> chunk tid % 8 of rows tid / 8 + 32 i
     const int lchunk = tid & 7, lrow = tid >> 3;
-    int slot_of_pair[2] = {0, 0};
+    constexpr int RPT = BT / MP;        // records per row tile (FWD)
+    int slot_of[RPT];
     if (FWD) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int r = 2 * bm + q;
+        for (int q = 0; q < RPT; ++q) {
+            const int r = RPT * bm + q;
             int worker = 0, ordinal = 0, slot = 0;
             if (r < a.nrec) record_of(a, r, worker, ordinal, slot);
-            slot_of_pair[q] = slot;
+            slot_of[q] = slot;
         }
     }
     auto a_ptr = [&](int row, int stage) -> const unsigned short* {
-        if (FWD) {
-            const int slot = slot_of_pair[row >> 6];
-            return a.xb + ((int64_t)slot * MP + (row & 63)) * d + stage * KT;
-        }
+        if (FWD) return a.xb + ((int64_t)slot_of[row / MP] * MP + (row % MP)) * d + stage * KT;
         return a.d1t + ((int64_t)consumed_slot(a, stage) * H + bm * BT + row) * MP;
     };
     auto b_ptr = [&](int row, int stage) -> const unsigned short* {
         if (FWD) return a.w1r + (int64_t)(bn * BT + row) * d + stage * KT;
         return a.xbt + ((int64_t)consumed_slot(a, stage) * d + bn * BT + row) * MP;
     };
-    u16x8 ra[4], rb[4];
+    u16x8 ra[LP], rb[LP];
     auto fetch = [&](int stage) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < LP; ++i) {
             const int row = lrow + 32 * i;
             ra[i] = *reinterpret_cast<const u16x8*>(a_ptr(row, stage) + 8 * lchunk);
             rb[i] = *reinterpret_cast<const u16x8*>(b_ptr(row, stage) + 8 * lchunk);
@@ -167,20 +170,19 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     };
     auto stash = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < LP; ++i) {
             const int row = lrow + 32 * i;
             *reinterpret_cast<u16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = ra[i];
             *reinterpret_cast<u16x8*>(Bs + (buf * BT + row) * LDT + 8 * lchunk) = rb[i];
         }
     };
 
-    // wave (wm, wn) computes a 64 x 64 block as 2 x 2 MFMA tiles of 32 x 32
     const int wm = wave >> 1, wn = wave & 1;
-    f32x16 acc[2][2];
+    f32x16 acc[NF][NF];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NF; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NF; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
@@ -192,144 +194,174 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
         if (st + 1 < stages) fetch(st + 1);
 #pragma unroll
         for (int kk = 0; kk < KT / 16; ++kk) {
-            bf16x8 fa[2], fb[2];
+            bf16x8 fa[NF], fb[NF];
             // operand layout of the 32x32x16 MFMA: lane -> row lane % 32, depth 8 (lane / 32) .. + 7
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8*>(As + (buf * BT + wm * 64 + i * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
+            for (int i = 0; i < NF; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8*>(As + (buf * BT + wm * WT + i * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8*>(Bs + (buf * BT + wn * 64 + j * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
+            for (int j = 0; j < NF; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8*>(Bs + (buf * BT + wn * WT + j * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < NF; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < NF; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
         if (st + 1 < stages) stash(buf ^ 1);
         __syncthreads();
     }
 
+    // The result goes through LDS so that the global accesses of the epilogue run along rows.
     // result layout: element e of lane -> row 8 (e / 4) + 4 (lane / 32) + e % 4, column lane % 32
-    const float scale = a.lr / (float)a.Kv;
+    constexpr int LDC = BT + 4;
+    float* Cs = reinterpret_cast<float*>(lds);      // [BT][LDC], fits in the operand buffers
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NF; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NF; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                const int col = wn * 64 + j * 32 + (lane & 31);
-                const float v = acc[i][j][e];
-                if (FWD) {
-                    const int r = 2 * bm + (row >> 6);
-                    if (r < a.nrec) {
-                        const int n = bn * BT + col;
-                        const float z = v + a.params[(int64_t)H * d + n];
-                        a.hbuf[((int64_t)slot_of_pair[row >> 6] * MP + (row & 63)) * H + n] = z > 0.0f ? z : 0.0f;
-                    }
-                } else {
-                    const int64_t q = (int64_t)(bm * BT + row) * d + bn * BT + col;
-                    const float w = a.params[q] - scale * v;
-                    a.params[q] = w;
-                    a.w1r[q] = bf16_bits(w);
-                    if (a.agg_out) a.agg_out[q] = v / (float)a.Kv;
-                }
+                const int row = wm * WT + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const int col = wn * WT + j * 32 + (lane & 31);
+                Cs[row * LDC + col] = acc[i][j][e];
             }
+    __syncthreads();
+    const float scale = a.lr / (float)a.Kv, invK = 1.0f / (float)a.Kv;
+    constexpr int C4 = BT / 4;           // float4 groups per row
+    for (int q = tid; q < BT * C4; q += 256) {
+        const int row = q / C4, c4 = q % C4;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(Cs + row * LDC + 4 * c4);
+        if (FWD) {
+            const int r = RPT * bm + row / MP;
+            if (r < a.nrec) {
+                const int n = bn * BT + 4 * c4;
+                const f32x4 b1 = *reinterpret_cast<const f32x4*>(a.params + (int64_t)H * d + n);
+                f32x4 h;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) { const float z = v[c] + b1[c]; h[c] = z > 0.0f ? z : 0.0f; }
+                *reinterpret_cast<f32x4*>(a.hbuf + ((int64_t)slot_of[row / MP] * MP + (row % MP)) * H + n) = h;
+            }
+        } else {
+            const int64_t p = (int64_t)(bm * BT + row) * d + bn * BT + 4 * c4;
+            f32x4 w = *reinterpret_cast<const f32x4*>(a.params + p);
+            unsigned short wb[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { w[c] -= scale * v[c]; wb[c] = bf16_bits(w[c]); }
+            *reinterpret_cast<f32x4*>(a.params + p) = w;
+            *reinterpret_cast<uint2*>(a.w1r + p) = make_uint2((uint32_t)wb[0] | ((uint32_t)wb[1] << 16), (uint32_t)wb[2] | ((uint32_t)wb[3] << 16));
+            if (a.agg_out) *reinterpret_cast<f32x4*>(a.agg_out + p) = v * invK;
+        }
+    }
 }
 
-// ---- layer 2, softmax, delta2, delta1: one workgroup per record --------------------------------
-__global__ __launch_bounds__(256) void mlp_layer2_kernel(MlpArgs a) {
-    __shared__ float d2s[MP][16];
-    __shared__ float red[MP];
-    const int r = blockIdx.x, tid = threadIdx.x;
+// ---- layer 2 and softmax: one workgroup per record; wave w takes rows 16 w .. 16 w + 15 -------------
+// Z2 = H W2^T is a 16 x 16 x H contraction per wave on the fp32 MFMA units (H is not rounded, so this
+// layer runs in fp32): operand lane -> (row or class lane % 16, 4 hidden units starting at 16 kk + 4 (lane / 16)).
+__global__ __launch_bounds__(256) void mlp_output_kernel(MlpArgs a) {
+    __shared__ float wsum[4];
+    const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int H = a.H, C = a.C, m = a.m;
     int worker, ordinal, slot;
     record_of(a, r, worker, ordinal, slot);
-    const float* hrow = a.hbuf + (int64_t)slot * MP * H;
-    const float* b2 = a.params + (int64_t)H * a.d + H + (int64_t)C * H;
-    // phase 1: four threads per row, each a quarter of the hidden units
-    {
-        const int s = tid >> 2, qd = tid & 3;
-        float z[16];
+    const int cls = lane & 15, kq = lane >> 4;
+    const float* hp = a.hbuf + ((int64_t)slot * MP + 16 * wave + (lane & 15)) * H + 4 * kq;
+    const float* wp = a.w2r + (int64_t)min(cls, C - 1) * H + 4 * kq;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int kk = 0; kk < H / 16; ++kk) {
+        const f32x4 hv = *reinterpret_cast<const f32x4*>(hp + 16 * kk);
+        const f32x4 wv = *reinterpret_cast<const f32x4*>(wp + 16 * kk);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv.x, wv.x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv.y, wv.y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv.z, wv.z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv.w, wv.w, acc, 0, 0, 0);
+    }
+    // result: lane holds class lane % 16 of rows 4 (lane / 16) + e, e < 4 (classes past C repeat class C-1: unused)
+    const float b2 = a.params[(int64_t)H * a.d + H + (int64_t)C * H + min(cls, C - 1)];
+    float lsum = 0.0f;
 #pragma unroll
-        for (int c = 0; c < 16; ++c) z[c] = 0.0f;
-        const int per = H / 4;
-        for (int j = qd * per; j < (qd + 1) * per; ++j) {
-            const float h = hrow[(int64_t)s * H + j];
-#pragma unroll
-            for (int c = 0; c < 16; ++c)
-                if (c < C) z[c] += a.w2r[c * H + j] * h;
-        }
-#pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            z[c] += __shfl_xor(z[c], 1, 64);
-            z[c] += __shfl_xor(z[c], 2, 64);
-        }
+    for (int e = 0; e < 4; ++e) {
+        const int s = 16 * wave + 4 * kq + e;
         const int lab = a.ylab[slot * MP + s];
         const bool ok = s < m && lab >= 0;
-        float zmax = -3.0e38f;
+        const float z = acc[e] + b2;
+        float zmax = cls < C ? z : -3.0e38f;
 #pragma unroll
-        for (int c = 0; c < 16; ++c)
-            if (c < C) { z[c] += b2[c]; zmax = fmaxf(zmax, z[c]); }
-        float den = 0.0f;
+        for (int o = 8; o >= 1; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 64));
+        const float ex = cls < C ? expf(z - zmax) : 0.0f;
+        float den = ex;
 #pragma unroll
-        for (int c = 0; c < 16; ++c)
-            if (c < C) den += expf(z[c] - zmax);
-        float ls = 0.0f;
+        for (int o = 8; o >= 1; o >>= 1) den += __shfl_xor(den, o, 64);
+        float dv = 0.0f;
+        if (cls < C && ok) {
+            dv = ex / den - (cls == lab ? 1.0f : 0.0f);
+            if (cls == lab) lsum += -(z - zmax - logf(den));
+        }
+        a.d2[(slot * MP + s) * 16 + cls] = dv;       // zero past C and for rows without a sample
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) lsum += __shfl_xor(lsum, o, 64);
+    if (lane == 0) wsum[wave] = lsum;
+    __syncthreads();
+    if (tid == 0) a.loss[slot] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+// ---- delta1 = (W2^T delta2) * [H > 0], second-layer gradient: workgroup = (record, 64 hidden units) ----
+// thread -> hidden unit jb * 64 + tid % 64, rows 16 (tid / 64) .. + 15
+__global__ __launch_bounds__(256) void mlp_delta1_kernel(MlpArgs a) {
+    __shared__ float d2s[MP][16];
+    __shared__ float part[3][64][17];
+    const int r = blockIdx.x, jb = blockIdx.y, tid = threadIdx.x;
+    const int H = a.H, C = a.C;
+    int worker, ordinal, slot;
+    record_of(a, r, worker, ordinal, slot);
+    for (int q = tid; q < MP * 16; q += 256) d2s[q >> 4][q & 15] = a.d2[slot * MP * 16 + q];
+    const int jl = tid & 63, rq = tid >> 6, j = jb * 64 + jl;
+    const float* hrow = a.hbuf + ((int64_t)slot * MP + 16 * rq) * H + j;
+    float h[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) h[e] = hrow[(int64_t)e * H];
+    const float inv_m = 1.0f / (float)a.m;
+    float w2c[16], gw[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) { w2c[c] = (c < C) ? a.w2r[c * H + j] : 0.0f; gw[c] = 0.0f; }
+    __syncthreads();
+    float g1 = 0.0f;
+    u16x8 pack[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int s = 16 * rq + e;
+        float d1 = 0.0f;
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
-            float dv = 0.0f;
-            if (c < C && ok) {
-                dv = expf(z[c] - zmax) / den - (c == lab ? 1.0f : 0.0f);
-                if (c == lab) ls = -(z[c] - zmax - logf(den));
-            }
-            if (qd == 0) d2s[s][c] = dv;
+            const float dv = d2s[s][c];          // zero past C
+            d1 += w2c[c] * dv;
+            gw[c] += dv * h[e];
         }
-        if (qd == 0) red[s] = ok ? ls : 0.0f;
+        if (!(h[e] > 0.0f)) d1 = 0.0f;
+        g1 += d1;
+        pack[e >> 3][e & 7] = bf16_bits(d1 * inv_m);
+    }
+    unsigned short* dst = a.d1t + ((int64_t)slot * H + j) * MP + 16 * rq;
+    *reinterpret_cast<u16x8*>(dst) = pack[0];
+    *reinterpret_cast<u16x8*>(dst + 8) = pack[1];
+    // the four row quarters are added in a fixed order
+    if (rq > 0) {
+        part[rq - 1][jl][16] = g1;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) part[rq - 1][jl][c] = gw[c];
     }
     __syncthreads();
-    if (tid < 16) {
+    if (rq == 0) {
+        a.gb1[slot * H + j] = ((g1 + part[0][jl][16]) + part[1][jl][16]) + part[2][jl][16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+            if (c < C) a.gw2[((int64_t)slot * C + c) * H + j] = ((gw[c] + part[0][jl][c]) + part[1][jl][c]) + part[2][jl][c];
+    }
+    if (jb == 0 && tid < 16) {
         float sum = 0.0f;
         for (int s = 0; s < MP; ++s) sum += d2s[s][tid];
         a.gb2[slot * 16 + tid] = sum;
-    }
-    if (tid == 16) {
-        float sum = 0.0f;
-        for (int s = 0; s < MP; ++s) sum += red[s];
-        a.loss[slot] = sum;
-    }
-    // phase 2: one thread per hidden unit (H / 256 units each): delta1 over the rows, second-layer gradient
-    const float inv_m = 1.0f / (float)m;
-    for (int j = tid; j < H; j += 256) {
-        float w2c[16], gw[16];
-#pragma unroll
-        for (int c = 0; c < 16; ++c) { w2c[c] = (c < C) ? a.w2r[c * H + j] : 0.0f; gw[c] = 0.0f; }
-        float g1 = 0.0f;
-        unsigned short* dst = a.d1t + ((int64_t)slot * H + j) * MP;
-        for (int s0 = 0; s0 < MP; s0 += 8) {
-            u16x8 pack;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int s = s0 + e;
-                const float h = hrow[(int64_t)s * H + j];
-                float d1 = 0.0f;
-#pragma unroll
-                for (int c = 0; c < 16; ++c) {
-                    const float dv = d2s[s][c];
-                    d1 += w2c[c] * dv;
-                    gw[c] += dv * h;
-                }
-                if (!(h > 0.0f)) d1 = 0.0f;
-                g1 += d1;
-                pack[e] = bf16_bits(d1 * inv_m);
-            }
-            *reinterpret_cast<u16x8*>(dst + s0) = pack;
-        }
-        a.gb1[slot * H + j] = g1;
-#pragma unroll
-        for (int c = 0; c < 16; ++c)
-            if (c < C) a.gw2[((int64_t)slot * C + c) * H + j] = gw[c];
     }
 }
 
@@ -387,6 +419,9 @@ __global__ void mlp_init_kernel(float* params, uint64_t seed, int64_t nw, int64_
     }
 }
 
+// operand double buffer; the epilogue's fp32 tile [BT][BT + 4] fits inside it
+size_t contract_lds(int bt) { return (size_t)4 * bt * LDT * 2; }
+
 struct DevMem {
     void* p = nullptr;
     hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 16); }
@@ -400,7 +435,7 @@ struct MlpState {
     int S = 0;
     int64_t nw = 0;
     int prevK = 0;          // size of the consume list of the last update run (records of the next K-async step)
-    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, loss, ylab;
+    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab;
     hipStream_t stream = nullptr;
 };
 
@@ -409,7 +444,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
     if (!model.bf16) return fail(hipErrorInvalidValue, "the MLP runs with bf16 operands only (model.bf16 = 1)");
     if (m > MP) return fail(hipErrorInvalidValue, "the MLP keeps at most 64 rows per mini-batch");
-    if (model.hidden % BT || model.d % BT) return fail(hipErrorInvalidValue, "the MLP needs hidden % 128 == 0 and d % 128 == 0");
+    if (model.hidden % 128 || model.d % 128) return fail(hipErrorInvalidValue, "the MLP needs hidden % 128 == 0 and d % 128 == 0");
     if (model.classes > 16) return fail(hipErrorInvalidValue, "at most 16 classes");
     MlpState* s = new MlpState();
     s->stream = stream;
@@ -432,6 +467,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(s->gb1.alloc(sizeof(float) * S * a.H));
     TRY(s->gw2.alloc(sizeof(float) * S * a.C * a.H));
     TRY(s->gb2.alloc(sizeof(float) * S * 16));
+    TRY(s->d2.alloc(sizeof(float) * S * MP * 16));
     TRY(s->loss.alloc(sizeof(float) * S));
     TRY(s->ylab.alloc(sizeof(int32_t) * S * MP));
     TRY(hipMemsetAsync(s->xb.p, 0, 2 * S * MP * a.d, stream));
@@ -446,14 +482,14 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     a.params = (float*)s->params.p; a.w1r = (unsigned short*)s->w1r.p; a.w2r = (float*)s->w2r.p;
     a.xb = (unsigned short*)s->xb.p; a.xbt = (unsigned short*)s->xbt.p; a.hbuf = (float*)s->hbuf.p;
     a.d1t = (unsigned short*)s->d1t.p; a.gb1 = (float*)s->gb1.p; a.gw2 = (float*)s->gw2.p; a.gb2 = (float*)s->gb2.p;
-    a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p;
+    a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p; a.d2 = (float*)s->d2.p;
     const float bound1 = (float)(1.0 / sqrt((double)a.d)), bound2 = (float)(1.0 / sqrt((double)a.H));
     hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
     TRY(hipGetLastError());
-    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            4 * BT * LDT * 2));
-    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            4 * BT * LDT * 2));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
 #undef TRY
     *out = s;
     return hipSuccess;
@@ -482,7 +518,6 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
     hipEvent_t e0 = nullptr, e1 = nullptr;
     (void)hipEventCreate(&e0); (void)hipEventCreate(&e1);
     (void)hipEventRecord(e0, stream);
-    const size_t lds = 4 * BT * LDT * 2;
     for (int64_t q = 0; q < n; ++q) {
         a.v = v0 + q;
         a.Kv = Ks[(size_t)q];
@@ -490,10 +525,18 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
         if (a.Kv < 1 || a.Kv > a.Kcap || a.nrec < 0 || a.nrec > a.P) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return fail(hipErrorInvalidValue, "inconsistent K in the trace"); }
         if (a.nrec > 0) {
             hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
-            hipLaunchKernelGGL(mlp_contract_kernel<true>, dim3((a.nrec + 1) / 2, a.H / BT), dim3(256), lds, stream, a);
-            hipLaunchKernelGGL(mlp_layer2_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
+            // small tiles while the large ones would not fill the chip
+            if (((a.nrec + 1) / 2) * (a.H / 128) >= 192)
+                hipLaunchKernelGGL((mlp_contract_kernel<true, 128>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
+            else
+                hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
+            hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
         }
-        hipLaunchKernelGGL(mlp_contract_kernel<false>, dim3(a.H / BT, a.d / BT), dim3(256), lds, stream, a);
+        if (a.Kv >= 64)
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 128>), dim3(a.H / 128, a.d / 128), dim3(256), contract_lds(128), stream, a);
+        else
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64), dim3(256), contract_lds(64), stream, a);
         hipLaunchKernelGGL(mlp_small_update_kernel, dim3(24), dim3(256), 0, stream, a);
         if (launches) *launches += 1;
     }
@@ -513,7 +556,7 @@ float* mlp_params(MlpState* s) { return s ? (float*)s->params.p : nullptr; }
 
 void mlp_destroy(MlpState* s) {
     if (!s) return;
-    DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->loss, &s->ylab};
+    DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss, &s->ylab};
     for (DevMem* b : bufs) b->release();
     delete s;
 }
