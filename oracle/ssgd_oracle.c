@@ -17,6 +17,13 @@
  * any conforming implementation reproduces them bit for bit.  Simulated
  * wall-clock times are fp64.
  *
+ * Parity unpinned (nothing outside this file fixes the values; the tests pin
+ * everything else against closed forms, brute force, known-answer vectors or
+ * textbook special cases): the K-async inter-update times of orc_runtime_mc
+ * under Pareto delays beyond the first update of a chain; the long-horizon
+ * trajectory of the two-layer network (pinned only through its per-step
+ * gradients, finite differences and a scaled-down run).
+ *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fPIC -shared
  */
 #include <math.h>
