@@ -9,7 +9,6 @@
 namespace ssgd {
 namespace {
 
-constexpr int NQ = kMaxWorkers / 64;
 
 struct Best { double key; int32_t id; };
 
@@ -17,17 +16,45 @@ __device__ __forceinline__ bool before(double ka, int32_t ia, double kb, int32_t
     return ka < kb || (ka == kb && ia < ib);   // ties go to the lower worker id
 }
 
-// Smallest (key, id) over the wavefront, known to every lane afterwards.
-__device__ __forceinline__ Best wave_min(Best b) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const double ok = __shfl_xor(b.key, off, 64);
-        const int32_t oi = __shfl_xor(b.id, off, 64);
-        if (before(ok, oi, b.key, b.id)) { b.key = ok; b.id = oi; }
-    }
-    return b;
+// Smallest (key, id) over the first `width` lanes (a power of two covering every worker), known to every
+// lane afterwards.  The butterfly carries the key only; the owner is found with a ballot, and the rare
+// tie between lanes goes to the lowest worker id.
+template <int CTRL>
+__device__ __forceinline__ double dpp_fetch(double k) {
+    const long long b = __double_as_longlong(k);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)((unsigned long long)b >> 32), CTRL, 0xF, 0xF, false);
+    return __longlong_as_double((long long)(((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo));
 }
 
+__device__ __forceinline__ Best wave_min(Best b, int width) {
+    double k = b.key;
+    // inside a row of 16 lanes the exchange is a data-parallel-primitive move (no LDS round trip):
+    // lane ^ 1, lane ^ 2, then the mirrored lane of the other half of 8, then of 16
+    if (width > 1) { const double o = dpp_fetch<0xB1>(k); k = o < k ? o : k; }     // quad_perm [1,0,3,2]
+    if (width > 2) { const double o = dpp_fetch<0x4E>(k); k = o < k ? o : k; }     // quad_perm [2,3,0,1]
+    if (width > 4) { const double o = dpp_fetch<0x141>(k); k = o < k ? o : k; }    // row_half_mirror
+    if (width > 8) { const double o = dpp_fetch<0x140>(k); k = o < k ? o : k; }    // row_mirror
+    for (int off = 16; off < width; off <<= 1) {
+        const double ok = __shfl_xor(k, off, 64);
+        k = ok < k ? ok : k;
+    }
+    const long long kb = __double_as_longlong(k);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)kb);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((unsigned long long)kb >> 32));
+    const double kmin = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+    unsigned long long mask = __ballot(b.key == kmin && b.id != 0x7FFFFFFF);
+    int best = 0x7FFFFFFF;
+    while (mask) {
+        const int l = __builtin_ctzll(mask);
+        mask &= mask - 1;
+        const int id = __builtin_amdgcn_readlane(b.id, l);
+        best = id < best ? id : best;
+    }
+    return Best{kmin, best};
+}
+
+template <int NQ>
 __device__ __forceinline__ Best local_min(const double (&key)[NQ], uint32_t skip, int lane, int P) {
     Best b{__longlong_as_double(0x7FF0000000000000LL), 0x7FFFFFFF};
 #pragma unroll
@@ -38,6 +65,9 @@ __device__ __forceinline__ Best local_min(const double (&key)[NQ], uint32_t skip
     return b;
 }
 
+// NQ: workers per lane (1 while P <= 64).  TABLE: delays come from a table in memory; kept out of the common
+// instantiation, whose loop then holds no load and never waits for its own trace stores.
+template <int NQ, bool TABLE>
 __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
     const int lane = threadIdx.x;
     const int rep = a.replica0 + blockIdx.x;
@@ -49,6 +79,12 @@ __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
     int32_t* tr_tau = a.tr.tau + (int64_t)rep * cap * Kcap;
     int32_t* tr_ord = a.tr.ord + (int64_t)rep * cap * Kcap;
 
+    auto draw_delay = [&](uint32_t worker, uint32_t ordinal, uint32_t version) -> float {
+        if constexpr (TABLE) return delay(a.dist, a.seed, kDelay, 0, rep, P, a.table_ord, worker, ordinal, version);
+        else return delay_from_bits(a.dist, draw(a.seed, kDelay, 0, rep, worker, ordinal, version).x);
+    };
+    int width = 1;
+    while (width < P && width < 64) width <<= 1;
     const int K = a.ws.curK[rep];
     double clock = a.ws.clock[rep];
     double key[NQ];
@@ -79,12 +115,12 @@ __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
             for (int q = 0; q < NQ; ++q) {
                 const int w = lane + 64 * q;
                 ord[q] = 0;
-                if (w < P) key[q] = (double)delay(a.dist, a.seed, kDelay, 0, rep, P, a.table_ord, w, 0, ver);
+                if (w < P) key[q] = (double)draw_delay(w, 0, ver);
             }
             uint32_t taken = 0;
             double last = 0.0;
             for (int l = 0; l < K; ++l) {
-                const Best b = wave_min(local_min(key, taken, lane, P));
+                const Best b = wave_min(local_min(key, taken, lane, P), width);
                 last = b.key;
                 if ((b.id & 63) == lane) {
                     const int q = b.id >> 6;
@@ -98,18 +134,26 @@ __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
                             // K-batch-sync: the worker starts its next mini-batch at the same w_j
                             ord[qq] += 1;
                             if (l + 1 < K)
-                                key[qq] = key[qq] + (double)delay(a.dist, a.seed, kDelay, 0, rep, P, a.table_ord,
-                                                                  b.id, ord[qq], ver);
+                                key[qq] = key[qq] + (double)draw_delay(b.id, ord[qq], ver);
                         }
                     }
                 }
             }
             t_new = clock + last;
         } else {
-            // K-async: the K earliest finishers contribute; only they restart, at t_{j+1}
+            // K-async: the K earliest finishers contribute; only they restart, at t_{j+1}.  The delay a
+            // worker would draw if it restarted now depends on (worker, version) only, so every lane
+            // draws it up front, off the selection's dependency chain.
+            double nd[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const int w = lane + 64 * q;
+                nd[q] = 0.0;
+                if (w < P) nd[q] = (double)draw_delay(w, 0, ver + 1u);
+            }
             uint32_t taken = 0;
             for (int l = 0; l < K; ++l) {
-                const Best b = wave_min(local_min(key, taken, lane, P));
+                const Best b = wave_min(local_min(key, taken, lane, P), width);
                 t_new = b.key;
                 if ((b.id & 63) == lane) {
                     const int q = b.id >> 6;
@@ -124,9 +168,8 @@ __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
                 if (!((taken >> q) & 1u)) continue;
-                const int w = lane + 64 * q;
                 tau[q] = (int32_t)(j + 1);
-                key[q] = t_new + (double)delay(a.dist, a.seed, kDelay, 0, rep, P, a.table_ord, w, 0, ver + 1u);
+                key[q] = t_new + nd[q];
             }
         }
         if (lane == 0) { tr_t[j] = t_new; tr_K[j] = K; }
@@ -194,7 +237,14 @@ __global__ void adasync_kernel(AdaArgs a, int replicas) {
 }  // namespace
 
 void launch_schedule(const SchedArgs& a, int replicas, hipStream_t s) {
-    hipLaunchKernelGGL(schedule_kernel, dim3(replicas), dim3(64), 0, s, a);
+    const bool table = a.dist.kind == 3;
+    if (a.P <= 64) {
+        if (table) hipLaunchKernelGGL((schedule_kernel<1, true>), dim3(replicas), dim3(64), 0, s, a);
+        else hipLaunchKernelGGL((schedule_kernel<1, false>), dim3(replicas), dim3(64), 0, s, a);
+    } else {
+        if (table) hipLaunchKernelGGL((schedule_kernel<kMaxWorkers / 64, true>), dim3(replicas), dim3(64), 0, s, a);
+        else hipLaunchKernelGGL((schedule_kernel<kMaxWorkers / 64, false>), dim3(replicas), dim3(64), 0, s, a);
+    }
 }
 
 void launch_adasync(const AdaArgs& a, int replicas, hipStream_t s) {
