@@ -53,7 +53,7 @@ struct ssgd_ctx {
     DevBuf tr_t, tr_loss, tr_K, tr_sel, tr_tau, tr_ord;
     WorkerState ws{};
     DevBuf ws_finish, ws_tau, ws_ord, ws_clock, ws_curK, ws_winprev, ws_winidx, ws_F0, ws_intstart, ws_crossed, ws_ndone;
-    DevBuf params, park, park_small, zpart, arrive, abort_flag, xcc_ids, prof;
+    DevBuf params, park, park_small, zpart, zx, arrive, abort_flag, xcc_ids, prof;
     int resident_groups = 0;
     size_t lds_bytes = 0;
     MlpState* mlp = nullptr;
@@ -176,6 +176,7 @@ ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, boo
     const int resident = tile ? c->tile_resident_groups : c->resident_groups;
     const int per_launch = std::max(1, 8 * ((resident / 8) / c->G));
     HIP_OK(c, hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * c->R, c->stream));
+    if (tile) HIP_OK(c, hipMemsetAsync(c->zx.p, 0xFF, sizeof(uint32_t) * 3 * 1024 * (size_t)c->R * c->G, c->stream));
     if (getenv("SSGD_DEBUG"))
         fprintf(stderr, "ssgd launch: v0=%lld n=%lld tile=%d resident=%d per_launch=%d R=%d\n", (long long)v0, (long long)n,
                 (int)tile, resident, per_launch, c->R);
@@ -215,6 +216,7 @@ ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_ou
     a.tr = c->tr;
     a.params = c->params.as<float>(); a.park = c->park.as<float>(); a.park_small = c->park_small.as<float>();
     a.zpart = c->zpart.as<float>(); a.maxrows = c->maxrows;
+    a.zx = c->zx.as<uint32_t>();
     a.arrive = c->arrive.as<unsigned int>();
     a.abort_flag = c->abort_flag.as<int32_t>();
     a.spin_limit = 4000000u;
@@ -418,6 +420,7 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         HIP_C(c->park_small.alloc(sizeof(float) * R * c->G * c->S * 17));
         HIP_C(hipMemsetAsync(c->park_small.p, 0, sizeof(float) * R * c->G * c->S * 17, c->stream));
         HIP_C(c->zpart.alloc(sizeof(float) * R * 2 * c->G * c->maxrows * 16));
+        HIP_C(c->zx.alloc(sizeof(uint32_t) * 3 * 1024 * (size_t)R * c->G));
         HIP_C(c->xcc_ids.alloc(sizeof(int32_t) * R * c->G));
         HIP_C(hipMemsetAsync(c->xcc_ids.p, 0xFF, sizeof(int32_t) * R * c->G, c->stream));
         if (getenv("SSGD_PHASE_PROFILE")) {
@@ -586,7 +589,7 @@ void ssgd_destroy(ssgd_ctx* c) {
     if (c->mlp) mlp_destroy(c->mlp);
     DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,
                       &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx, &c->ws_F0,
-                      &c->ws_intstart, &c->ws_crossed, &c->ws_ndone, &c->params, &c->park, &c->park_small, &c->zpart,
+                      &c->ws_intstart, &c->ws_crossed, &c->ws_ndone, &c->params, &c->park, &c->park_small, &c->zpart, &c->zx,
                       &c->arrive, &c->abort_flag, &c->xcc_ids, &c->prof};
     for (DevBuf* b : bufs) b->release();
     delete c;

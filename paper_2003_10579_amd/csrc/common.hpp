@@ -83,6 +83,7 @@ struct LinArgs {
     float* park_small;       // [R][G][S][17]: bias gradient (16) and mean loss (1) of every slot
     float* zpart;            // [R][2][G][maxrows][16] partial logits exchanged inside a cluster
     int32_t maxrows;
+    uint32_t* zx;            // [R][3][G][64][16] exchange of the steady-state kernel: every word 0xFFFFFFFF until written
     unsigned int* arrive;    // [R][kArriveStride] arrival counters of the cluster exchange, zero at launch:
                              // word 0 fenced exchanges, word kArriveFast shared-L2 exchanges (a cache line each)
     int32_t* abort_flag;

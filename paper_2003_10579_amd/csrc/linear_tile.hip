@@ -300,6 +300,9 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
 
     const __amdgpu_buffer_rsrc_t zrsrc = make_rsrc(zpart, (uint32_t)(2u * G * a.maxrows * 16u * sizeof(float)));
     const __amdgpu_buffer_rsrc_t crsrc = make_rsrc(arrive, kArriveStride * 4u);
+    // shared-L2 exchange: three buffers of G x 64 x 16 words used in turn; a word is the sentinel until written
+    const __amdgpu_buffer_rsrc_t xrsrc = make_rsrc(a.zx + (int64_t)rep * 3 * G * 1024, (uint32_t)(3u * G * 4096u));
+    constexpr uint32_t kSentinel = 0xFFFFFFFFu;
     // parked gradients of this workgroup: class own_cls + vv of slot s, 4 columns: 16 bytes at ((s*4 + vv)*NTC + tid)*16
     const __amdgpu_buffer_rsrc_t prsrc = make_rsrc(park, (uint32_t)S * 16u * NTC * 4u);
     int pk_off[4];
@@ -375,8 +378,17 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             mark(8);
             // 16-byte buffer stores carry their whole offset in the vector register: with the scalar offset in a
             // register, such a store has lost data here when the next instruction rewrote its source registers
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, out), zrsrc,
-                                                   z_store_off + (par * G + slice) * slice_bytes, 0, 0);
+            if (fast) {
+                // the re-arming stores of the last exchange are in the L2 before this exchange's data can be seen
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                u32x4 ob = __builtin_bit_cast(u32x4, out);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) ob[c] = (ob[c] == kSentinel) ? 0x7FC00000u : ob[c];   // a NaN that is not the sentinel
+                __builtin_amdgcn_raw_buffer_store_b128(ob, xrsrc, z_store_off + (int)((n_fast % 3u) * G + slice) * 4096, 0, 0);
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, out), zrsrc,
+                                                       z_store_off + (par * G + slice) * slice_bytes, 0, 0);
+            }
         }
         // ---- the part of update v that earlier steps parked: the first two such gradients are fetched
         //      while the exchange stores are on their way
@@ -394,13 +406,9 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         if (n_stale > 1) park_load(st01.y, pvb);
         mark(9);
         // ---- arrival: this wave's stores are in the L2 (shared-L2 mode) or released to the device
-        if (fast) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the stores have been acknowledged by the L2
-            mark(10);
-            if (lane == 0) (void)__builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, crsrc, kArriveFast * 4, 0, 0);
-        } else {
-            if (lane == 0) __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        // ---- arrival.  Shared-L2 mode needs none: the readers poll the data words themselves.  Otherwise the
+        //      wave's stores are released to the device and counted.
+        if (!fast && lane == 0) __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         mark(1);
 
         float gsum[16];          // this thread's part of sum_l g_l: gsum[4 vv + c]
@@ -415,14 +423,13 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
 
         // ---- wave 0 polls the counter in the L2 (all 4 G compute waves of the cluster have arrived) and
         //      relays the result through an LDS word, which the other waves poll
-        {
-            const uint32_t target = (fast ? n_fast + 1u : n_fenced + 1u) * (uint32_t)(4 * G);
-            const int want = (int)(n_fast + n_fenced + 1u);
+        if (!fast) {
+            const uint32_t target = (n_fenced + 1u) * (uint32_t)(4 * G);
+            const int want = (int)(n_fenced + 1u);
             if (wave == 0) {
                 uint32_t spins = 0;
                 for (;;) {
-                    uint32_t got = fast ? __builtin_amdgcn_raw_buffer_load_b32(crsrc, kArriveFast * 4, 0, kAgentLoad)
-                                        : __hip_atomic_load(arrive, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                    uint32_t got = __hip_atomic_load(arrive, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
                     asm volatile("" ::: "memory");   // the load is repeated every turn
                     got = (uint32_t)__builtin_amdgcn_readfirstlane((int)got);
                     if ((int32_t)(got - target) >= 0) break;
@@ -441,9 +448,9 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             } else {
                 while (__builtin_amdgcn_readfirstlane(__hip_atomic_load(&L.ctl[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) < want)
                     __builtin_amdgcn_s_sleep(1);
-                if (!fast) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             }
-            if (!fast && a.allow_fast && tid == 0) {
+            if (a.allow_fast && tid == 0) {
                 // first exchange of the launch: do all slices of this cluster share an XCD (one L2)?
                 const int32_t* ids = a.xcc_ids + (int64_t)rep * G;
                 int same = 1;
@@ -452,25 +459,74 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                     if ((__hip_atomic_load(ids + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xFF) != mine) same = 0;
                 L.ctl[2] = same;
             }
-            if (fast) ++n_fast; else ++n_fenced;
+            ++n_fenced;
         }
         mark(3);
 
         // ---- full logits of row z_row (sum of the G partials in slice order), then residual / softmax
         {
             f32x4 zz = {0.f, 0.f, 0.f, 0.f};
-            const int zbase = par * G * slice_bytes;
-            for (int g0 = 0; g0 < G; g0 += 12) {
-                // straight-line batch: slices past the end re-read the last one and are not added
-                f32x4 part[12];
+            if (fast) {
+                // Poll the partial logits themselves: a slice has arrived for this wave when none of the words
+                // its lanes need is the sentinel.  Slices are added in order; a round re-reads the batch.
+                const int xbase = (int)((n_fast % 3u) * G) * 4096;
+                uint32_t spins = 0;
+                int done = 0;
+                for (int g0 = 0; g0 < G; g0 += 12) {
+                    const int upto = min(g0 + 12, G);
+                    for (;;) {
+                        u32x4 part[12];
 #pragma unroll
-                for (int i = 0; i < 12; ++i)
-                    part[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-                        zrsrc, z_load_off, zbase + min(g0 + i, G - 1) * slice_bytes, kAgentLoad));
+                        for (int i = 0; i < 12; ++i)
+                            part[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, z_load_off, xbase + min(g0 + i, G - 1) * 4096, kAgentLoad);
+                        asm volatile("" ::: "memory");   // the loads are repeated every round
 #pragma unroll
-                for (int i = 0; i < 12; ++i) {
-                    const float keep = (g0 + i < G) ? 1.0f : 0.0f;
-                    zz += part[i] * keep;
+                        for (int i = 0; i < 12; ++i) {
+                            const bool missing = part[i].x == kSentinel || part[i].y == kSentinel || part[i].z == kSentinel || part[i].w == kSentinel;
+                            const bool arrived = __ballot(missing) == 0ull;
+                            if (g0 + i == done && done < upto && arrived) { zz += __builtin_bit_cast(f32x4, part[i]); ++done; }
+                        }
+                        if (done >= upto) break;
+                        switch (a.tune & 7) {
+                            case 1: __builtin_amdgcn_s_sleep(1); break;
+                            case 2: __builtin_amdgcn_s_sleep(4); break;
+                            case 3: __builtin_amdgcn_s_sleep(8); break;
+                            case 4: break;
+                            default: __builtin_amdgcn_s_sleep(2); break;
+                        }
+                        ++spins;
+                        if (spins > a.spin_limit ||
+                            ((spins & 63u) == 0 && __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                            if (lane == 0) {
+                                __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                L.ctl[0] = 1;
+                            }
+                            done = G;      // give up: the launch is aborted at the next barrier
+                            break;
+                        }
+                    }
+                }
+                // Every slice of this exchange has been written, so every workgroup has finished reading the one
+                // before it: this wave's rows of that buffer are re-armed for their next use.
+                uint32_t sv = kSentinel;
+                asm volatile("" : "+v"(sv));      // built here, not kept in registers across the loop
+                const u32x4 arm = {sv, sv, sv, sv};
+                __builtin_amdgcn_raw_buffer_store_b128(arm, xrsrc, z_store_off + (int)(((n_fast + 2u) % 3u) * G + slice) * 4096, 0, 0);
+                ++n_fast;
+            } else {
+                const int zbase = par * G * slice_bytes;
+                for (int g0 = 0; g0 < G; g0 += 12) {
+                    // straight-line batch: slices past the end re-read the last one and are not added
+                    f32x4 part[12];
+#pragma unroll
+                    for (int i = 0; i < 12; ++i)
+                        part[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                            zrsrc, z_load_off, zbase + min(g0 + i, G - 1) * slice_bytes, kAgentLoad));
+#pragma unroll
+                    for (int i = 0; i < 12; ++i) {
+                        const float keep = (g0 + i < G) ? 1.0f : 0.0f;
+                        zz += part[i] * keep;
+                    }
                 }
             }
             mark(4);
