@@ -435,3 +435,31 @@ def test_mlp_adasync_plateau_doubling(ssgd, oracle, torch_cuda):
     assert_trace_equal(g, o)
     assert rel(ctx.params(), tr.params()) <= 5e-3
     ctx.close()
+
+
+def test_config4_mlp_full_size_first_updates(ssgd, oracle, torch_cuda, mixture_full):
+    """Config 4 at its real shape (d=3072, 512 hidden units, 10 classes, N=50000, P=256, m=64, K=8, shifted-Exp):
+    update 0 starts all 256 workers (16384 rows through the large-tile contraction); three per-step aggregates
+    and then ten free-running updates against the oracle (a longer horizon costs the oracle a second per update)."""
+    torch = torch_cuda
+    X, y, Xd, yd = mixture_full
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    ada = dict(mode=1, K0=8, Kmax=256, window=200, rel_tol=0.01)
+    ctx = ssgd.Context("mlp2", Xd, yd, 256, 8, 64, "k_async", gd, 0.05, seed=0, classes=10, hidden=512, bf16=1, adasync=ada)
+    tr = oracle.Trainer(oracle.Model("mlp2", X, y, classes=10, hidden=512, bf16=1), 256, 8, 64, "k_async", od, 0.05,
+                        seed=0, adasync=ada)
+    assert np.array_equal(ctx.params(), tr.params())
+    agg = torch.zeros(ctx.nw, dtype=torch.float32, device="cuda")
+    worst = 0.0
+    for j in range(3):
+        ctx.step(agg)
+        worst = max(worst, rel(agg.cpu().numpy(), tr.step()))
+    ctx.run(10)
+    tr.run(10)
+    assert_trace_equal(ctx.trace(), tr.trace())
+    pr = rel(ctx.params(), tr.params())
+    print(f"config 4 full size: worst per-step gradient error {worst:.3e}, parameter error after 13 updates {pr:.3e}")
+    assert worst <= MLP_GRAD_TOL, worst
+    assert pr <= MLP_PARAM_TOL, pr
+    assert np.allclose(ctx.trace()["loss"], tr.trace()["loss"], rtol=5e-3, atol=1e-4)
+    ctx.close()
