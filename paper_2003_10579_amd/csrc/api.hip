@@ -405,7 +405,7 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         c->S = async ? P : Kcap;
         const int C = model->kind == SSGD_LSQ ? 1 : model->classes;
         c->maxrows = 64 * chunks_for(async ? std::max(P, Kcap) : Kcap, c->mp);
-        c->lds_bytes = linear_lds_bytes(c->nbw, C, c->S);
+        c->lds_bytes = linear_lds_bytes(c->nbw, C, c->S, async);
         if (c->lds_bytes > 160 * 1024) return bail(SSGD_EINVAL, "too many gradient slots for the LDS of one workgroup");
         c->resident_groups = linear_max_resident_groups(c->nbw, c->lds_bytes);
         if (c->resident_groups < c->G) return bail(SSGD_EINVAL, "d is too large for a co-resident cluster of workgroups");

@@ -99,7 +99,7 @@ struct LinArgs {
     unsigned long long* prof;   // nullable diagnostics: [R][G][20] shader-clock cycles spent per phase
 };
 int linear_max_resident_groups(int nbw, size_t lds_bytes);
-size_t linear_lds_bytes(int nbw, int C, int S);
+size_t linear_lds_bytes(int nbw, int C, int S, bool parks);
 hipError_t launch_linear(const LinArgs& a, int nbw, hipStream_t s);
 // Single-tile steady-state kernel (256 columns per workgroup, same state layout as launch_linear with nbw = 4).
 // max_records: the most mini-batches any step of the segment computes.

@@ -89,8 +89,9 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
     float* ylab = reinterpret_cast<float*>(rowid + ROWS);    // [64] label (int bits) or target
     float* lossrow = ylab + ROWS;                            // [64]
     float* bias = lossrow + ROWS;                            // [16]
-    float* small = bias + 16;                                // [S][17] bias gradient + loss per parked slot
-    int* stop = reinterpret_cast<int*>(small + S * 17);      // [4]: stop flag, exchange mode, same-XCD flag
+    const int Ssm = async ? S : 0;                           // the synchronous variants never park a gradient
+    float* small = bias + 16;                                // [Ssm][17] bias gradient + loss per parked slot
+    int* stop = reinterpret_cast<int*>(small + Ssm * 17);      // [4]: stop flag, exchange mode, same-XCD flag
     int* sched = stop + 4;                                   // [4 + 3 KC] lists of the step, from the loader
     int* s_sel = sched + 4;                                  // [KC] consume list of update v: slot
     int* s_tau = s_sel + KC;                                 // [KC]                          version read
@@ -404,7 +405,7 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
         }
     }
     if (tid < 16) bias[tid] = (a.kind == kSoftmax && tid < C) ? params[(int64_t)C * d + tid] : 0.0f;
-    for (int q = tid; q < S * 17; q += NTC) small[q] = small_g[q];
+    for (int q = tid; q < Ssm * 17; q += NTC) small[q] = small_g[q];
     if (tid == 0) {
         stop[0] = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         stop[1] = 0;   // exchange mode: fenced until the cluster is known to share an XCD
@@ -809,12 +810,12 @@ __global__ __launch_bounds__(128 * NBW, 4) void linear_cluster_kernel(LinArgs a)
         }
     }
     if (a.kind == kSoftmax && slice == 0 && tid < C) params[(int64_t)C * d + tid] = bias[tid];
-    for (int q = tid; q < S * 17; q += NTC) small_g[q] = small[q];
+    for (int q = tid; q < Ssm * 17; q += NTC) small_g[q] = small[q];
 }
 
 template <int NBW, bool VEC, bool BIG, bool PROF>
 hipError_t launch_p(const LinArgs& a, hipStream_t s) {
-    const size_t lds = linear_lds_bytes(NBW, a.C, a.S);
+    const size_t lds = linear_lds_bytes(NBW, a.C, a.S, a.variant == kAsync);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_cluster_kernel<NBW, VEC, BIG, PROF>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -858,9 +859,9 @@ hipError_t launch_n(const LinArgs& a, hipStream_t s) {
 
 }  // namespace
 
-size_t linear_lds_bytes(int nbw, int C, int S) {
+size_t linear_lds_bytes(int nbw, int C, int S, bool parks) {
     const size_t SL = 64 * (size_t)nbw;
-    const size_t words = ROWS * SL + (size_t)C * SL + ROWS * 16 + 3 * ROWS + 16 + (size_t)S * 17 + 4 + 4 + 3 * KC;
+    const size_t words = ROWS * SL + (size_t)C * SL + ROWS * 16 + 3 * ROWS + 16 + (parks ? (size_t)S * 17 : 0) + 4 + 4 + 3 * KC;
     return sizeof(float) * words + (((size_t)S + 15) / 16) * 16;
 }
 

@@ -71,6 +71,17 @@ __device__ __forceinline__ Lds carve(unsigned char* smem, int C, int S) {
     return l;
 }
 
+// value of lane ^ 1 / lane ^ 2 inside a quad: a data-parallel-primitive move, no LDS round trip
+__device__ __forceinline__ float quad_xor1(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+}
+__device__ __forceinline__ float quad_xor2(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+}
+__device__ __forceinline__ float quad_lane0(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x00, 0xF, 0xF, false));   // quad_perm [0,0,0,0]
+}
+
 __device__ __forceinline__ void lds_barrier() {
     // orders LDS traffic only: outstanding global loads and stores stay in flight
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -345,6 +356,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         const bool fast = L.ctl[1] != 0;
         const int4 ctl4 = *reinterpret_cast<const int4*>(L.ctl + 4);
         const int2 st01 = *reinterpret_cast<const int2*>(L.s_stale);
+        const int2 rec01 = *reinterpret_cast<const int2*>(L.s_rec);     // records 0 and 1, read ahead of their use
         const int Kv = __builtin_amdgcn_readfirstlane(ctl4.x);
         const int n_rec = __builtin_amdgcn_readfirstlane(ctl4.y);
         const int n_stale = __builtin_amdgcn_readfirstlane(ctl4.z);
@@ -534,7 +546,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             f32x4 dl = {0.f, 0.f, 0.f, 0.f};
             float loss = 0.0f;
             if constexpr (KIND == kLsq) {
-                const float z0 = __shfl(zz.x, lane & ~3, 64);
+                const float z0 = quad_lane0(zz.x);
                 const float r = z0 - L.ylab[z_row];
                 if (ok) loss = 0.5f * r * r;
                 if (z_qd == 0 && ok) dl.x = r * inv_m;
@@ -546,8 +558,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                     zz[e] += L.bias[4 * z_qd + e];
                     if (4 * z_qd + e < C) zmax = fmaxf(zmax, zz[e]);
                 }
-                zmax = fmaxf(zmax, __shfl_xor(zmax, 1, 64));
-                zmax = fmaxf(zmax, __shfl_xor(zmax, 2, 64));
+                zmax = fmaxf(zmax, quad_xor1(zmax));
+                zmax = fmaxf(zmax, quad_xor2(zmax));
                 float den = 0.0f, lt_ = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -556,10 +568,10 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                     if (4 * z_qd + e == lab) lt_ = -(zz[e] - zmax);
                     dl[e] = ex;
                 }
-                den += __shfl_xor(den, 1, 64);
-                den += __shfl_xor(den, 2, 64);
-                lt_ += __shfl_xor(lt_, 1, 64);
-                lt_ += __shfl_xor(lt_, 2, 64);
+                den += quad_xor1(den);
+                den += quad_xor2(den);
+                lt_ += quad_xor1(lt_);
+                lt_ += quad_xor2(lt_);
                 loss = ok ? lt_ + logf(den) : 0.0f;
                 const float inv = 1.0f / den;
 #pragma unroll
@@ -608,7 +620,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             // record r is complete: add it to the aggregate of update v, or park it in its slot
             auto finish = [&](int r) {
                 if constexpr (PROF) { asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])); mark(11); }
-                const int word = __builtin_amdgcn_readfirstlane(L.s_rec[r]);
+                const int word = __builtin_amdgcn_readfirstlane(r == 0 ? rec01.x : (r == 1 ? rec01.y : L.s_rec[r]));
                 if ((word >> 16) != 0) {
 #pragma unroll
                     for (int vv = 0; vv < 4; ++vv)
