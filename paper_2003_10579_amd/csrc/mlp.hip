@@ -373,15 +373,27 @@ __global__ __launch_bounds__(256) void mlp_small_update_kernel(MlpArgs a) {
     float* W2 = b1 + H;
     float* b2 = W2 + (int64_t)C * H;
     const int total = H + C * H + C + 1;
+    __shared__ int slots[256];
+    for (int l = threadIdx.x; l < a.Kv; l += blockDim.x) slots[l] = consumed_slot(a, l);
+    __syncthreads();
     for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < total; q += gridDim.x * blockDim.x) {
+        // element q of the per-slot record [gb1 | gw2 | gb2 | loss]; slots are summed in list order, eight loads in flight
+        const float* base;
+        int stride;
+        if (q < H) { base = a.gb1 + q; stride = H; }
+        else if (q < H + C * H) { base = a.gw2 + (q - H); stride = C * H; }
+        else if (q < H + C * H + C) { base = a.gb2 + (q - H - C * H); stride = 16; }
+        else { base = a.loss; stride = 1; }
         float sum = 0.0f;
-        for (int l = 0; l < a.Kv; ++l) {
-            const int slot = consumed_slot(a, l);
-            if (q < H) sum += a.gb1[slot * H + q];
-            else if (q < H + C * H) sum += a.gw2[(int64_t)slot * C * H + (q - H)];
-            else if (q < H + C * H + C) sum += a.gb2[slot * 16 + (q - H - C * H)];
-            else sum += a.loss[slot];
+        int l = 0;
+        for (; l + 8 <= a.Kv; l += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = base[(int64_t)slots[l + u] * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += v[u];
         }
+        for (; l < a.Kv; ++l) sum += base[(int64_t)slots[l] * stride];
         const float g = sum * invKm;
         if (q < H) { b1[q] -= a.lr * g; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = g; }
         else if (q < H + C * H) {
@@ -487,7 +499,6 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
     TRY(hipGetLastError());
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
-    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
 #undef TRY
@@ -533,10 +544,9 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
             hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
             hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
         }
-        if (a.Kv >= 64)
-            hipLaunchKernelGGL((mlp_contract_kernel<false, 128>), dim3(a.H / 128, a.d / 128), dim3(256), contract_lds(128), stream, a);
-        else
-            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64), dim3(256), contract_lds(64), stream, a);
+        // the gradient contraction always uses the small tiles: 384 workgroups instead of 96 matter more than the
+        // reuse inside a larger tile
+        hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64), dim3(256), contract_lds(64), stream, a);
         hipLaunchKernelGGL(mlp_small_update_kernel, dim3(24), dim3(256), 0, stream, a);
         if (launches) *launches += 1;
     }
