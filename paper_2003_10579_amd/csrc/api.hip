@@ -225,8 +225,6 @@ ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_ou
     a.allow_fast = 1;
     if (const char* e = getenv("SSGD_EXCHANGE")) a.allow_fast = (strcmp(e, "fenced") == 0) ? 0 : 1;
     a.prof = c->prof.as<unsigned long long>();
-    a.tune = 0;
-    if (const char* e = getenv("SSGD_TUNE")) a.tune = atoi(e);
     a.agg_out = agg_out;
 
     // The steady-state kernel runs the steps whose mini-batches fit one tile; step 0 of K-async

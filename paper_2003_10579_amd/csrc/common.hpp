@@ -91,7 +91,6 @@ struct LinArgs {
     float* agg_out;          // nullable: averaged gradient of the last update of replica 0
     int32_t* xcc_ids;        // [R][G] XCD each workgroup of a cluster runs on (checked on the device)
     int32_t allow_fast;      // 1: exchange through the shared L2 once a cluster is known to sit on one XCD
-    int32_t tune;            // experiment knobs of the steady-state kernel (0 = defaults)
     // Steady-state kernel, full launches only: CUs per XCD and resident workgroups per CU.  When set, the
     // workgroup slots of an XCD are dealt out so that the clusters that share CUs share all of them in pairs
     // (0: clusters take consecutive slots).

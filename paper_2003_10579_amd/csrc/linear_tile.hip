@@ -6,12 +6,15 @@
 //
 //   TU  tile, lists and the updated weights are in LDS          (workgroup barrier)
 //       partial logits on the fp32 MFMA units, stored to the cluster's exchange buffer;
-//       each wave waits for its own stores and adds 1 to the arrival counter;
-//       while the other slices arrive: the parked (stale) part of update v is summed;
-//       each wave polls the counter, then sums the G partials of its 16 rows and goes
-//       straight on to residual / softmax in registers
+//       the parked (stale) part of update v is fetched while the stores travel;
+//       each wave polls the partial logits of its 16 rows from all G slices (a word is a
+//       sentinel until it has been written), sums them in slice order and goes straight on
+//       to residual / softmax in registers; the buffer of the exchange before is re-armed.
+//       A cluster that does not sit on one XCD (no shared L2) exchanges through released
+//       stores and an arrival counter instead, as does the first exchange of every launch.
 //   D   delta in LDS                                            (workgroup barrier)
-//       gradient slices delta^T X per record; added to the aggregate or parked
+//       gradient slices delta^T X per record; added to the aggregate or parked;
+//       a loader wave sums delta's columns: bias gradient, loss, bias step
 //   B   the tile has been read                                   (workgroup barrier)
 //       compute waves: w -= (lr/K) * aggregate;  loader waves: next tile -> LDS
 //
@@ -204,8 +207,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 // rows without a sample read row 0; their delta is zero
                 uint32_t id = (uint32_t)__builtin_amdgcn_readlane((int)row_id, lw + 4 * i);
                 id = (id == kNoRow) ? 0u : id;
-                pref[i] = (a.tune & 2) ? __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[i & 3], (int)(id * row_bytes), 0))
-                                       : __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[i & 3], (int)(id * row_bytes), kStream));
+                pref[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[i & 3], (int)(id * row_bytes), kStream));
             }
         };
         auto publish = [&]() {
@@ -312,7 +314,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     const __amdgpu_buffer_rsrc_t zrsrc = make_rsrc(zpart, (uint32_t)(2u * G * a.maxrows * 16u * sizeof(float)));
     const __amdgpu_buffer_rsrc_t crsrc = make_rsrc(arrive, kArriveStride * 4u);
     // shared-L2 exchange: three buffers of G x 64 x 16 words used in turn; a word is the sentinel until written
-    const __amdgpu_buffer_rsrc_t xrsrc = make_rsrc(a.zx + (int64_t)rep * 3 * G * 1024, (uint32_t)(3u * G * 4096u));
+    const __amdgpu_buffer_rsrc_t ersrc = make_rsrc(a.zx + (int64_t)rep * 3 * G * 1024, (uint32_t)(3u * G * 4096u));
     constexpr uint32_t kSentinel = 0xFFFFFFFFu;
     // parked gradients of this workgroup: class own_cls + vv of slot s, 4 columns: 16 bytes at ((s*4 + vv)*NTC + tid)*16
     const __amdgpu_buffer_rsrc_t prsrc = make_rsrc(park, (uint32_t)S * 16u * NTC * 4u);
@@ -396,7 +398,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 u32x4 ob = __builtin_bit_cast(u32x4, out);
 #pragma unroll
                 for (int c = 0; c < 4; ++c) ob[c] = (ob[c] == kSentinel) ? 0x7FC00000u : ob[c];   // a NaN that is not the sentinel
-                __builtin_amdgcn_raw_buffer_store_b128(ob, xrsrc, z_store_off + (int)((n_fast % 3u) * G + slice) * 4096, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(ob, ersrc, z_store_off + (int)((n_fast % 3u) * G + slice) * 4096, 0, 0);
             } else {
                 __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, out), zrsrc,
                                                        z_store_off + (par * G + slice) * slice_bytes, 0, 0);
@@ -445,7 +447,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                     asm volatile("" ::: "memory");   // the load is repeated every turn
                     got = (uint32_t)__builtin_amdgcn_readfirstlane((int)got);
                     if ((int32_t)(got - target) >= 0) break;
-                    if (a.tune & 1) __builtin_amdgcn_s_sleep(2); else __builtin_amdgcn_s_sleep(8);
+                    __builtin_amdgcn_s_sleep(8);
                     ++spins;
                     if (spins > a.spin_limit ||
                         ((spins & 63u) == 0 && __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
@@ -490,7 +492,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                         u32x4 part[12];
 #pragma unroll
                         for (int i = 0; i < 12; ++i)
-                            part[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, z_load_off, xbase + min(g0 + i, G - 1) * 4096, kAgentLoad);
+                            part[i] = __builtin_amdgcn_raw_buffer_load_b128(ersrc, z_load_off, xbase + min(g0 + i, G - 1) * 4096, kAgentLoad);
                         asm volatile("" ::: "memory");   // the loads are repeated every round
 #pragma unroll
                         for (int i = 0; i < 12; ++i) {
@@ -499,13 +501,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                             if (g0 + i == done && done < upto && arrived) { zz += __builtin_bit_cast(f32x4, part[i]); ++done; }
                         }
                         if (done >= upto) break;
-                        switch (a.tune & 7) {
-                            case 1: __builtin_amdgcn_s_sleep(1); break;
-                            case 2: __builtin_amdgcn_s_sleep(4); break;
-                            case 3: __builtin_amdgcn_s_sleep(8); break;
-                            case 4: break;
-                            default: __builtin_amdgcn_s_sleep(2); break;
-                        }
+                        __builtin_amdgcn_s_sleep(2);
                         ++spins;
                         if (spins > a.spin_limit ||
                             ((spins & 63u) == 0 && __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
@@ -523,7 +519,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 uint32_t sv = kSentinel;
                 asm volatile("" : "+v"(sv));      // built here, not kept in registers across the loop
                 const u32x4 arm = {sv, sv, sv, sv};
-                __builtin_amdgcn_raw_buffer_store_b128(arm, xrsrc, z_store_off + (int)(((n_fast + 2u) % 3u) * G + slice) * 4096, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(arm, ersrc, z_store_off + (int)(((n_fast + 2u) % 3u) * G + slice) * 4096, 0, 0);
                 ++n_fast;
             } else {
                 const int zbase = par * G * slice_bytes;

@@ -463,3 +463,12 @@ def test_config4_mlp_full_size_first_updates(ssgd, oracle, torch_cuda, mixture_f
     assert pr <= MLP_PARAM_TOL, pr
     assert np.allclose(ctx.trace()["loss"], tr.trace()["loss"], rtol=5e-3, atol=1e-4)
     ctx.close()
+
+
+def test_exchange_fallback_without_shared_l2(ssgd, oracle, torch_cuda, monkeypatch):
+    """The cluster exchange has two protocols: through the L2 of one XCD (data words polled directly) and, for a
+    cluster that is spread over XCDs, released stores with an arrival counter.  The second one is forced here."""
+    monkeypatch.setenv("SSGD_EXCHANGE", "fenced")
+    X, y = synth.mixture_data(1500, 640, 10, seed=1)
+    _run_pair(ssgd, oracle, torch_cuda, "softmax", X, y, 8, 2, 32, "k_async", ("shifted_exp", 0.5, 1.0), 0.05, 150, seed=4,
+              classes=10)
