@@ -472,3 +472,36 @@ def test_exchange_fallback_without_shared_l2(ssgd, oracle, torch_cuda, monkeypat
     X, y = synth.mixture_data(1500, 640, 10, seed=1)
     _run_pair(ssgd, oracle, torch_cuda, "softmax", X, y, 8, 2, 32, "k_async", ("shifted_exp", 0.5, 1.0), 0.05, 150, seed=4,
               classes=10)
+
+
+@pytest.mark.parametrize("kind,variant,P,K,m,d,classes", [
+    ("lsq", "k_async", 6, 3, 16, 300, 1),          # least squares on the single-tile kernel, ragged second slice
+    ("lsq", "k_sync", 5, 4, 10, 516, 1),           # m not a multiple of 4 (padded rows), three slices
+    ("softmax", "k_async", 7, 4, 10, 260, 15),     # 15 classes (the most the single-tile kernel takes), 48 of 64 rows used
+    ("softmax", "k_batch_sync", 4, 6, 8, 1028, 7), # a worker contributes twice; five slices
+])
+def test_single_tile_kernel_shapes(ssgd, oracle, torch_cuda, kind, variant, P, K, m, d, classes):
+    if kind == "lsq":
+        X, y, _ = synth.lsq_data(1200, d, 5)
+    else:
+        X, y = synth.mixture_data(1200, d, classes, seed=5)
+    _run_pair(ssgd, oracle, torch_cuda, kind, X, y, P, K, m, variant, ("shifted_exp", 0.5, 1.0), 0.02, 100, seed=6,
+              classes=classes)
+
+
+def test_more_replicas_than_one_launch_holds(ssgd, oracle, torch_cuda):
+    """45 replicas of a 12-slice cluster need two launches (40 + 5); zero updates are a no-op."""
+    torch = torch_cuda
+    X, y = synth.mixture_data(3000, 3072, 10, seed=7)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    ctx = ssgd.Context("softmax", Xd, yd, 8, 2, 32, "k_async", gd, 0.05, seed=2, classes=10, replicas=45)
+    ctx.run(0)
+    assert ctx.updates == 0
+    ctx.run(60)
+    for r in (0, 39, 40, 44):
+        tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=2, replica=r)
+        tr.run(60)
+        assert_trace_equal(ctx.trace(r), tr.trace())
+        assert rel(ctx.params(r), tr.params()) <= PARAM_TOL
+    ctx.close()
