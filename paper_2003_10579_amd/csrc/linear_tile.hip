@@ -92,7 +92,7 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int KIND, bool PROF>
+template <int KIND, bool PROF, bool WHOLE>
 __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     // consecutive block ids go to different XCDs: all slices of one cluster take block ids that
     // are congruent modulo 8 and share one L2
@@ -481,26 +481,22 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         {
             f32x4 zz = {0.f, 0.f, 0.f, 0.f};
             if (fast) {
-                // Poll the partial logits themselves: a slice has arrived for this wave when none of the words
-                // its lanes need is the sentinel.  Slices are added in order; a round re-reads the batch.
+                // Poll the partial logits themselves: a batch of slices has arrived for this wave when none of
+                // the words its lanes need is the sentinel, i.e. when the largest word read is not all ones.
+                // A round re-reads the whole batch; the slices are added in order once it is complete.
                 const int xbase = (int)((n_fast % 3u) * G) * 4096;
                 uint32_t spins = 0;
-                int done = 0;
                 for (int g0 = 0; g0 < G; g0 += 12) {
-                    const int upto = min(g0 + 12, G);
+                    u32x4 part[12];
                     for (;;) {
-                        u32x4 part[12];
 #pragma unroll
                         for (int i = 0; i < 12; ++i)
                             part[i] = __builtin_amdgcn_raw_buffer_load_b128(ersrc, z_load_off, xbase + min(g0 + i, G - 1) * 4096, kAgentLoad);
                         asm volatile("" ::: "memory");   // the loads are repeated every round
+                        uint32_t top = 0u;
 #pragma unroll
-                        for (int i = 0; i < 12; ++i) {
-                            const bool missing = part[i].x == kSentinel || part[i].y == kSentinel || part[i].z == kSentinel || part[i].w == kSentinel;
-                            const bool arrived = __ballot(missing) == 0ull;
-                            if (g0 + i == done && done < upto && arrived) { zz += __builtin_bit_cast(f32x4, part[i]); ++done; }
-                        }
-                        if (done >= upto) break;
+                        for (int i = 0; i < 12; ++i) top = max(max(top, max(part[i].x, part[i].y)), max(part[i].z, part[i].w));
+                        if (__ballot(top == kSentinel) == 0ull) break;
                         __builtin_amdgcn_s_sleep(2);
                         ++spins;
                         if (spins > a.spin_limit ||
@@ -509,9 +505,17 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                                 __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                 L.ctl[0] = 1;
                             }
-                            done = G;      // give up: the launch is aborted at the next barrier
-                            break;
+                            break;         // give up: the launch is aborted at the next barrier
                         }
+                    }
+                    if (g0 + 12 <= G) {
+#pragma unroll
+                        for (int i = 0; i < 12; ++i) zz += __builtin_bit_cast(f32x4, part[i]);
+                    } else {
+                        // the last, partial batch re-read its final slice in the unused places
+#pragma unroll
+                        for (int i = 0; i < 12; ++i)
+                            if (g0 + i < G) zz += __builtin_bit_cast(f32x4, part[i]);
                     }
                 }
                 // Every slice of this exchange has been written, so every workgroup has finished reading the one
@@ -634,25 +638,109 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
                 mark(12);
             };
-            // the operands of the next group are read into a second register set before the MFMAs of this one
-            float dv[4];
-            f32x4 xv[4];
-            int r = opq, g = 0;
-            if (n_rec > 0) load_group(r, 0, dv, xv);
-            while (r < n_rec) {
-                int rn = r, gn = g + 1;
-                if (gn == ngrp) { gn = 0; rn = r + 1; }
-                float dn[4];
-                f32x4 xn[4];
+            if constexpr (WHOLE) {
+                // Whole groups of 16 rows only, at most four of them: the tile and delta addresses are four base
+                // addresses (one per k-step of a group, carrying the swizzle key of its rows) plus constants, and
+                // two register sets take turns, one being read from LDS while the MFMAs of the other are issued.
+                int olo = b_lo, och = own_ch, ocl = b_cls;
+                asm volatile("" : "+v"(olo), "+v"(och), "+v"(ocl));   // rebuilt every step, not kept across the loop
+                const float* bx[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) { dn[u] = dv[u]; xn[u] = xv[u]; }
-                if (rn < n_rec) load_group(rn, gn, dn, xn);
-                __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs
-                contract(g, dv, xv);
-                if (rn != r) finish(r);
+                for (int u = 0; u < 4; ++u) bx[u] = L.tile + (4 * u + olo) * SL + ((och ^ (4 * u + olo)) << 2);
+                const float* bz = L.zbuf + olo * 16 + ocl;
+                // half-group h: k-steps 2 h and 2 h + 1, i.e. rows 8 h .. 8 h + 7
+                auto fetch = [&](int h, float (&dv)[2], f32x4 (&xv)[2]) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) { dv[u] = dn[u]; xv[u] = xn[u]; }
-                r = rn; g = gn;
+                    for (int u = 0; u < 2; ++u) {
+                        dv[u] = bz[(8 * h + 4 * u) * 16];
+                        xv[u] = *reinterpret_cast<const f32x4*>(bx[2 * (h & 1) + u] + 16 * (h >> 1) * SL);
+                    }
+                };
+                auto mac = [&](bool first, const float (&dv)[2], const f32x4 (&xv)[2]) {
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const f32x4 init = (first && u == 0) ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[c];
+                            acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv[u], xv[u][c], init, 0, 0, 0);
+                        }
+                    }
+                };
+                auto done = [&](int r) {
+                    if constexpr (PROF) { asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])); mark(11); }
+                    const int word = __builtin_amdgcn_readfirstlane(r == 0 ? rec01.x : rec01.y);
+                    if ((word >> 16) != 0) {
+#pragma unroll
+                        for (int vv = 0; vv < 4; ++vv)
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) gsum[vv * 4 + c] += acc[c][vv];
+                    } else {
+                        const int soff = (word & 0xFFFF) * 16 * NTC * 4;
+#pragma unroll
+                        for (int vv = 0; vv < 4; ++vv) {
+                            const f32x4 gv = {acc[0][vv], acc[1][vv], acc[2][vv], acc[3][vv]};
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, gv), prsrc, pk_off[vv] + soff, 0, 0);
+                        }
+                    }
+                    mark(12);
+                };
+                float da[2], db[2];
+                f32x4 xa[2], xb[2];
+                const int H = n_rec * (mp >> 3);          // half-groups in the tile: 0, 4 or 8
+                if (H > 0) {
+                    fetch(0, da, xa);
+                    fetch(1, db, xb);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mac(true, da, xa);
+                    fetch(2, da, xa);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mac(false, db, xb);
+                    fetch(3, db, xb);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mac(false, da, xa);
+                    if (H > 4) fetch(4, da, xa);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mac(false, db, xb);
+                    if (H > 4) {
+                        const bool two = mp == 32;          // the second record starts with half-group 4
+                        if (two) done(0);
+                        fetch(5, db, xb);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (two) mac(true, da, xa); else mac(false, da, xa);
+                        fetch(6, da, xa);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mac(false, db, xb);
+                        fetch(7, db, xb);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mac(false, da, xa);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mac(false, db, xb);
+                        done(two ? 1 : 0);
+                    } else {
+                        done(0);
+                    }
+                }
+            } else {
+                // the operands of the next group are read into a second register set before the MFMAs of this one
+                float dv[4];
+                f32x4 xv[4];
+                int r = opq, g = 0;
+                if (n_rec > 0) load_group(r, 0, dv, xv);
+                while (r < n_rec) {
+                    int rn = r, gn = g + 1;
+                    if (gn == ngrp) { gn = 0; rn = r + 1; }
+                    float dn[4];
+                    f32x4 xn[4];
+    #pragma unroll
+                    for (int u = 0; u < 4; ++u) { dn[u] = dv[u]; xn[u] = xv[u]; }
+                    if (rn < n_rec) load_group(rn, gn, dn, xn);
+                    __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs
+                    contract(g, dv, xv);
+                    if (rn != r) finish(r);
+    #pragma unroll
+                    for (int u = 0; u < 4; ++u) { dv[u] = dn[u]; xv[u] = xn[u]; }
+                    r = rn; g = gn;
+                }
             }
         }
         mark(6);
@@ -698,15 +786,21 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     for (int q = tid; q < S * 17; q += NTC) small_g[q] = L.small[q];
 }
 
-template <int KIND, bool PROF>
-hipError_t launch_k(const LinArgs& a, size_t lds, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<KIND, PROF>),
+template <int KIND, bool PROF, bool WHOLE>
+hipError_t launch_w(const LinArgs& a, size_t lds, hipStream_t s) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<KIND, PROF, WHOLE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const int groups = (a.replicas + 7) / 8;
     const int blocks = a.pair_cus > 0 ? 8 * a.pair_cus * a.pair_layers : groups * 8 * a.G;
-    hipLaunchKernelGGL((linear_tile_kernel<KIND, PROF>), dim3(blocks), dim3(512), lds, s, a);
+    hipLaunchKernelGGL((linear_tile_kernel<KIND, PROF, WHOLE>), dim3(blocks), dim3(512), lds, s, a);
     return hipGetLastError();
+}
+
+// WHOLE: every record is a whole number of 32-row blocks, so the gradient contraction is fully unrolled
+template <int KIND, bool PROF>
+hipError_t launch_k(const LinArgs& a, size_t lds, hipStream_t s) {
+    return (a.mp == 32 || a.mp == 64) ? launch_w<KIND, PROF, true>(a, lds, s) : launch_w<KIND, PROF, false>(a, lds, s);
 }
 
 }  // namespace
@@ -730,9 +824,9 @@ int linear_tile_resident_groups(size_t lds_bytes) {
     int dev = 0, per_cu = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<kSoftmax, false>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<kSoftmax, false, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, linear_tile_kernel<kSoftmax, false>, 512, lds_bytes) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, linear_tile_kernel<kSoftmax, false, false>, 512, lds_bytes) != hipSuccess) return 0;
     return per_cu * prop.multiProcessorCount;
 }
 
