@@ -187,6 +187,7 @@ ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, boo
         a.v0 = v0; a.nsteps = n;
         a.agg_out = agg_out;
         a.pair_cus = 0; a.pair_layers = 0;
+        a.shared_cus = (a.replicas * c->G > c->cu_count) ? 1 : 0;
         if (tile && a.replicas == per_launch && c->cu_count % 8 == 0 && resident % c->cu_count == 0 && !getenv("SSGD_NO_PAIRING")) {
             a.pair_cus = c->cu_count / 8;
             a.pair_layers = resident / c->cu_count;

@@ -95,6 +95,10 @@ struct LinArgs {
     // workgroup slots of an XCD are dealt out so that the clusters that share CUs share all of them in pairs
     // (0: clusters take consecutive slots).
     int32_t pair_cus, pair_layers;
+    // Steady-state kernel: 1 when the launch has more workgroups than the device has CUs, so that workgroups share
+    // CUs.  Polling for the exchange then pauses longer between rounds: the re-reads of a waiting workgroup compete
+    // with the memory operations of the one it shares the CU with.
+    int32_t shared_cus;
     unsigned long long* prof;   // nullable diagnostics: [R][G][20] shader-clock cycles spent per phase
 };
 int linear_max_resident_groups(int nbw, size_t lds_bytes);

@@ -228,19 +228,43 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             const int Kv = __builtin_amdgcn_readfirstlane(L.ctl[4]);
             const int n_rec = __builtin_amdgcn_readfirstlane(L.ctl[5]);
             const int n_st = __builtin_amdgcn_readfirstlane(L.ctl[6]);
+            // lane = class + 16 * (record within a batch of four records)
             const int c = lane & 15, grp = lane >> 4;
             const int sidx = (c == 15) ? 16 : c;          // the slot record keeps the loss in word 16
             float tot = 0.0f;
-            for (int i = 0; i < n_st; ++i) tot += L.small[__builtin_amdgcn_readfirstlane(L.s_stale[i]) * 17 + sidx];
-            for (int r = 0; r < n_rec; ++r) {
-                float part = 0.0f;
-                for (int row = r * mp + grp; row < (r + 1) * mp; row += 4) part += L.zbuf[row * 16 + c];
-                part += __shfl_xor(part, 16, 64);
-                part += __shfl_xor(part, 32, 64);
-                const int word = __builtin_amdgcn_readfirstlane(L.s_rec[r]);
-                if ((word >> 16) != 0) tot += part;
-                else if (lane < 16) L.small[(word & 0xFFFF) * 17 + sidx] = part;
+            for (int i = 0; i < n_st; ++i) {
+                const float was = L.small[__builtin_amdgcn_readfirstlane(L.s_stale[i]) * 17 + sidx];
+                if (grp == 0) tot += was;
             }
+            for (int r0 = 0; r0 < n_rec; r0 += 4) {
+                const int r = r0 + grp;
+                const bool have = r < n_rec;
+                const float* zp = L.zbuf + (have ? r : 0) * mp * 16 + c;
+                float p0 = 0.0f, p1 = 0.0f;
+                int i0 = 0;
+                for (; i0 + 16 <= mp; i0 += 16) {     // sixteen rows in flight
+                    float t[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) t[i] = zp[(i0 + i) * 16];
+#pragma unroll
+                    for (int i = 0; i < 16; i += 2) { p0 += t[i]; p1 += t[i + 1]; }
+                }
+                for (; i0 < mp; i0 += 4) {
+                    float t[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) t[i] = zp[(i0 + i) * 16];
+                    p0 += t[0] + t[2];
+                    p1 += t[1] + t[3];
+                }
+                const float part = p0 + p1;
+                const int word = have ? L.s_rec[r] : 0;
+                if (have) {
+                    if ((word >> 16) != 0) tot += part;
+                    else L.small[(word & 0xFFFF) * 17 + sidx] = part;
+                }
+            }
+            tot += __shfl_xor(tot, 16, 64);
+            tot += __shfl_xor(tot, 32, 64);
             if (KIND == kSoftmax && lane < C) L.bias[lane] -= (a.lr / (float)Kv) * tot;
             if (lane == 15 && slice == 0) a.tr.loss[(int64_t)rep * cap + v] = tot * (1.0f / (float)Kv);
         };
@@ -497,7 +521,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
 #pragma unroll
                         for (int i = 0; i < 12; ++i) top = max(max(top, max(part[i].x, part[i].y)), max(part[i].z, part[i].w));
                         if (__ballot(top == kSentinel) == 0ull) break;
-                        __builtin_amdgcn_s_sleep(2);
+                        // with another workgroup on this CU, re-reading at once would slow its memory operations
+                        if (a.shared_cus) __builtin_amdgcn_s_sleep(32); else __builtin_amdgcn_s_sleep(2);
                         ++spins;
                         if (spins > a.spin_limit ||
                             ((spins & 63u) == 0 && __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
