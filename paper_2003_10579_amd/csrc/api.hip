@@ -236,6 +236,7 @@ ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_ou
     if (tile) {
         a.v0 = v0;
         if (c->variant == SSGD_K_ASYNC && v0 == 0) { head = 1; a.v0 = 1; }
+        a.chunked = (c->variant != SSGD_K_ASYNC && a.mp * c->Kcap > 64) ? 1 : 0;
         tile = linear_tile_supports(a, c->Kcap);
     }
     if (!tile) return launch_steps(c, v0, n, agg_out, false, events);

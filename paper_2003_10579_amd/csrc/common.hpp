@@ -99,6 +99,10 @@ struct LinArgs {
     // CUs.  Polling for the exchange then pauses longer between rounds: the re-reads of a waiting workgroup compete
     // with the memory operations of the one it shares the CU with.
     int32_t shared_cus;
+    // Steady-state kernel: 1 for a synchronous variant whose iteration does not fit one 64-row tile.  The rows of the
+    // K mini-batches are then taken 64 at a time, each tile through the whole forward / exchange / backward schedule,
+    // the gradient summed over the tiles and the update applied after the last one.
+    int32_t chunked;
     unsigned long long* prof;   // nullable diagnostics: [R][G][20] shader-clock cycles spent per phase
 };
 int linear_max_resident_groups(int nbw, size_t lds_bytes);

@@ -33,7 +33,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int ROWS = 64;        // rows of the LDS tile
 constexpr int SL = 256;         // columns per workgroup
 constexpr int NTC = 256;        // compute threads
-constexpr int LW = 4;           // loader waves
 constexpr int LLOADS = 16;      // 16-byte loads per loader lane per tile
 constexpr int KC = 32;          // list entries per step
 constexpr int kAgentLoad = 16;  // cache policy: served by the L2, never by a CU's L1
@@ -92,7 +91,7 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int KIND, bool PROF, bool WHOLE>
+template <int KIND, bool PROF, bool WHOLE, bool CHUNKED>
 __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     // consecutive block ids go to different XCDs: all slices of one cluster take block ids that
     // are congruent modulo 8 and share one L2
@@ -119,6 +118,12 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     const int64_t cap = a.tr.cap;
     const int col0 = slice * SL;
     const bool async = a.variant == kAsync;
+    // A tile holds whole records of mp rows; when an iteration spans several tiles, a tile is one block of 64 rows
+    // of the iteration's mini-batches, all of them part of the update.
+    // (read from the arguments where it is possible at all: as a compile-time constant it led the compiler to keep
+    // two tiles of gathered rows alive and spill them)
+    const bool chunked = CHUNKED && a.chunked != 0;
+    const int mpt = chunked ? ROWS : mp;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const Lds L = carve(smem, C, S);
@@ -134,7 +139,6 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
 
         // tile row `lane` is sample s_of of record r_of
         const int r_of = lane / mp, s_of = lane % mp;
-        const bool samp_ok = s_of < m;
         // Row lw + 4 i of the tile is fetched by instruction i of this wave, one 16-byte chunk per lane.
         // The swizzle is applied on the global side: lane l fetches chunk l ^ key and writes position l.
         int goff[4];
@@ -167,40 +171,57 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 if (!async) q_ord = tr_ord[ver * Kcap + lane];
             }
         };
-        // Everything of version `ver` from the lists in q_*; leaves the gathers in flight.
-        auto prepare = [&](int64_t ver, bool more) {
+        // The lists of version `ver` (in flight in q_*) become the description of its tiles.
+        int h_worker = -1, h_ord = 0, h_nrec = 0, h_tiles = 1;
+        auto take_lists = [&](int64_t ver, bool more) {
             const int l_sel = q_sel, l_tau = q_tau, l_ord = q_ord;
             const int K = __popcll(__ballot(l_sel >= 0));
             const int nrec = async ? __popcll(__ballot(cur_sel >= 0)) : K;
-            const int rec_worker = async ? cur_sel : l_sel;      // lane r: worker of record r
             const int rec_slot = async ? cur_sel : lane;
             int fr = (!async && lane < K) ? 1 : 0;
             if (async)
                 for (int l = 0; l < K; ++l)
                     if (__builtin_amdgcn_readlane(l_tau, l) == (int32_t)ver && __builtin_amdgcn_readlane(l_sel, l) == rec_slot) fr = 1;
-            n_K = K; n_nrec = nrec;
+            n_K = K;
             // parked gradients that update ver consumes: entries whose version is older, compacted
             const bool is_stale = lane < K && l_tau != (int32_t)ver;
             const unsigned long long smask = __ballot(is_stale);
             n_nstale = __popcll(smask);
             n_stale = async ? l_sel : lane;
             n_stale_pos = is_stale ? __popcll(smask & ((1ull << lane) - 1ull)) : KC;
-            n_rec_word = (lane < nrec) ? (rec_slot | (fr << 16)) : 0;
-            const int worker = __shfl(rec_worker, r_of, 64);
-            const int ordinal = async ? 0 : __shfl(l_ord, r_of, 64);
+            if (chunked) {
+                // every tile is one record of 64 rows that update ver consumes itself
+                n_nrec = 1;
+                n_rec_word = (lane == 0) ? (1 << 16) : 0;
+            } else {
+                n_nrec = nrec;
+                n_rec_word = (lane < nrec) ? (rec_slot | (fr << 16)) : 0;
+            }
+            h_worker = async ? cur_sel : l_sel;      // lane r: worker of record r
+            h_ord = async ? 0 : l_ord;
+            h_nrec = nrec;
+            h_tiles = chunked ? max(1, (nrec * mp + ROWS - 1) / ROWS) : 1;
+            cur_sel = l_sel;
+            asm volatile("" : "+v"(n_stale), "+v"(n_stale_pos), "+v"(n_rec_word), "+v"(cur_sel), "+v"(h_worker), "+v"(h_ord) : : "memory");
+            if (more) issue_lists(ver + 1);
+        };
+        // Tile `t` of version `ver`: sample ids and labels; leaves the gathers in flight.
+        auto make_tile = [&](int64_t ver, int t) {
+            int rec = r_of, smp = s_of;
+            if (chunked) { const int q = t * ROWS + lane; rec = q / mp; smp = q - rec * mp; }
+            const int worker = __shfl(h_worker, min(rec, 63), 64);
+            const int ordinal = __shfl(h_ord, min(rec, 63), 64);
             row_id = kNoRow;
             row_lab = 0.0f;
-            if (samp_ok && r_of < nrec) {
+            if (smp < m && rec < h_nrec) {
                 row_id = batch_index(a.seed, (uint32_t)rep, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)ver,
-                                     (uint32_t)s_of, a.N);
+                                     (uint32_t)smp, a.N);
                 row_lab = (KIND == kLsq) ? reinterpret_cast<const float*>(a.y)[row_id]
                                          : __int_as_float(reinterpret_cast<const int32_t*>(a.y)[row_id]);
             }
-            cur_sel = l_sel;
             // The lists are consumed before the gathers are issued: the gathers are the youngest
             // vector-memory operations of this wave until the tile is published.
-            asm volatile("" : "+v"(n_stale), "+v"(n_stale_pos), "+v"(n_rec_word), "+v"(cur_sel), "+v"(row_id) : : "memory");
-            if (more) issue_lists(ver + 1);
+            asm volatile("" : "+v"(row_id) : : "memory");
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < LLOADS; ++i) {
@@ -210,12 +231,13 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 pref[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[i & 3], (int)(id * row_bytes), kStream));
             }
         };
-        auto publish = [&]() {
+        // flags: bit 0 last tile of its update, bit 1 first tile of its update
+        auto publish = [&](int flags) {
 #pragma unroll
             for (int i = 0; i < LLOADS; ++i) *reinterpret_cast<f32x4*>(my_tile + 4 * i * SL) = pref[i];
             if (lw == 0) {
                 L.rowid[lane] = row_id; L.ylab[lane] = row_lab;
-                if (lane == 0) { L.ctl[4] = n_K; L.ctl[5] = n_nrec; L.ctl[6] = n_nstale; }
+                if (lane == 0) { L.ctl[4] = n_K; L.ctl[5] = n_nrec; L.ctl[6] = n_nstale; L.ctl[7] = flags; }
                 if (n_stale_pos < KC) L.s_stale[n_stale_pos] = n_stale;
                 if (lane < KC) L.s_rec[lane] = n_rec_word;
             }
@@ -224,7 +246,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         // Loader wave 0, between D and B: the column sums of the delta tile per record, i.e. the bias
         // gradient (classes 0..C-1) and the mean mini-batch loss (class 15), summed over the consume
         // list of update v like the weight gradients; then the bias step and the loss record.
-        auto bias_and_loss = [&](int64_t v) {
+        float run_tot = 0.0f;      // sums of the earlier tiles of the same update
+        auto bias_and_loss = [&](int64_t v, int flags) {
             const int Kv = __builtin_amdgcn_readfirstlane(L.ctl[4]);
             const int n_rec = __builtin_amdgcn_readfirstlane(L.ctl[5]);
             const int n_st = __builtin_amdgcn_readfirstlane(L.ctl[6]);
@@ -239,17 +262,17 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             for (int r0 = 0; r0 < n_rec; r0 += 4) {
                 const int r = r0 + grp;
                 const bool have = r < n_rec;
-                const float* zp = L.zbuf + (have ? r : 0) * mp * 16 + c;
+                const float* zp = L.zbuf + (have ? r : 0) * mpt * 16 + c;
                 float p0 = 0.0f, p1 = 0.0f;
                 int i0 = 0;
-                for (; i0 + 16 <= mp; i0 += 16) {     // sixteen rows in flight
+                for (; i0 + 16 <= mpt; i0 += 16) {     // sixteen rows in flight
                     float t[16];
 #pragma unroll
                     for (int i = 0; i < 16; ++i) t[i] = zp[(i0 + i) * 16];
 #pragma unroll
                     for (int i = 0; i < 16; i += 2) { p0 += t[i]; p1 += t[i + 1]; }
                 }
-                for (; i0 < mp; i0 += 4) {
+                for (; i0 < mpt; i0 += 4) {
                     float t[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) t[i] = zp[(i0 + i) * 16];
@@ -265,28 +288,42 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             }
             tot += __shfl_xor(tot, 16, 64);
             tot += __shfl_xor(tot, 32, 64);
-            if (KIND == kSoftmax && lane < C) L.bias[lane] -= (a.lr / (float)Kv) * tot;
-            if (lane == 15 && slice == 0) a.tr.loss[(int64_t)rep * cap + v] = tot * (1.0f / (float)Kv);
+            if ((flags & 2) == 0) tot += run_tot;
+            run_tot = tot;
+            if ((flags & 1) != 0) {
+                if (KIND == kSoftmax && lane < C) L.bias[lane] -= (a.lr / (float)Kv) * tot;
+                if (lane == 15 && slice == 0) a.tr.loss[(int64_t)rep * cap + v] = tot * (1.0f / (float)Kv);
+            }
         };
 
         lds_barrier();                               // the compute waves have set up the control words
         if (L.ctl[0] != 0) return;
         if (async && lane < Kcap) cur_sel = tr_sel[(a.v0 - 1) * Kcap + lane];   // v0 >= 1 for K-async
         issue_lists(a.v0);
-        prepare(a.v0, a.nsteps > 1);
+        take_lists(a.v0, a.nsteps > 1);
+        make_tile(a.v0, 0);
         for (int64_t step = 0; step < a.nsteps; ++step) {
-            if constexpr (PROF) { if (lprof) lprev = (uint32_t)clock64(); }
-            publish();
-            lmark(0);
-            lds_barrier();                           // TU
-            if (step + 1 < a.nsteps) prepare(a.v0 + step + 1, step + 2 < a.nsteps);
-            lmark(1);
-            lds_barrier();                           // D
-            if (L.ctl[0] != 0) return;
-            if (lw == 0) bias_and_loss(a.v0 + step);
-            lmark(2);
-            lds_barrier();                           // B
-            lmark(3);
+            const int tiles = h_tiles;               // of update a.v0 + step
+            for (int t = 0; t < tiles; ++t) {
+                if constexpr (PROF) { if (lprof) lprev = (uint32_t)clock64(); }
+                const int flags = (t + 1 == tiles ? 1 : 0) | (t == 0 ? 2 : 0);
+                publish(flags);
+                lmark(0);
+                lds_barrier();                       // TU
+                if (t + 1 < tiles) {
+                    make_tile(a.v0 + step, t + 1);
+                } else if (step + 1 < a.nsteps) {
+                    take_lists(a.v0 + step + 1, step + 2 < a.nsteps);
+                    make_tile(a.v0 + step + 1, 0);
+                }
+                lmark(1);
+                lds_barrier();                       // D
+                if (L.ctl[0] != 0) return;
+                if (lw == 0) bias_and_loss(a.v0 + step, flags);
+                lmark(2);
+                lds_barrier();                       // B
+                lmark(3);
+            }
         }
         if constexpr (PROF) {
             if (lprof)
@@ -336,7 +373,6 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     if (L.ctl[0] != 0) return;
 
     const __amdgpu_buffer_rsrc_t zrsrc = make_rsrc(zpart, (uint32_t)(2u * G * a.maxrows * 16u * sizeof(float)));
-    const __amdgpu_buffer_rsrc_t crsrc = make_rsrc(arrive, kArriveStride * 4u);
     // shared-L2 exchange: three buffers of G x 64 x 16 words used in turn; a word is the sentinel until written
     const __amdgpu_buffer_rsrc_t ersrc = make_rsrc(a.zx + (int64_t)rep * 3 * G * 1024, (uint32_t)(3u * G * 4096u));
     constexpr uint32_t kSentinel = 0xFFFFFFFFu;
@@ -374,8 +410,9 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         if constexpr (PROF) { if (profiling) { const uint32_t now = (uint32_t)clock64(); ph[phase] += now - tprev; tprev = now; } }
     };
 
+    float gsum[16];          // this thread's part of sum_l g_l of the update in progress: gsum[4 vv + c]
     for (int64_t step = 0; step < a.nsteps; ++step) {
-        const int64_t v = a.v0 + step;
+      for (bool last_tile = false; !last_tile;) {           // the tiles of update a.v0 + step
         if constexpr (PROF) { if (profiling) tprev = (uint32_t)clock64(); }
         lds_barrier();                                      // TU
         mark(0);
@@ -386,6 +423,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         const int Kv = __builtin_amdgcn_readfirstlane(ctl4.x);
         const int n_rec = __builtin_amdgcn_readfirstlane(ctl4.y);
         const int n_stale = __builtin_amdgcn_readfirstlane(ctl4.z);
+        const int tile_flags = __builtin_amdgcn_readfirstlane(ctl4.w);
+        last_tile = (tile_flags & 1) != 0;
         const int par = (int)(step & 1);
         // An opaque zero: addresses built from it are recomputed every step instead of being kept in
         // registers across the whole loop (they would be spilled to scratch memory).
@@ -449,9 +488,10 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         if (!fast && lane == 0) __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         mark(1);
 
-        float gsum[16];          // this thread's part of sum_l g_l: gsum[4 vv + c]
+        if ((tile_flags & 2) != 0) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) gsum[e] = pva[e >> 2][e & 3] + pvb[e >> 2][e & 3];
+            for (int e = 0; e < 16; ++e) gsum[e] = pva[e >> 2][e & 3] + pvb[e >> 2][e & 3];
+        }
         for (int i = 2; i < n_stale; ++i) {     // further parked gradients (K > 2)
             park_load(L.s_stale[i], pva);
 #pragma unroll
@@ -617,14 +657,14 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         // ---- per record: the gradient slice delta^T X, in groups of four k-steps (16 rows); the operands
         //      of the next group are read from LDS before the MFMAs of this one are issued
         {
-            const int kpr = mp >> 2;               // k-steps per record
+            const int kpr = mpt >> 2;              // k-steps per record
             const int ngrp = (kpr + 3) >> 2;       // groups per record
             const int b_lo = lane >> 4, b_cls = lane & 15;
             auto load_group = [&](int r, int g, float (&dv)[4], f32x4 (&xv)[4]) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int k = 4 * g + u;
-                    const int row = r * mp + 4 * min(k, kpr - 1) + b_lo;
+                    const int row = r * mpt + 4 * min(k, kpr - 1) + b_lo;
                     dv[u] = L.zbuf[row * 16 + b_cls];   // k-steps past the record are masked when they are used
                     xv[u] = *reinterpret_cast<const f32x4*>(L.tile + row * SL + ((own_ch ^ (row & 15)) << 2));
                 }
@@ -711,7 +751,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 };
                 float da[2], db[2];
                 f32x4 xa[2], xb[2];
-                const int H = n_rec * (mp >> 3);          // half-groups in the tile: 0, 4 or 8
+                const int H = n_rec * (mpt >> 3);         // half-groups in the tile: 0, 4 or 8
                 if (H > 0) {
                     fetch(0, da, xa);
                     fetch(1, db, xb);
@@ -727,7 +767,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                     __builtin_amdgcn_sched_barrier(0);
                     mac(false, db, xb);
                     if (H > 4) {
-                        const bool two = mp == 32;          // the second record starts with half-group 4
+                        const bool two = mpt == 32;         // the second record starts with half-group 4
                         if (two) done(0);
                         fetch(5, db, xb);
                         __builtin_amdgcn_sched_barrier(0);
@@ -771,7 +811,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         mark(6);
         lds_barrier();                                      // B: the loader waves may rewrite the tile and the lists
         // ---- update v: each compute thread owns its weights; nobody reads them before TU
-        {
+        if (last_tile) {
             const float scale = a.lr / (float)Kv;
             int och = own_ch, ocl = own_cls;
             asm volatile("" : "+v"(och), "+v"(ocl));   // the four addresses below are rebuilt here, not kept across the loop
@@ -786,9 +826,10 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                     *wp = w;
                 }
             }
-            if (tid == 0 && L.ctl[2] != 0) L.ctl[1] = 1;   // later exchanges of this launch use the shared L2
         }
+        if (tid == 0 && L.ctl[2] != 0) L.ctl[1] = 1;   // later exchanges of this launch use the shared L2
         mark(7);
+      }
     }
     if constexpr (PROF) {
         if (profiling)
@@ -811,21 +852,23 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     for (int q = tid; q < S * 17; q += NTC) small_g[q] = L.small[q];
 }
 
-template <int KIND, bool PROF, bool WHOLE>
+template <int KIND, bool PROF, bool WHOLE, bool CHUNKED>
 hipError_t launch_w(const LinArgs& a, size_t lds, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<KIND, PROF, WHOLE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<KIND, PROF, WHOLE, CHUNKED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const int groups = (a.replicas + 7) / 8;
     const int blocks = a.pair_cus > 0 ? 8 * a.pair_cus * a.pair_layers : groups * 8 * a.G;
-    hipLaunchKernelGGL((linear_tile_kernel<KIND, PROF, WHOLE>), dim3(blocks), dim3(512), lds, s, a);
+    hipLaunchKernelGGL((linear_tile_kernel<KIND, PROF, WHOLE, CHUNKED>), dim3(blocks), dim3(512), lds, s, a);
     return hipGetLastError();
 }
 
-// WHOLE: every record is a whole number of 32-row blocks, so the gradient contraction is fully unrolled
+// WHOLE: every record is a whole number of 32-row blocks, so the gradient contraction is fully unrolled;
+// CHUNKED: an iteration spans several tiles
 template <int KIND, bool PROF>
 hipError_t launch_k(const LinArgs& a, size_t lds, hipStream_t s) {
-    return (a.mp == 32 || a.mp == 64) ? launch_w<KIND, PROF, true>(a, lds, s) : launch_w<KIND, PROF, false>(a, lds, s);
+    if (a.chunked) return launch_w<KIND, PROF, true, true>(a, lds, s);      // tiles of one 64-row record
+    return (a.mp == 32 || a.mp == 64) ? launch_w<KIND, PROF, true, false>(a, lds, s) : launch_w<KIND, PROF, false, false>(a, lds, s);
 }
 
 }  // namespace
@@ -837,7 +880,8 @@ size_t linear_tile_lds_bytes(int C, int S) {
 
 bool linear_tile_supports(const LinArgs& a, int max_records) {
     if (a.C > 15 || (a.d % 4) != 0 || a.tr.Kcap > KC || max_records > KC) return false;
-    if (a.mp * max_records > ROWS) return false;
+    if (a.mp * max_records > ROWS && !a.chunked) return false;
+    if (a.chunked && a.variant == kAsync) return false;
     if ((uint64_t)a.N * (uint64_t)a.d * 4u >= (1ull << 32)) return false;   // one buffer descriptor spans the sample matrix
     if (a.agg_out != nullptr) return false;
     if (a.variant == kAsync && a.v0 < 1) return false;    // step 0 of K-async starts all P workers
@@ -849,9 +893,9 @@ int linear_tile_resident_groups(size_t lds_bytes) {
     int dev = 0, per_cu = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<kSoftmax, false, false>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<kSoftmax, false, false, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, linear_tile_kernel<kSoftmax, false, false>, 512, lds_bytes) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, linear_tile_kernel<kSoftmax, false, false, false>, 512, lds_bytes) != hipSuccess) return 0;
     return per_cu * prop.multiProcessorCount;
 }
 
