@@ -102,8 +102,50 @@ __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
 
     int64_t done = 0;
     int crossed = 0;
-    float ahead = 0.0f;          // few workers: delays of restarts at versions ahead_base + lane / width
-    int64_t ahead_base = -1;
+    if (NQ == 1 && !TABLE && a.variant == kAsync && P <= 16 && !(a.interval_t > 0.0)) {
+        // K-async with few workers, in a loop of its own: every lane ranks its worker's finish time against all
+        // P of them, which gives the K earliest in consume-list order at once.  The delay a worker would draw if
+        // it restarted now depends on (worker, version) only: the 64 lanes draw it for 64 / width versions in one go.
+        const int wmask = width - 1, per = 64 / width;
+        const int me = lane & wmask;
+        float ahead = 0.0f;
+        int64_t ahead_base = a.j0 + 1 - per;         // refilled before the first use
+        double mine = key[0];
+        int32_t mytau = tau[0];
+        for (; done < a.count; ++done) {
+            const int64_t j = a.j0 + done;
+            const int slot = (int)(j + 1 - ahead_base);
+            if (slot >= per) {
+                ahead_base = j + 1;
+                ahead = 0.0f;
+                if (me < P) ahead = draw_delay((uint32_t)me, 0, (uint32_t)(ahead_base + lane / width));
+            }
+            const float restart = __shfl(ahead, me + width * (slot >= per ? 0 : slot), 64);
+            const long long bits = __double_as_longlong(mine);
+            int rank = 0;
+            for (int w = 0; w < P; ++w) {
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, w);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((unsigned long long)bits >> 32), w);
+                const double other = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+                rank += before(other, w, mine, lane) ? 1 : 0;
+            }
+            const int last = __builtin_ctzll(__ballot(lane < P && rank == K - 1));
+            const uint32_t tlo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, last);
+            const uint32_t thi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((unsigned long long)bits >> 32), last);
+            const double t_new = __longlong_as_double((long long)(((unsigned long long)thi << 32) | tlo));
+            if (lane < P && rank < K) {
+                tr_sel[j * Kcap + rank] = lane; tr_tau[j * Kcap + rank] = mytau; tr_ord[j * Kcap + rank] = 0;
+                mytau = (int32_t)(j + 1);
+                mine = t_new + (double)restart;
+            }
+            for (int l = K + lane; l < Kcap; l += 64) {
+                tr_sel[j * Kcap + l] = -1; tr_tau[j * Kcap + l] = -1; tr_ord[j * Kcap + l] = -1;
+            }
+            if (lane == 0) { tr_t[j] = t_new; tr_K[j] = K; }
+            clock = t_new;
+        }
+        key[0] = mine; tau[0] = mytau;
+    }
     for (; done < a.count; ++done) {
         const int64_t j = a.j0 + done;
         const uint32_t ver = (uint32_t)j;
@@ -142,37 +184,6 @@ __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
                 }
             }
             t_new = clock + last;
-        } else if (NQ == 1 && !TABLE && P <= 16) {
-            // K-async with few workers: every lane ranks its worker's finish time against all P of them, which
-            // gives the K earliest in consume-list order at once.  The delay a worker would draw if it restarted
-            // now depends on (worker, version) only: the 64 lanes draw it for 64 / width versions in one go.
-            const int wmask = width - 1;
-            const int64_t need = j + 1;
-            if (ahead_base < 0 || need >= ahead_base + 64 / width) {
-                ahead_base = need;
-                ahead = 0.0f;
-                if ((lane & wmask) < P) ahead = draw_delay((uint32_t)(lane & wmask), 0, (uint32_t)(ahead_base + lane / width));
-            }
-            const float restart = __shfl(ahead, (lane & wmask) + width * (int)(need - ahead_base), 64);
-            const long long mine = __double_as_longlong(key[0]);
-            int rank = 0;
-            for (int w = 0; w < P; ++w) {
-                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)mine, w);
-                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((unsigned long long)mine >> 32), w);
-                const double other = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-                rank += before(other, w, key[0], lane) ? 1 : 0;
-            }
-            const int last = __builtin_ctzll(__ballot(lane < P && rank == K - 1));
-            {
-                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)mine, last);
-                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((unsigned long long)mine >> 32), last);
-                t_new = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-            }
-            if (lane < P && rank < K) {
-                tr_sel[j * Kcap + rank] = lane; tr_tau[j * Kcap + rank] = tau[0]; tr_ord[j * Kcap + rank] = 0;
-                tau[0] = (int32_t)(j + 1);
-                key[0] = t_new + (double)restart;
-            }
         } else {
             // K-async: the K earliest finishers contribute; only they restart, at t_{j+1}.  The delay a
             // worker would draw if it restarted now depends on (worker, version) only, so every lane
