@@ -311,7 +311,12 @@ def test_config2_softmax_kbatch_sync_full_size(ssgd, oracle, torch_cuda, mixture
     assert worst <= GRAD_TOL, worst
     assert_trace_equal(ctx.trace(), tr.trace())
     assert rel(ctx.params(), tr.params()) <= PARAM_TOL
-    ctx.run(1975)
+    # the steady-state kernel takes an iteration as 32 tiles of 64 rows: 15 more iterations against the oracle
+    ctx.run(15)
+    tr.run(15)
+    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
+    assert np.allclose(ctx.trace()["loss"], tr.trace()["loss"], rtol=2e-4, atol=1e-6)
+    ctx.run(1960)
     Xs, ys, _ = synth.lsq_data(16, 2, 0)
     sched = oracle.Trainer(oracle.Model("lsq", Xs, ys), 64, 16, 1, "k_batch_sync", od, 0.0, seed=0)
     sched.run(2000)
@@ -504,4 +509,40 @@ def test_more_replicas_than_one_launch_holds(ssgd, oracle, torch_cuda):
         tr.run(60)
         assert_trace_equal(ctx.trace(r), tr.trace())
         assert rel(ctx.params(r), tr.params()) <= PARAM_TOL
+    ctx.close()
+
+
+@pytest.mark.parametrize("kind,variant,P,K,m,d,classes", [
+    ("lsq", "k_batch_sync", 3, 5, 70, 132, 1),     # records of 72 rows straddle the 64-row tiles; 5.6 tiles
+    ("softmax", "k_sync", 6, 5, 30, 516, 10),      # 2.5 tiles of padded 32-row records, three slices
+    ("softmax", "k_batch_sync", 5, 12, 64, 260, 3),  # twelve full tiles, a worker contributes several times
+])
+def test_iterations_of_several_tiles(ssgd, oracle, torch_cuda, kind, variant, P, K, m, d, classes):
+    """Synchronous iterations whose K mini-batches do not fit one 64-row tile run tile by tile in the steady-state
+    kernel, the update after the last tile."""
+    if kind == "lsq":
+        X, y, _ = synth.lsq_data(1200, d, 8)
+    else:
+        X, y = synth.mixture_data(1200, d, classes, seed=8)
+    _run_pair(ssgd, oracle, torch_cuda, kind, X, y, P, K, m, variant, ("pareto", 2.5, 1.0), 0.02, 60, seed=9,
+              classes=classes, check_steps=20)
+
+
+def test_adasync_ksync_rule_with_growing_tile_count(ssgd, oracle, torch_cuda):
+    """K-sync under the paper's rule for K (Appendix D): K grows from 2 to 16 during the run, so the iterations go
+    from one tile to two; trace and parameters against the oracle."""
+    torch = torch_cuda
+    X, y, _ = synth.lsq_data(512, 16, 3)
+    gd, od = dist_pair(ssgd, oracle, ("exp", 1.0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    ada = dict(mode=3, K0=2, Kmax=16, interval_t=6.0)
+    ctx = ssgd.Context("lsq", Xd, yd, 16, 2, 8, "k_sync", gd, 0.03, seed=2, adasync=ada)
+    tr = oracle.Trainer(oracle.Model("lsq", X, y), 16, 2, 8, "k_sync", od, 0.03, seed=2, adasync=ada)
+    ctx.run(300)
+    tr.run(300)
+    g, o = ctx.trace(), tr.trace()
+    assert o["K"][-1] > 8
+    assert_trace_equal(g, o)
+    assert np.allclose(g["loss"], o["loss"], rtol=2e-4, atol=1e-6)
+    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
     ctx.close()
