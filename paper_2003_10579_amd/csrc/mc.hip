@@ -22,6 +22,7 @@ struct McArgs {
     Dist dist;
     uint64_t seed;
     int32_t variant, P, Kmin, Kmax, chain_len;
+    int32_t nslices;     // block b takes the values K = Kmin + b % nslices, + nslices, ...: small accumulators, many waves per CU
     int64_t trial0, trials;
     double* partial;     // [blocks][nK*chain_len][2]
     double* per_trial;   // nullable
@@ -62,6 +63,77 @@ __device__ __forceinline__ void sort_keys(double (&key)[NQ], int lane) {
     }
 }
 
+// Positions [0, B) sorted in descending order, B a power of two below the array size: the network of sort_keys
+// turned round, the other positions untouched.
+template <int NQ, int B>
+__device__ __forceinline__ void sort_prefix_descending(double (&key)[NQ], int lane) {
+#pragma unroll
+    for (int k = 2; k <= B; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            if (j < 64) {
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    if (q * 64 >= B) continue;
+                    const int p = q * 64 + lane;
+                    const double other = __shfl_xor(key[q], j, 64);
+                    const bool down = (p & k) == 0, lower = (p & j) == 0;
+                    const double v = (down == lower) ? fmax(key[q], other) : fmin(key[q], other);
+                    key[q] = (p < B) ? v : key[q];
+                }
+            } else {
+                const int dq = j >> 6;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    if ((q & dq) == 0 && (q | dq) < NQ && (q | dq) * 64 < B) {
+                        const int p = q * 64 + lane;
+                        const bool down = (p & k) == 0;
+                        const double a = key[q], b = key[q | dq];
+                        key[q] = down ? fmax(a, b) : fmin(a, b);
+                        key[q | dq] = down ? fmin(a, b) : fmax(a, b);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// The array was ascending and its first K keys have been replaced (K wave-uniform): sorted again.  The first B
+// positions, B the power of two that covers K, are sorted in descending order; together with the untouched
+// ascending rest that is a bitonic sequence, which one merge pass sorts.
+template <int NQ>
+__device__ __forceinline__ void resort_prefix(double (&key)[NQ], int lane, int K) {
+    constexpr int N = 64 * NQ;
+    if (2 * K > N) { sort_keys<NQ>(key, lane); return; }
+    if (K > 64) { if constexpr (NQ > 2) sort_prefix_descending<NQ, 128>(key, lane); }
+    else if (K > 32) sort_prefix_descending<NQ, 64>(key, lane);
+    else if (K > 16) sort_prefix_descending<NQ, 32>(key, lane);
+    else if (K > 8) sort_prefix_descending<NQ, 16>(key, lane);
+    else if (K > 4) sort_prefix_descending<NQ, 8>(key, lane);
+    else if (K > 2) sort_prefix_descending<NQ, 4>(key, lane);
+    else if (K > 1) sort_prefix_descending<NQ, 2>(key, lane);
+#pragma unroll
+    for (int j = N >> 1; j > 0; j >>= 1) {
+        if (j < 64) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const double other = __shfl_xor(key[q], j, 64);
+                key[q] = ((lane & j) == 0) ? fmin(key[q], other) : fmax(key[q], other);
+            }
+        } else {
+            const int dq = j >> 6;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                if ((q & dq) == 0) {
+                    const double a = key[q], b = key[q | dq];
+                    key[q] = fmin(a, b);
+                    key[q | dq] = fmax(a, b);
+                }
+            }
+        }
+    }
+}
+
 // key at position pos (wave-uniform pos), known to every lane
 template <int NQ>
 __device__ __forceinline__ double key_at(const double (&key)[NQ], int pos) {
@@ -92,14 +164,16 @@ __device__ __forceinline__ Best wave_argmin(const double (&key)[NQ], int lane) {
 
 template <int NQ>
 __global__ __launch_bounds__(64) void mc_kernel(McArgs a) {
-    extern __shared__ double acc[];   // [nK*chain_len][2]
+    extern __shared__ double acc[];   // [values of K of this block][chain_len][2]
     const int lane = threadIdx.x;
     const int P = a.P, L = a.chain_len, nK = a.Kmax - a.Kmin + 1;
-    const int cells = nK * L;
+    const int slice = blockIdx.x % a.nslices, group = blockIdx.x / a.nslices, groups = gridDim.x / a.nslices;
+    const int cells = ((nK - slice + a.nslices - 1) / a.nslices) * L;
+    const int cells_max = ((nK + a.nslices - 1) / a.nslices) * L;
     for (int c = lane; c < 2 * cells; c += 64) acc[c] = 0.0;
     __syncthreads();
 
-    for (int64_t q0 = blockIdx.x; q0 < a.trials; q0 += gridDim.x) {
+    for (int64_t q0 = group; q0 < a.trials; q0 += groups) {
         const uint32_t trial = (uint32_t)(a.trial0 + q0);
         // fresh launch: P delays, shared by every K
         double base[NQ];
@@ -113,7 +187,7 @@ __global__ __launch_bounds__(64) void mc_kernel(McArgs a) {
         for (int q = 0; q < NQ; ++q) sorted0[q] = base[q];
         sort_keys<NQ>(sorted0, lane);
 
-        for (int K = a.Kmin; K <= a.Kmax; ++K) {
+        for (int K = a.Kmin + slice; K <= a.Kmax; K += a.nslices) {
             double key[NQ];
             double t = 0.0;
 #pragma unroll
@@ -125,10 +199,11 @@ __global__ __launch_bounds__(64) void mc_kernel(McArgs a) {
                     // the a-th earliest finisher restarts at t_new with the a-th fresh delay
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
+                        if (q * 64 >= K) continue;        // wave-uniform: no key of this register restarts
                         const int p = q * 64 + lane;
                         if (p < K) key[q] = t_new + (double)delay(a.dist, a.seed, kMonteCarlo, (uint32_t)K, trial, P, 1, p, 0, l + 1);
                     }
-                    if (l + 1 < L) sort_keys<NQ>(key, lane);
+                    if (l + 1 < L) resort_prefix<NQ>(key, lane, K);
                 } else {
                     if (l > 0) {
 #pragma unroll
@@ -157,7 +232,7 @@ __global__ __launch_bounds__(64) void mc_kernel(McArgs a) {
                 }
                 const double T = t_new - t;
                 t = t_new;
-                const int cell = (K - a.Kmin) * L + l;
+                const int cell = ((K - a.Kmin) / a.nslices) * L + l;
                 if (lane == 0) {
                     acc[2 * cell] += T;
                     acc[2 * cell + 1] += T * T;
@@ -167,7 +242,7 @@ __global__ __launch_bounds__(64) void mc_kernel(McArgs a) {
         }
     }
     __syncthreads();
-    for (int c = lane; c < 2 * cells; c += 64) a.partial[(int64_t)blockIdx.x * 2 * cells + c] = acc[c];
+    for (int c = lane; c < 2 * cells; c += 64) a.partial[(int64_t)blockIdx.x * 2 * cells_max + c] = acc[c];
 }
 
 }  // namespace
@@ -191,23 +266,28 @@ extern "C" ssgd_status ssgd_runtime_mc(int32_t variant, int32_t P, int32_t Kmin,
     if (Kmax > 65535) { mc_fail("K too large"); return SSGD_EINVAL; }
     const int nK = Kmax - Kmin + 1;
     const int64_t cells = (int64_t)nK * chain_len;
-    const size_t lds = sizeof(double) * 2 * cells;
-    if (lds > 64 * 1024) { mc_fail("(Kmax-Kmin+1) * chain_len too large for one launch"); return SSGD_EINVAL; }
+    // accumulators of at most 5 KB per wavefront, so that 32 of them fit a CU
+    int nslices = 1;
+    while (nslices < nK && (int64_t)((nK + nslices - 1) / nslices) * chain_len * 16 > 5120) ++nslices;
+    const int64_t cells_max = (int64_t)((nK + nslices - 1) / nslices) * chain_len;
+    const size_t lds = sizeof(double) * 2 * cells_max;
+    if (lds > 64 * 1024) { mc_fail("chain_len too large for one launch"); return SSGD_EINVAL; }
     if (per_trial && trials * cells > (1ll << 27)) { mc_fail("per_trial output limited to 2^27 values"); return SSGD_EINVAL; }
     hipStream_t st = (hipStream_t)hip_stream;
     McArgs a{};
     a.dist.kind = dist->kind; a.dist.shift = (float)dist->shift; a.dist.rate = (float)dist->rate;
     a.dist.alpha = (float)dist->alpha; a.dist.scale = (float)dist->scale; a.dist.table = nullptr; a.dist.table_len = 0;
     a.seed = seed; a.variant = variant; a.P = P; a.Kmin = Kmin; a.Kmax = Kmax; a.chain_len = chain_len;
-    a.trial0 = trial0; a.trials = trials;
+    a.trial0 = trial0; a.trials = trials; a.nslices = nslices;
     int dev = 0; hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { mc_fail("no device"); return SSGD_EDEVICE; }
-    int64_t blocks = std::min<int64_t>(trials, (int64_t)prop.multiProcessorCount * 8);
+    const int64_t groups = std::max<int64_t>(1, std::min<int64_t>(trials, (int64_t)prop.multiProcessorCount * 32 / nslices));
+    const int64_t blocks = groups * nslices;
     void *d_partial = nullptr, *d_pt = nullptr;
     ssgd_status rc = SSGD_OK;
-    std::vector<double> host((size_t)(blocks * 2 * cells));
+    std::vector<double> host((size_t)(blocks * 2 * cells_max));
     do {
-        if (hipMalloc(&d_partial, sizeof(double) * blocks * 2 * cells) != hipSuccess) { mc_fail("hipMalloc"); rc = SSGD_ENOMEM; break; }
+        if (hipMalloc(&d_partial, sizeof(double) * blocks * 2 * cells_max) != hipSuccess) { mc_fail("hipMalloc"); rc = SSGD_ENOMEM; break; }
         if (per_trial && hipMalloc(&d_pt, sizeof(double) * trials * cells) != hipSuccess) { mc_fail("hipMalloc"); rc = SSGD_ENOMEM; break; }
         a.partial = (double*)d_partial; a.per_trial = (double*)d_pt;
         const int nq = (P + 63) / 64;
@@ -220,8 +300,11 @@ extern "C" ssgd_status ssgd_runtime_mc(int32_t variant, int32_t P, int32_t Kmin,
         if (e == hipSuccess && per_trial) e = hipMemcpy(per_trial, d_pt, sizeof(double) * trials * cells, hipMemcpyDeviceToHost);
         if (e != hipSuccess) { mc_fail(std::string("mc kernel: ") + hipGetErrorString(e)); rc = SSGD_EDEVICE; break; }
         for (int64_t c = 0; c < cells; ++c) {
+            // cell (K, update) lives in the blocks of slice (K - Kmin) % nslices, at its place among their values of K
+            const int64_t kk = c / chain_len, l = c % chain_len;
+            const int64_t local = (kk / nslices) * chain_len + l;
             double s = 0.0, s2 = 0.0;
-            for (int64_t b = 0; b < blocks; ++b) { s += host[(b * cells + c) * 2]; s2 += host[(b * cells + c) * 2 + 1]; }
+            for (int64_t b = kk % nslices; b < blocks; b += nslices) { s += host[(b * cells_max + local) * 2]; s2 += host[(b * cells_max + local) * 2 + 1]; }
             if (sum) sum[c] = s;
             if (sumsq) sumsq[c] = s2;
             if (mean) mean[c] = s / (double)trials;
