@@ -149,7 +149,8 @@ ssgd_status ssgd_force_K(ssgd_ctx *ctx, int32_t K);
  * the simulation behind Fig. 6).  Trial r draws P fresh delays; for every K in
  * [Kmin, Kmax] the variant's event process is run for chain_len updates from that
  * fresh start and T_l (l = 1..chain_len) is recorded.  Supported: SSGD_K_SYNC,
- * SSGD_K_BATCH_SYNC, SSGD_K_ASYNC.  P <= 256.  Outputs are HOST arrays of
+ * SSGD_K_BATCH_SYNC, SSGD_K_ASYNC.  P <= 256, chain_len <= 4096 (else
+ * SSGD_EINVAL).  Outputs are HOST arrays of
  * (Kmax-Kmin+1) x chain_len entries: mean and unbiased variance of T_l, and
  * (nullable) the raw sums `sum` and `sumsq`; per_trial (HOST, nullable,
  * trials x (Kmax-Kmin+1) x chain_len fp64) receives every trial's T_l. */
