@@ -31,8 +31,13 @@ def cpu_baseline(X, y, spec, budget_s=12.0):
         tr.run(50)
         done += 50
     dt = time.perf_counter() - t0
+    # the oracle's Monte-Carlo estimator, same shape as mc_rate below
+    t1 = time.perf_counter()
+    oracle.runtime_mc("k_async", 128, 1, 128, oracle.Dist("exp", 1.0), 200, 8, seed=1)
+    dt_mc = time.perf_counter() - t1
     return {"value": done * 2 / dt, "unit": "worker-gradients/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {done} of 5000 updates of replica 0 ({done * 2} worker-gradients), {dt:.1f} s"}
+            "sample": f"first {done} of 5000 updates of replica 0 ({done * 2} worker-gradients), {dt:.1f} s",
+            "mc_trials_per_s": 200 / dt_mc, "mc_sample": f"200 trials (P=128, K=1..128, chains of 8, Exp(1)), {dt_mc:.1f} s"}
 
 
 def measured_traffic(replicas, updates):

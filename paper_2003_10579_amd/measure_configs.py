@@ -1,9 +1,11 @@
 """Throughput of the configurations that bench.py does not time: config 0 (least squares K-sync), config 2
 (softmax K-batch-sync, P=64, m=128, K=16, Pareto delays) and config 3 (runtime Monte Carlo, P=128, all K,
 10^7 trials per delay distribution), one JSON line each.  Config 3 also reports the largest deviation of the
-Exp(1) order-statistic means from their closed form (App. B.1) in standard errors, and the oracle's rate on one
-host core for a small number of trials.
+Exp(1) order-statistic means from their closed form (App. B.1) in standard errors.
+
+  python3 paper_2003_10579_amd/measure_configs.py [--configs 0,2,3] [--mc-trials N]
 """
+import argparse
 import json
 import os
 import sys
@@ -16,12 +18,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def main(mc_trials=10_000_000):
+def main(mc_trials=10_000_000, configs=(0, 2, 3)):
     import torch
 
     from paper_2003_10579_amd import ssgd, synth
 
-    # ---- config 0
+    if 0 in configs:
+        config0(torch, ssgd, synth)
+    if 2 in configs:
+        config2(torch, ssgd, synth)
+    if 3 in configs:
+        config3(ssgd, mc_trials)
+
+
+def config0(torch, ssgd, synth):
     X, y, _ = synth.lsq_data(4096, 64, 0)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
     ctx = ssgd.Context("lsq", Xd, yd, 4, 2, 16, "k_sync", ssgd.delay_dist("exp", 1.0), 0.01, seed=0)
@@ -32,7 +42,8 @@ def main(mc_trials=10_000_000):
                       "us_per_update": dt / 500 * 1e6, "worker_gradients_per_s": 500 * 2 / dt}), flush=True)
     ctx.close()
 
-    # ---- config 2
+
+def config2(torch, ssgd, synth):
     X, y = synth.mixture_data(50000, 3072, 10, seed=0)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
     R, J = 40, 200
@@ -47,7 +58,8 @@ def main(mc_trials=10_000_000):
                       "algorithmic_GBps": g * 128 * 3073 * 4 / 1e9, "frac_of_8TBps": g * 128 * 3073 * 4 / 8e12}), flush=True)
     ctx.close()
 
-    # ---- config 3
+
+def config3(ssgd, mc_trials):
     P, L = 128, 8
     H = np.cumsum(1.0 / np.arange(1, P + 1))
     for name, spec in (("exp", ("exp", 1.0)), ("shifted_exp", ("shifted_exp", 0.2, 1.0)), ("pareto", ("pareto", 2.5, 1.0))):
@@ -63,16 +75,10 @@ def main(mc_trials=10_000_000):
             se = np.sqrt(out["var"] / mc_trials)
             rec["max_abs_dev_in_standard_errors_all_K_all_updates"] = float(np.max(np.abs(out["mean"] - exact[:, None]) / se))
         print(json.dumps(rec), flush=True)
-    try:
-        import oracle
-        od = oracle.Dist("exp", 1.0)
-        t0 = time.perf_counter()
-        oracle.runtime_mc("k_async", P, 1, P, od, 200, L, seed=3)
-        dt = time.perf_counter() - t0
-        print(json.dumps({"config": 3, "cpu_oracle": True, "cores": 1, "trials": 200, "trials_per_s": 200 / dt}), flush=True)
-    except ImportError:
-        pass
-
 
 if __name__ == "__main__":
-    main()
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", default="0,2,3")
+    ap.add_argument("--mc-trials", type=int, default=10_000_000)
+    args = ap.parse_args()
+    main(args.mc_trials, tuple(int(c) for c in args.configs.split(",")))
