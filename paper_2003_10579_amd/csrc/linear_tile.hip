@@ -1,8 +1,11 @@
-// Steady-state kernel of the linear models (Sec. 2.2, Eq. (2), Eq. (3)) for the common shape:
-// every step's mini-batches fit one 64-row tile (records * padded m <= 64), at most 15 classes,
-// rows readable 16 bytes at a time.  Same cluster decomposition, state layout and arithmetic as
-// the general kernel (linear.hip), which runs every other shape and may be mixed with this one
-// launch by launch; what differs is the schedule inside a step:
+// Steady-state kernel of the linear models (Sec. 2.2, Eq. (2), Eq. (3)) for the common shapes:
+// at most 15 classes, rows readable 16 bytes at a time, and either every step's mini-batches
+// fit one 64-row tile (records * padded m <= 64) or the variant is synchronous, in which case
+// the rows of an iteration's K mini-batches are taken 64 at a time: every tile goes through the
+// schedule below, the gradient is summed over the tiles and the update follows the last one.
+// Same cluster decomposition, state layout and arithmetic as the general kernel (linear.hip),
+// which runs every other shape and may be mixed with this one launch by launch; what differs
+// is the schedule inside a step:
 //
 //   TU  tile, lists and the updated weights are in LDS          (workgroup barrier)
 //       partial logits on the fp32 MFMA units, stored to the cluster's exchange buffer;
@@ -16,12 +19,13 @@
 //       gradient slices delta^T X per record; added to the aggregate or parked;
 //       a loader wave sums delta's columns: bias gradient, loss, bias step
 //   B   the tile has been read                                   (workgroup barrier)
-//       compute waves: w -= (lr/K) * aggregate;  loader waves: next tile -> LDS
+//       compute waves: w -= (lr/K) * aggregate (after the last tile of the update);
+//       loader waves: next tile -> LDS
 //
 // Four compute waves, four loader waves.  A wave's vector-memory counter retires in order,
 // so the long HBM gathers live in waves of their own: the loader waves fetch everything of
-// step v+1 (lists, sample ids, labels, rows) while step v computes, hold the rows in
-// registers, and copy them to LDS between B and TU.
+// the next tile (lists, sample ids, labels, rows) while the current one is computed, hold the
+// rows in registers, and copy them to LDS between B and TU.
 #include "common.hpp"
 
 namespace ssgd {
