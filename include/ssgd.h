@@ -145,6 +145,25 @@ ssgd_status ssgd_set_params(ssgd_ctx *ctx, int32_t replica, const float *w_in);
 /* Force K for the following updates (1 <= K <= Kmax); AdaSync keeps running. */
 ssgd_status ssgd_force_K(ssgd_ctx *ctx, int32_t K);
 
+/* The mini-batch each worker of a K-async run has in flight (Sec. 2.2: a worker that is not
+ * among the K selected keeps computing on the parameters it read): version read tau_i, ordinal,
+ * absolute finish time f_i.  HOST arrays of P entries, each nullable.  SSGD_EINVAL for the
+ * synchronous variants, which restart every worker at every update. */
+ssgd_status ssgd_get_workers(ssgd_ctx *ctx, int32_t replica, int32_t *tau, int32_t *ord, double *finish);
+
+/* Snapshot and resume.  A snapshot holds everything later updates depend on: the trace so far,
+ * update count, simulated clock, current K and the AdaSync bookkeeping, every worker's tau_i and
+ * f_i, the parameters, and the gradients (linear models) or gradient factors (MLP) of the
+ * mini-batches in flight, which were taken at parameters that no longer exist.  It is an opaque
+ * HOST buffer of ssgd_state_bytes() bytes (the size grows with the trace); ssgd_set_state accepts
+ * it only on a context created with the same model shape, P, m, variant, replicas, seed and
+ * AdaSync mode (else SSGD_EINVAL, context unchanged), replaces that context's state and trace,
+ * and the updates that follow are those the original context would have run.  The data set is
+ * not part of the snapshot. */
+ssgd_status ssgd_state_bytes(ssgd_ctx *ctx, int64_t *bytes);
+ssgd_status ssgd_get_state(ssgd_ctx *ctx, void *host_buf, int64_t bytes);
+ssgd_status ssgd_set_state(ssgd_ctx *ctx, const void *host_buf, int64_t bytes);
+
 /* Monte-Carlo estimate of the runtime per iteration T (Sec. 2.3, Lemmas 1-3;
  * the simulation behind Fig. 6).  Trial r draws P fresh delays; for every K in
  * [Kmin, Kmax] the variant's event process is run for chain_len updates from that

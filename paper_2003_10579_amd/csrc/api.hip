@@ -519,6 +519,134 @@ ssgd_status ssgd_force_K(ssgd_ctx* c, int32_t K) {
     return SSGD_OK;
 }
 
+ssgd_status ssgd_get_workers(ssgd_ctx* c, int32_t replica, int32_t* tau, int32_t* ord, double* finish) {
+    if (!c) return fail(nullptr, SSGD_EINVAL, "null context");
+    if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
+    if (c->variant != SSGD_K_ASYNC) return fail(c, SSGD_EINVAL, "the synchronous variants keep no mini-batch in flight between updates");
+    HIP_OK(c, hipSetDevice(c->device));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    const size_t off = (size_t)replica * c->P;
+    if (tau) HIP_OK(c, hipMemcpy(tau, c->ws.tau + off, sizeof(int32_t) * c->P, hipMemcpyDeviceToHost));
+    if (ord) HIP_OK(c, hipMemcpy(ord, c->ws.ord + off, sizeof(int32_t) * c->P, hipMemcpyDeviceToHost));
+    if (finish) HIP_OK(c, hipMemcpy(finish, c->ws.finish + off, sizeof(double) * c->P, hipMemcpyDeviceToHost));
+    return SSGD_OK;
+}
+
+namespace {
+
+// Snapshot layout: header, then the trace of the updates done (replica by replica), then every device buffer that
+// later updates depend on, each as raw bytes in the order of state_buffers().
+struct StateHeader {
+    char magic[8];
+    int64_t total_bytes;
+    int32_t kind, d, classes, hidden, P, m, variant, R, Kcap, S, G, ada_mode;
+    int64_t N, nw, j, mlp_bytes;
+    uint64_t seed;
+    int32_t win_cnt, reserved;
+};
+
+std::vector<DevBuf*> state_buffers(ssgd_ctx* c) {
+    std::vector<DevBuf*> b = {&c->ws_finish, &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx,
+                              &c->ws_F0, &c->ws_intstart, &c->ws_crossed, &c->ws_ndone};
+    if (c->model.kind != SSGD_MLP2) { b.push_back(&c->params); b.push_back(&c->park); b.push_back(&c->park_small); }
+    return b;
+}
+
+int64_t trace_bytes(const ssgd_ctx* c, int64_t j) {
+    return (int64_t)c->R * j * (int64_t)(sizeof(double) + sizeof(float) + sizeof(int32_t) + 3 * sizeof(int32_t) * c->Kcap);
+}
+
+StateHeader make_header(ssgd_ctx* c) {
+    StateHeader h{};
+    memcpy(h.magic, "SSGDST01", 8);
+    h.kind = c->model.kind; h.d = c->model.d; h.classes = c->model.classes; h.hidden = c->model.hidden;
+    h.P = c->P; h.m = c->m; h.variant = c->variant; h.R = c->R; h.Kcap = c->Kcap; h.S = c->S; h.G = c->G;
+    h.ada_mode = c->ada.mode; h.N = c->model.N; h.nw = c->nw; h.j = c->j; h.seed = c->seed; h.win_cnt = c->win_cnt;
+    h.mlp_bytes = c->mlp ? mlp_state_bytes(c->mlp) : 0;
+    int64_t n = (int64_t)sizeof(StateHeader) + trace_bytes(c, c->j) + h.mlp_bytes;
+    for (DevBuf* b : state_buffers(c)) n += (int64_t)b->bytes;
+    h.total_bytes = n;
+    return h;
+}
+
+}  // namespace
+
+ssgd_status ssgd_state_bytes(ssgd_ctx* c, int64_t* bytes) {
+    if (!c || !bytes) return fail(c, SSGD_EINVAL, "null argument");
+    *bytes = make_header(c).total_bytes;
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_get_state(ssgd_ctx* c, void* host_buf, int64_t bytes) {
+    if (!c || !host_buf) return fail(c, SSGD_EINVAL, "null argument");
+    if (c->broken) return fail(c, SSGD_ESTATE, "context is unusable after a device error");
+    const StateHeader h = make_header(c);
+    if (bytes < h.total_bytes) return fail(c, SSGD_EINVAL, "buffer smaller than ssgd_state_bytes");
+    HIP_OK(c, hipSetDevice(c->device));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    unsigned char* out = static_cast<unsigned char*>(host_buf);
+    memcpy(out, &h, sizeof(h));
+    size_t off = sizeof(h);
+    const int64_t j = c->j, W = c->Kcap, cap = c->tr.cap;
+    for (int64_t r = 0; r < c->R && j > 0; ++r) {
+        HIP_OK(c, hipMemcpy(out + off, c->tr.t + r * cap, sizeof(double) * j, hipMemcpyDeviceToHost)); off += sizeof(double) * j;
+        HIP_OK(c, hipMemcpy(out + off, c->tr.loss + r * cap, sizeof(float) * j, hipMemcpyDeviceToHost)); off += sizeof(float) * j;
+        HIP_OK(c, hipMemcpy(out + off, c->tr.K + r * cap, sizeof(int32_t) * j, hipMemcpyDeviceToHost)); off += sizeof(int32_t) * j;
+        HIP_OK(c, hipMemcpy(out + off, c->tr.sel + r * cap * W, sizeof(int32_t) * j * W, hipMemcpyDeviceToHost)); off += sizeof(int32_t) * j * W;
+        HIP_OK(c, hipMemcpy(out + off, c->tr.tau + r * cap * W, sizeof(int32_t) * j * W, hipMemcpyDeviceToHost)); off += sizeof(int32_t) * j * W;
+        HIP_OK(c, hipMemcpy(out + off, c->tr.ord + r * cap * W, sizeof(int32_t) * j * W, hipMemcpyDeviceToHost)); off += sizeof(int32_t) * j * W;
+    }
+    for (DevBuf* b : state_buffers(c)) {
+        HIP_OK(c, hipMemcpy(out + off, b->p, b->bytes, hipMemcpyDeviceToHost));
+        off += b->bytes;
+    }
+    if (c->mlp) HIP_OK(c, mlp_get_state(c->mlp, out + off));
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_set_state(ssgd_ctx* c, const void* host_buf, int64_t bytes) {
+    if (!c || !host_buf) return fail(c, SSGD_EINVAL, "null argument");
+    if (c->broken) return fail(c, SSGD_ESTATE, "context is unusable after a device error");
+    if (bytes < (int64_t)sizeof(StateHeader)) return fail(c, SSGD_EINVAL, "not a state snapshot");
+    StateHeader h;
+    memcpy(&h, host_buf, sizeof(h));
+    if (memcmp(h.magic, "SSGDST01", 8) != 0) return fail(c, SSGD_EINVAL, "not a state snapshot");
+    // the snapshot must come from a context of the same configuration
+    StateHeader mine = make_header(c);
+    if (h.kind != mine.kind || h.d != mine.d || h.classes != mine.classes || h.hidden != mine.hidden || h.P != mine.P ||
+        h.m != mine.m || h.variant != mine.variant || h.R != mine.R || h.Kcap != mine.Kcap || h.S != mine.S || h.G != mine.G ||
+        h.ada_mode != mine.ada_mode || h.N != mine.N || h.nw != mine.nw || h.seed != mine.seed || h.mlp_bytes != mine.mlp_bytes)
+        return fail(c, SSGD_EINVAL, "the snapshot was taken from a context of another configuration");
+    if (h.j < 0 || h.total_bytes > bytes) return fail(c, SSGD_EINVAL, "truncated state snapshot");
+    HIP_OK(c, hipSetDevice(c->device));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    c->j = 0;     // nothing of the old trace is kept
+    ssgd_status st = grow_trace(c, h.j);
+    if (st != SSGD_OK) return st;
+    int64_t expect = (int64_t)sizeof(StateHeader) + trace_bytes(c, h.j) + h.mlp_bytes;
+    for (DevBuf* b : state_buffers(c)) expect += (int64_t)b->bytes;
+    if (expect != h.total_bytes) return fail(c, SSGD_EINVAL, "state snapshot of unexpected size");
+    const unsigned char* in = static_cast<const unsigned char*>(host_buf);
+    size_t off = sizeof(h);
+    const int64_t j = h.j, W = c->Kcap, cap = c->tr.cap;
+    for (int64_t r = 0; r < c->R && j > 0; ++r) {
+        HIP_OK(c, hipMemcpy(c->tr.t + r * cap, in + off, sizeof(double) * j, hipMemcpyHostToDevice)); off += sizeof(double) * j;
+        HIP_OK(c, hipMemcpy(c->tr.loss + r * cap, in + off, sizeof(float) * j, hipMemcpyHostToDevice)); off += sizeof(float) * j;
+        HIP_OK(c, hipMemcpy(c->tr.K + r * cap, in + off, sizeof(int32_t) * j, hipMemcpyHostToDevice)); off += sizeof(int32_t) * j;
+        HIP_OK(c, hipMemcpy(c->tr.sel + r * cap * W, in + off, sizeof(int32_t) * j * W, hipMemcpyHostToDevice)); off += sizeof(int32_t) * j * W;
+        HIP_OK(c, hipMemcpy(c->tr.tau + r * cap * W, in + off, sizeof(int32_t) * j * W, hipMemcpyHostToDevice)); off += sizeof(int32_t) * j * W;
+        HIP_OK(c, hipMemcpy(c->tr.ord + r * cap * W, in + off, sizeof(int32_t) * j * W, hipMemcpyHostToDevice)); off += sizeof(int32_t) * j * W;
+    }
+    for (DevBuf* b : state_buffers(c)) {
+        HIP_OK(c, hipMemcpy(b->p, in + off, b->bytes, hipMemcpyHostToDevice));
+        off += b->bytes;
+    }
+    if (c->mlp) HIP_OK(c, mlp_set_state(c->mlp, in + off));
+    c->j = h.j;
+    c->win_cnt = h.win_cnt;
+    return SSGD_OK;
+}
+
 ssgd_status ssgd_debug_delays(const ssgd_delay_dist* dist, const uint32_t* bits, int64_t n, float* out) {
     if (!dist_ok(dist) || dist->kind == SSGD_TABLE || !bits || !out || n < 0) return fail(nullptr, SSGD_EINVAL, "invalid argument");
     if (n == 0) return SSGD_OK;

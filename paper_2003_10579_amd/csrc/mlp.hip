@@ -19,6 +19,7 @@
 #include "mlp.hpp"
 
 #include <cmath>
+#include <cstring>
 #include <vector>
 
 namespace ssgd {
@@ -436,7 +437,8 @@ size_t contract_lds(int bt) { return (size_t)4 * bt * LDT * 2; }
 
 struct DevMem {
     void* p = nullptr;
-    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 16); }
+    size_t bytes = 0;
+    hipError_t alloc(size_t n) { bytes = n; return hipMalloc(&p, n ? n : 16); }
     void release() { if (p) (void)hipFree(p); p = nullptr; }
 };
 
@@ -559,6 +561,44 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
     e = hipGetLastError();
     if (e != hipSuccess) return fail(e, "launching the segment");
     (void)ws;
+    return hipSuccess;
+}
+
+// Everything a later update depends on: parameters (fp32 master and operand copies) and the factors of the
+// mini-batches in flight, slot by slot.
+static std::vector<DevMem*> mlp_state_buffers(MlpState* s) {
+    return {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss,
+            &s->ylab};
+}
+
+int64_t mlp_state_bytes(MlpState* s) {
+    int64_t n = 8;
+    for (DevMem* b : mlp_state_buffers(s)) n += (int64_t)b->bytes;
+    return n;
+}
+
+hipError_t mlp_get_state(MlpState* s, unsigned char* host) {
+    const int64_t k = s->prevK;
+    memcpy(host, &k, 8);
+    size_t off = 8;
+    for (DevMem* b : mlp_state_buffers(s)) {
+        hipError_t e = hipMemcpy(host + off, b->p, b->bytes, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return e;
+        off += b->bytes;
+    }
+    return hipSuccess;
+}
+
+hipError_t mlp_set_state(MlpState* s, const unsigned char* host) {
+    int64_t k = 0;
+    memcpy(&k, host, 8);
+    s->prevK = (int)k;
+    size_t off = 8;
+    for (DevMem* b : mlp_state_buffers(s)) {
+        hipError_t e = hipMemcpy(b->p, host + off, b->bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) return e;
+        off += b->bytes;
+    }
     return hipSuccess;
 }
 

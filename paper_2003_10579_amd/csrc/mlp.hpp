@@ -15,6 +15,10 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
 hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n, float* agg_out,
                            hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg);
 float* mlp_params(MlpState* s);
+// Snapshot of everything later updates depend on (host memory; the stream must be idle).
+int64_t mlp_state_bytes(MlpState* s);
+hipError_t mlp_get_state(MlpState* s, unsigned char* host);
+hipError_t mlp_set_state(MlpState* s, const unsigned char* host);
 void mlp_destroy(MlpState* s);
 
 void set_global_error(const std::string& msg);

@@ -20,6 +20,7 @@ _KINDS = {"lsq": LSQ, "softmax": SOFTMAX, "mlp2": MLP2}
 EXPORTS = [
     "ssgd_create", "ssgd_run", "ssgd_reserve_trace", "ssgd_step", "ssgd_param_count", "ssgd_updates_done", "ssgd_current_K",
     "ssgd_trace_width", "ssgd_get_trace", "ssgd_get_params", "ssgd_set_params", "ssgd_force_K",
+    "ssgd_get_workers", "ssgd_state_bytes", "ssgd_get_state", "ssgd_set_state",
     "ssgd_runtime_mc", "ssgd_debug_delays", "ssgd_debug_batch", "ssgd_last_error", "ssgd_last_kernel_ms",
     "ssgd_destroy",
 ]
@@ -84,6 +85,10 @@ def lib():
         L.ssgd_get_params.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.ssgd_set_params.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.ssgd_force_K.argtypes = [C.c_void_p, C.c_int32]
+        L.ssgd_get_workers.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ssgd_state_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+        L.ssgd_get_state.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        L.ssgd_set_state.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
         L.ssgd_runtime_mc.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(DelayDist), C.c_int64,
                                       C.c_int64, C.c_int32, C.c_uint64, C.c_void_p] + [C.c_void_p] * 5
         L.ssgd_debug_delays.argtypes = [C.POINTER(DelayDist), C.c_void_p, C.c_int64, C.c_void_p]
@@ -184,6 +189,24 @@ class Context:
 
     def force_K(self, K):
         _check(lib().ssgd_force_K(self.h, K), self.h)
+
+    def workers(self, replica=0):
+        tau = np.zeros(self.P, dtype=np.int32)
+        ordn = np.zeros(self.P, dtype=np.int32)
+        finish = np.zeros(self.P, dtype=np.float64)
+        _check(lib().ssgd_get_workers(self.h, replica, tau.ctypes.data, ordn.ctypes.data, finish.ctypes.data), self.h)
+        return dict(tau=tau, ordinal=ordn, finish=finish)
+
+    def get_state(self):
+        n = C.c_int64()
+        _check(lib().ssgd_state_bytes(self.h, C.byref(n)), self.h)
+        buf = np.zeros(n.value, dtype=np.uint8)
+        _check(lib().ssgd_get_state(self.h, buf.ctypes.data, n.value), self.h)
+        return buf
+
+    def set_state(self, buf):
+        buf = np.ascontiguousarray(buf, dtype=np.uint8)
+        _check(lib().ssgd_set_state(self.h, buf.ctypes.data, buf.size), self.h)
 
     def params(self, replica=0):
         w = np.zeros(self.nw, dtype=np.float32)

@@ -546,3 +546,89 @@ def test_adasync_ksync_rule_with_growing_tile_count(ssgd, oracle, torch_cuda):
     assert np.allclose(g["loss"], o["loss"], rtol=2e-4, atol=1e-6)
     assert rel(ctx.params(), tr.params()) <= PARAM_TOL
     ctx.close()
+
+
+# ------------------------------------------------------------------------------- worker state, snapshot and resume
+
+def test_workers_in_flight_bit_exact(ssgd, oracle, torch_cuda):
+    """tau_i and f_i of every K-async worker after a run, against the oracle's event state."""
+    torch = torch_cuda
+    X, y, _ = synth.lsq_data(256, 8, 1)
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.2, 1.0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    ctx = ssgd.Context("lsq", Xd, yd, 24, 5, 4, "k_async", gd, 0.01, seed=11)
+    tr = oracle.Trainer(oracle.Model("lsq", X, y), 24, 5, 4, "k_async", od, 0.01, seed=11)
+    ctx.run(333)
+    tr.run(333)
+    g = ctx.workers()
+    otau, ofinish = tr.workers()
+    assert np.array_equal(g["tau"].astype(np.int64), otau)
+    assert np.array_equal(g["finish"], ofinish)
+    ctx.close()
+    sync = ssgd.Context("lsq", Xd, yd, 4, 2, 4, "k_sync", gd, 0.01, seed=11)
+    with pytest.raises(ssgd.SsgdError):
+        sync.workers()
+    sync.close()
+
+
+@pytest.mark.parametrize("kind,variant,P,K,m,d,classes,ada", [
+    ("softmax", "k_async", 8, 2, 32, 512, 10, None),                 # steady-state kernel, parked gradients in flight
+    ("softmax", "k_batch_sync", 5, 6, 40, 260, 4, None),             # iterations of several tiles
+    ("lsq", "k_async", 12, 2, 6, 30, 1, dict(mode=1, K0=2, Kmax=12, window=16, rel_tol=0.5)),   # general kernel, AdaSync window open
+])
+def test_snapshot_resume_continues_the_same_run(ssgd, oracle, torch_cuda, kind, variant, P, K, m, d, classes, ada):
+    """A run that is snapshotted and resumed in a new context is the run that was never interrupted: identical trace
+    and parameters, bit for bit (every sum on the device is taken in a fixed order); the oracle agrees with both."""
+    torch = torch_cuda
+    if kind == "lsq":
+        X, y, _ = synth.lsq_data(900, d, 12)
+    else:
+        X, y = synth.mixture_data(900, d, classes, seed=12)
+    gd, od = dist_pair(ssgd, oracle, ("exp", 1.0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    mk = lambda: ssgd.Context(kind, Xd, yd, P, K, m, variant, gd, 0.03, seed=13, classes=classes, replicas=3, adasync=ada)
+    a = mk()
+    a.run(57)
+    blob = a.get_state()
+    a.run(43)
+    b = mk()
+    b.run(5)                 # whatever the receiving context did before is replaced
+    b.set_state(blob)
+    assert b.updates == 57
+    b.run(43)
+    for r in range(3):
+        ta, tb = a.trace(r), b.trace(r)
+        for key in ta:
+            assert np.array_equal(ta[key], tb[key]), (r, key)
+        assert np.array_equal(a.params(r), b.params(r)), r
+    tr = oracle.Trainer(oracle.Model(kind, X, y, classes=classes), P, K, m, variant, od, 0.03, seed=13, replica=2, adasync=ada)
+    tr.run(100)
+    assert_trace_equal(b.trace(2), tr.trace())
+    assert rel(b.params(2), tr.params()) <= PARAM_TOL
+    # a snapshot of another configuration is refused and leaves the context as it was
+    other = ssgd.Context(kind, Xd, yd, P, K, m, variant, gd, 0.03, seed=14, classes=classes, replicas=3, adasync=ada)
+    with pytest.raises(ssgd.SsgdError):
+        other.set_state(blob)
+    assert other.updates == 0
+    for c in (a, b, other):
+        c.close()
+
+
+def test_mlp_snapshot_resume(ssgd, oracle, torch_cuda):
+    torch = torch_cuda
+    X, y = synth.mixture_data(600, 256, 5, seed=15)
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    mk = lambda: ssgd.Context("mlp2", Xd, yd, 6, 2, 16, "k_async", gd, 0.05, seed=16, classes=5, hidden=128, bf16=1)
+    a = mk()
+    a.run(9)
+    blob = a.get_state()
+    a.run(7)
+    b = mk()
+    b.set_state(blob)
+    b.run(7)
+    ta, tb = a.trace(), b.trace()
+    for key in ta:
+        assert np.array_equal(ta[key], tb[key]), key
+    assert np.array_equal(a.params(), b.params())
+    a.close(); b.close()

@@ -73,3 +73,12 @@ def test_runtime_mc_rejects_invalid_arguments(L):
     for bad in (dict(P=0), dict(P=300), dict(Kmin=0), dict(Kmax=9), dict(trials=0), dict(chain=0),
                 dict(variant=ssgd.K_BATCH_ASYNC), dict(Kmax=128, P=128, chain=5000)):
         assert L.ssgd_runtime_mc(*args(**bad)) == ssgd.EINVAL
+
+
+def test_state_entry_points_reject_null_arguments(L):
+    n = C.c_int64(0)
+    buf = (C.c_ubyte * 16)()
+    assert L.ssgd_state_bytes(None, C.byref(n)) == ssgd.EINVAL
+    assert L.ssgd_get_state(None, buf, 16) == ssgd.EINVAL
+    assert L.ssgd_set_state(None, buf, 16) == ssgd.EINVAL
+    assert L.ssgd_get_workers(None, 0, None, None, None) == ssgd.EINVAL
