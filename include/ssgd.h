@@ -52,7 +52,10 @@ typedef enum {
     SSGD_K_SYNC = 0,       /* Eq. (2): first K of P workers, the rest are cancelled */
     SSGD_K_BATCH_SYNC = 1, /* first K mini-batches; a finished worker starts another at w_j */
     SSGD_K_ASYNC = 2,      /* Eq. (3): first K of P workers, nobody is cancelled, stale w */
-    SSGD_K_BATCH_ASYNC = 3 /* first K mini-batches, immediate re-fetch (not built yet) */
+    SSGD_K_BATCH_ASYNC = 3 /* first K mini-batches, nobody is cancelled: a worker that pushes re-reads the
+                              current parameters and starts its next mini-batch at once.  Linear models
+                              with 128 < d, d % 4 == 0, at most 15 classes, m <= 64, K <= 32 and
+                              P + K - 1 <= 64; fixed K or AdaSync mode 1; else SSGD_EINVAL */
 } ssgd_variant;
 
 /* Delay X of one mini-batch on one worker (Sec. 3.1).

@@ -236,9 +236,10 @@ ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_ou
     if (tile) {
         a.v0 = v0;
         if (c->variant == SSGD_K_ASYNC && v0 == 0) { head = 1; a.v0 = 1; }
-        a.chunked = (c->variant != SSGD_K_ASYNC && a.mp * c->Kcap > 64) ? 1 : 0;
+        a.chunked = ((c->variant == SSGD_K_SYNC || c->variant == SSGD_K_BATCH_SYNC) && a.mp * c->Kcap > 64) ? 1 : 0;
         tile = linear_tile_supports(a, c->Kcap);
     }
+    if (!tile && c->variant == SSGD_K_BATCH_ASYNC) return fail(c, SSGD_EINVAL, "K-batch-async: the cluster of this shape does not fit the device");
     if (!tile) return launch_steps(c, v0, n, agg_out, false, events);
     if (head > 0) {
         ssgd_status st = launch_steps(c, v0, std::min(head, n), agg_out, false, events);
@@ -324,7 +325,6 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
     if (!model->X || !model->y || model->N < 1 || model->N >= (1ll << 32) || model->d < 1)
         return fail(nullptr, SSGD_EINVAL, "invalid data set description");
     if (variant < SSGD_K_SYNC || variant > SSGD_K_BATCH_ASYNC) return fail(nullptr, SSGD_EINVAL, "unknown variant");
-    if (variant == SSGD_K_BATCH_ASYNC) return fail(nullptr, SSGD_EINVAL, "K-batch-async is not built yet");
     if (P < 1 || P > kMaxWorkers || K < 1 || m < 1 || m > 65535 || replicas < 1 || !(lr >= 0))
         return fail(nullptr, SSGD_EINVAL, "P, K, m, replicas or lr out of range");
     ssgd_adasync ada{};
@@ -339,6 +339,15 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
     const int32_t Kcap = ada.Kmax;
     if ((variant == SSGD_K_SYNC || variant == SSGD_K_ASYNC) && Kcap > P) return fail(nullptr, SSGD_EINVAL, "K must not exceed P");
     if (Kcap > kMaxWorkers) return fail(nullptr, SSGD_EINVAL, "K must not exceed 256");
+    if (variant == SSGD_K_BATCH_ASYNC) {
+        // this variant runs through the steady-state kernel of the linear models only
+        const int32_t mp = (m + 3) / 4 * 4;
+        const int32_t classes = model->kind == SSGD_LSQ ? 1 : model->classes;
+        if (model->kind == SSGD_MLP2 || model->d <= 128 || model->d % 4 != 0 || classes > 15 || mp > 64 || Kcap > 32 ||
+            P + Kcap - 1 > 64 || ada.mode >= 2)
+            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models with 128 < d, d % 4 == 0, at most 15 classes, m <= 64, "
+                                             "K <= 32, P + K - 1 <= 64, fixed K or plateau doubling");
+    }
     if (model->kind == SSGD_LSQ) {
         if (model->bf16) return fail(nullptr, SSGD_EINVAL, "bf16 is for the MLP only");
     } else if (model->kind == SSGD_SOFTMAX) {
@@ -401,7 +410,7 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         if (const char* e = getenv("SSGD_NBW")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->nbw = v; }
         const int SL = 64 * c->nbw;
         c->G = (d + SL - 1) / SL;
-        const bool async = variant == SSGD_K_ASYNC;
+        const bool async = variant == SSGD_K_ASYNC || variant == SSGD_K_BATCH_ASYNC;   // gradients are parked per worker
         c->S = async ? P : Kcap;
         const int C = model->kind == SSGD_LSQ ? 1 : model->classes;
         c->maxrows = 64 * chunks_for(async ? std::max(P, Kcap) : Kcap, c->mp);
@@ -522,7 +531,8 @@ ssgd_status ssgd_force_K(ssgd_ctx* c, int32_t K) {
 ssgd_status ssgd_get_workers(ssgd_ctx* c, int32_t replica, int32_t* tau, int32_t* ord, double* finish) {
     if (!c) return fail(nullptr, SSGD_EINVAL, "null context");
     if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
-    if (c->variant != SSGD_K_ASYNC) return fail(c, SSGD_EINVAL, "the synchronous variants keep no mini-batch in flight between updates");
+    if (c->variant != SSGD_K_ASYNC && c->variant != SSGD_K_BATCH_ASYNC)
+        return fail(c, SSGD_EINVAL, "the synchronous variants keep no mini-batch in flight between updates");
     HIP_OK(c, hipSetDevice(c->device));
     HIP_OK(c, hipStreamSynchronize(c->stream));
     const size_t off = (size_t)replica * c->P;

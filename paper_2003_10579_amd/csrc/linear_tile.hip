@@ -95,7 +95,7 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int KIND, bool PROF, bool WHOLE, bool CHUNKED>
+template <int KIND, bool PROF, bool WHOLE, bool CHUNKED, bool BATCH>
 __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     // consecutive block ids go to different XCDs: all slices of one cluster take block ids that
     // are congruent modulo 8 and share one L2
@@ -177,21 +177,42 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         };
         // The lists of version `ver` (in flight in q_*) become the description of its tiles.
         int h_worker = -1, h_ord = 0, h_nrec = 0, h_tiles = 1;
+        int h_recword = 0, h_nstale = 0;         // K-batch-async: all records of the version, tile by tile below
+        const int rpt = ROWS / mp;               // K-batch-async: whole records per tile
         auto take_lists = [&](int64_t ver, bool more) {
             const int l_sel = q_sel, l_tau = q_tau, l_ord = q_ord;
             const int K = __popcll(__ballot(l_sel >= 0));
-            const int nrec = async ? __popcll(__ballot(cur_sel >= 0)) : K;
-            const int rec_slot = async ? cur_sel : lane;
+            int nrec = async ? __popcll(__ballot(cur_sel >= 0)) : K;
+            int rec_slot = async ? cur_sel : lane;
+            int rec_ord = async ? 0 : l_ord;
             int fr = (!async && lane < K) ? 1 : 0;
             if (async)
                 for (int l = 0; l < K; ++l)
                     if (__builtin_amdgcn_readlane(l_tau, l) == (int32_t)ver && __builtin_amdgcn_readlane(l_sel, l) == rec_slot) fr = 1;
+            if constexpr (BATCH) {
+                // Mini-batches that start at version ver: at ver = 0 every worker's first one, later the one of the
+                // worker whose push triggered update ver - 1; then, for each of the first K - 1 pushes of update ver,
+                // the next mini-batch of the pushing worker (ordinal: how many it has started at this version).
+                // Record r sits in lane r.
+                const int Kprev = __popcll(__ballot(cur_sel >= 0));
+                const int first = (ver == 0) ? a.P : 1;
+                nrec = first + K - 1;
+                const int l = min(max(lane - first, 0), 63);
+                const int p_sel = __shfl(l_sel, l, 64), p_tau = __shfl(l_tau, l, 64), p_ord = __shfl(l_ord, l, 64);
+                const int trigger = (ver == 0) ? lane : __builtin_amdgcn_readlane(cur_sel, max(Kprev - 1, 0));
+                rec_slot = (lane < first) ? trigger : p_sel;
+                rec_ord = (lane < first) ? 0 : ((p_tau == (int32_t)ver) ? p_ord + 1 : 0);
+                fr = 0;     // consumed by update ver itself?
+                for (int q = 0; q < K; ++q)
+                    if (__builtin_amdgcn_readlane(l_sel, q) == rec_slot && __builtin_amdgcn_readlane(l_tau, q) == (int32_t)ver &&
+                        __builtin_amdgcn_readlane(l_ord, q) == rec_ord) fr = 1;
+            }
             n_K = K;
             // parked gradients that update ver consumes: entries whose version is older, compacted
             const bool is_stale = lane < K && l_tau != (int32_t)ver;
             const unsigned long long smask = __ballot(is_stale);
             n_nstale = __popcll(smask);
-            n_stale = async ? l_sel : lane;
+            n_stale = (async || BATCH) ? l_sel : lane;
             n_stale_pos = is_stale ? __popcll(smask & ((1ull << lane) - 1ull)) : KC;
             if (chunked) {
                 // every tile is one record of 64 rows that update ver consumes itself
@@ -201,10 +222,15 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 n_nrec = nrec;
                 n_rec_word = (lane < nrec) ? (rec_slot | (fr << 16)) : 0;
             }
-            h_worker = async ? cur_sel : l_sel;      // lane r: worker of record r
-            h_ord = async ? 0 : l_ord;
+            h_worker = BATCH ? rec_slot : (async ? cur_sel : l_sel);      // lane r: worker of record r
+            h_ord = rec_ord;
             h_nrec = nrec;
             h_tiles = chunked ? max(1, (nrec * mp + ROWS - 1) / ROWS) : 1;
+            if constexpr (BATCH) {
+                h_recword = n_rec_word;
+                h_nstale = n_nstale;
+                h_tiles = max(1, (nrec + rpt - 1) / rpt);
+            }
             cur_sel = l_sel;
             asm volatile("" : "+v"(n_stale), "+v"(n_stale_pos), "+v"(n_rec_word), "+v"(cur_sel), "+v"(h_worker), "+v"(h_ord) : : "memory");
             if (more) issue_lists(ver + 1);
@@ -213,6 +239,14 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         auto make_tile = [&](int64_t ver, int t) {
             int rec = r_of, smp = s_of;
             if (chunked) { const int q = t * ROWS + lane; rec = q / mp; smp = q - rec * mp; }
+            if constexpr (BATCH) {
+                // records t * rpt .. of the version; the parked part of the update comes with the first tile
+                rec = (r_of < rpt) ? t * rpt + r_of : 64;
+                n_nrec = min(rpt, h_nrec - t * rpt);
+                n_rec_word = __shfl(h_recword, min(t * rpt + lane, 63), 64);
+                if (lane >= n_nrec) n_rec_word = 0;
+                n_nstale = (t == 0) ? h_nstale : 0;
+            }
             const int worker = __shfl(h_worker, min(rec, 63), 64);
             const int ordinal = __shfl(h_ord, min(rec, 63), 64);
             row_id = kNoRow;
@@ -297,12 +331,15 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             if ((flags & 1) != 0) {
                 if (KIND == kSoftmax && lane < C) L.bias[lane] -= (a.lr / (float)Kv) * tot;
                 if (lane == 15 && slice == 0) a.tr.loss[(int64_t)rep * cap + v] = tot * (1.0f / (float)Kv);
+                // the averaged gradient of replica 0, when the caller asked for it: bias part
+                if (KIND == kSoftmax && a.agg_out != nullptr && rep == 0 && slice == 0 && lane < C)
+                    a.agg_out[(int64_t)C * d + lane] = tot * (1.0f / (float)Kv);
             }
         };
 
         lds_barrier();                               // the compute waves have set up the control words
         if (L.ctl[0] != 0) return;
-        if (async && lane < Kcap) cur_sel = tr_sel[(a.v0 - 1) * Kcap + lane];   // v0 >= 1 for K-async
+        if ((async || (BATCH && a.v0 >= 1)) && lane < Kcap) cur_sel = tr_sel[(a.v0 - 1) * Kcap + lane];   // v0 >= 1 for K-async
         issue_lists(a.v0);
         take_lists(a.v0, a.nsteps > 1);
         make_tile(a.v0, 0);
@@ -830,6 +867,18 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                     *wp = w;
                 }
             }
+            if (a.agg_out != nullptr && rep == 0) {
+                // the averaged gradient of replica 0, when the caller asked for it
+                const float invK = 1.0f / (float)Kv;
+#pragma unroll
+                for (int vv = 0; vv < 4; ++vv) {
+                    const int cls = own_cls + vv;
+                    if (cls < C)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            if (own_col + c < d) a.agg_out[(int64_t)cls * d + own_col + c] = gsum[vv * 4 + c] * invK;
+                }
+            }
         }
         if (tid == 0 && L.ctl[2] != 0) L.ctl[1] = 1;   // later exchanges of this launch use the shared L2
         mark(7);
@@ -856,23 +905,26 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     for (int q = tid; q < S * 17; q += NTC) small_g[q] = L.small[q];
 }
 
-template <int KIND, bool PROF, bool WHOLE, bool CHUNKED>
+template <int KIND, bool PROF, bool WHOLE, bool CHUNKED, bool BATCH>
 hipError_t launch_w(const LinArgs& a, size_t lds, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<KIND, PROF, WHOLE, CHUNKED>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<KIND, PROF, WHOLE, CHUNKED, BATCH>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const int groups = (a.replicas + 7) / 8;
     const int blocks = a.pair_cus > 0 ? 8 * a.pair_cus * a.pair_layers : groups * 8 * a.G;
-    hipLaunchKernelGGL((linear_tile_kernel<KIND, PROF, WHOLE, CHUNKED>), dim3(blocks), dim3(512), lds, s, a);
+    hipLaunchKernelGGL((linear_tile_kernel<KIND, PROF, WHOLE, CHUNKED, BATCH>), dim3(blocks), dim3(512), lds, s, a);
     return hipGetLastError();
 }
 
 // WHOLE: every record is a whole number of 32-row blocks, so the gradient contraction is fully unrolled;
-// CHUNKED: an iteration spans several tiles
+// CHUNKED: an iteration spans several tiles; BATCH: K-batch-async record lists
 template <int KIND, bool PROF>
 hipError_t launch_k(const LinArgs& a, size_t lds, hipStream_t s) {
-    if (a.chunked) return launch_w<KIND, PROF, true, true>(a, lds, s);      // tiles of one 64-row record
-    return (a.mp == 32 || a.mp == 64) ? launch_w<KIND, PROF, true, false>(a, lds, s) : launch_w<KIND, PROF, false, false>(a, lds, s);
+    if (a.chunked) return launch_w<KIND, PROF, true, true, false>(a, lds, s);      // tiles of one 64-row record
+    const bool whole = a.mp == 32 || a.mp == 64;
+    if (a.variant == kBatchAsync)        // (no phase profile for this variant)
+        return whole ? launch_w<KIND, false, true, false, true>(a, lds, s) : launch_w<KIND, false, false, false, true>(a, lds, s);
+    return whole ? launch_w<KIND, PROF, true, false, false>(a, lds, s) : launch_w<KIND, PROF, false, false, false>(a, lds, s);
 }
 
 }  // namespace
@@ -884,12 +936,16 @@ size_t linear_tile_lds_bytes(int C, int S) {
 
 bool linear_tile_supports(const LinArgs& a, int max_records) {
     if (a.C > 15 || (a.d % 4) != 0 || a.tr.Kcap > KC || max_records > KC) return false;
-    if (a.mp * max_records > ROWS && !a.chunked) return false;
+    if (a.mp * max_records > ROWS && !a.chunked && a.variant != kBatchAsync) return false;
     if (a.chunked && a.variant == kAsync) return false;
     if ((uint64_t)a.N * (uint64_t)a.d * 4u >= (1ull << 32)) return false;   // one buffer descriptor spans the sample matrix
+    if (a.variant == kBatchAsync) {
+        // whole records per tile, every record of a version in one lane each (version 0: P + K - 1 of them)
+        if (a.mp > ROWS || a.P + a.tr.Kcap - 1 > 64) return false;
+        return linear_tile_lds_bytes(a.C, a.S) <= 160 * 1024;
+    }
     if (a.agg_out != nullptr) return false;
     if (a.variant == kAsync && a.v0 < 1) return false;    // step 0 of K-async starts all P workers
-    if (a.variant == kBatchAsync) return false;
     return linear_tile_lds_bytes(a.C, a.S) <= 160 * 1024;
 }
 
@@ -897,9 +953,9 @@ int linear_tile_resident_groups(size_t lds_bytes) {
     int dev = 0, per_cu = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<kSoftmax, false, false, false>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(linear_tile_kernel<kSoftmax, false, false, false, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, linear_tile_kernel<kSoftmax, false, false, false>, 512, lds_bytes) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, linear_tile_kernel<kSoftmax, false, false, false, false>, 512, lds_bytes) != hipSuccess) return 0;
     return per_cu * prop.multiProcessorCount;
 }
 

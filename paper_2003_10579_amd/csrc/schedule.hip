@@ -184,6 +184,29 @@ __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
                 }
             }
             t_new = clock + last;
+        } else if (a.variant == kBatchAsync) {
+            // K-batch-async: the K earliest mini-batches contribute, whoever computed them.  A worker that pushes
+            // one of the first K-1 re-reads the parameters (still w_j) and starts its next mini-batch at once; the
+            // K-th push triggers update j, and that worker reads w_{j+1}.
+            for (int l = 0; l < K; ++l) {
+                const Best b = wave_min(local_min(key, 0u, lane, P), width);
+                t_new = b.key;
+                if ((b.id & 63) == lane) {
+                    const int q = b.id >> 6;
+#pragma unroll
+                    for (int qq = 0; qq < NQ; ++qq) {
+                        if (qq != q) continue;
+                        tr_sel[j * Kcap + l] = b.id; tr_tau[j * Kcap + l] = tau[qq]; tr_ord[j * Kcap + l] = ord[qq];
+                        if (l + 1 < K) {
+                            if (tau[qq] == (int32_t)j) ord[qq] += 1; else { tau[qq] = (int32_t)j; ord[qq] = 0; }
+                            key[qq] = key[qq] + (double)draw_delay(b.id, ord[qq], ver);
+                        } else {
+                            tau[qq] = (int32_t)(j + 1); ord[qq] = 0;
+                            key[qq] = t_new + (double)draw_delay(b.id, 0, ver + 1u);
+                        }
+                    }
+                }
+            }
         } else {
             // K-async: the K earliest finishers contribute; only they restart, at t_{j+1}.  The delay a
             // worker would draw if it restarted now depends on (worker, version) only, so every lane

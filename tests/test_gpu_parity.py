@@ -632,3 +632,57 @@ def test_mlp_snapshot_resume(ssgd, oracle, torch_cuda):
         assert np.array_equal(ta[key], tb[key]), key
     assert np.array_equal(a.params(), b.params())
     a.close(); b.close()
+
+
+# ------------------------------------------------------------------------------- K-batch-async
+
+@pytest.mark.parametrize("kind,P,K,m,d,classes,spec", [
+    ("softmax", 8, 2, 32, 320, 10, ("shifted_exp", 0.5, 1.0)),   # the shape of config 1, two slices
+    ("lsq", 6, 4, 10, 132, 1, ("exp", 1.0)),                      # padded mini-batches, five records per tile
+    ("softmax", 5, 7, 16, 260, 3, ("pareto", 2.5, 1.0)),          # K > P: workers push several times per update
+    ("softmax", 12, 3, 64, 516, 15, ("exp", 2.5)),                # one record per tile: 14 tiles at version 0
+])
+def test_kbatch_async_parity(ssgd, oracle, torch_cuda, kind, P, K, m, d, classes, spec):
+    """K-batch-async (Sec. 2.2): delays, selections, ordinals and staleness bit for bit, per-update averaged gradients
+    and final parameters within tolerance, free-running against the oracle."""
+    if kind == "lsq":
+        X, y, _ = synth.lsq_data(1000, d, 21)
+    else:
+        X, y = synth.mixture_data(1000, d, classes, seed=21)
+    _run_pair(ssgd, oracle, torch_cuda, kind, X, y, P, K, m, "k_batch_async", spec, 0.03, 150, seed=22, classes=classes,
+              check_steps=50)
+
+
+def test_kbatch_async_long_schedule_and_workers(ssgd, oracle, torch_cuda):
+    """2000 updates with P = 40 workers and K = 9: the trace and the workers' in-flight state (tau_i, f_i) against
+    the oracle, then a snapshot taken mid-run resumes to the same end."""
+    torch = torch_cuda
+    X, y, _ = synth.lsq_data(400, 132, 23)
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.2, 1.0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    mk = lambda: ssgd.Context("lsq", Xd, yd, 40, 9, 2, "k_batch_async", gd, 0.01, seed=24)
+    ctx = mk()
+    tr = oracle.Trainer(oracle.Model("lsq", X, y), 40, 9, 2, "k_batch_async", od, 0.01, seed=24)
+    ctx.run(1200)
+    blob = ctx.get_state()
+    ctx.run(800)
+    tr.run(2000)
+    assert_trace_equal(ctx.trace(), tr.trace())
+    g = ctx.workers()
+    otau, ofinish = tr.workers()
+    assert np.array_equal(g["tau"].astype(np.int64), otau)
+    assert np.array_equal(g["finish"], ofinish)
+    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
+    other = mk()
+    other.set_state(blob)
+    other.run(800)
+    assert np.array_equal(other.params(), ctx.params())
+    ctx.close(); other.close()
+
+
+def test_kbatch_async_unsupported_shapes_are_refused(ssgd, torch_cuda):
+    torch = torch_cuda
+    X, y, _ = synth.lsq_data(64, 64, 1)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    with pytest.raises(ssgd.SsgdError):
+        ssgd.Context("lsq", Xd, yd, 4, 2, 8, "k_batch_async", ssgd.delay_dist("exp", 1.0), 0.01)
