@@ -170,8 +170,9 @@ ssgd_status ssgd_set_state(ssgd_ctx *ctx, const void *host_buf, int64_t bytes);
 /* Monte-Carlo estimate of the runtime per iteration T (Sec. 2.3, Lemmas 1-3;
  * the simulation behind Fig. 6).  Trial r draws P fresh delays; for every K in
  * [Kmin, Kmax] the variant's event process is run for chain_len updates from that
- * fresh start and T_l (l = 1..chain_len) is recorded.  Supported: SSGD_K_SYNC,
- * SSGD_K_BATCH_SYNC, SSGD_K_ASYNC.  P <= 256, chain_len <= 4096 (else
+ * fresh start and T_l (l = 1..chain_len) is recorded; for SSGD_K_BATCH_ASYNC (Lemma 5)
+ * the pushes of all workers form one sequence for every K and update l is push l K.
+ * P <= 256, chain_len <= 4096, for SSGD_K_BATCH_ASYNC chain_len * Kmax <= 7500 (else
  * SSGD_EINVAL).  Outputs are HOST arrays of
  * (Kmax-Kmin+1) x chain_len entries: mean and unbiased variance of T_l, and
  * (nullable) the raw sums `sum` and `sumsq`; per_trial (HOST, nullable,

@@ -762,6 +762,8 @@ void orc_get_workers(const orc_ctx *c, int64_t *tau, double *finish)
 /*   K-sync        every update is a fresh start: T_l = K-th smallest of P    */
 /*   K-batch-sync  every update is a fresh start with immediate re-draws      */
 /*   K-async       contributors restart at t_l, the rest keep running         */
+/*   K-batch-async every push restarts its worker at once: one push sequence  */
+/*                 for all K, update l at push l*K (Lemma 5)                  */
 /* sum / sumsq: [(Kmax-Kmin+1) x chain_len] fp64 accumulators, added to.      */
 /* per_trial (nullable): [ntrials x nK x chain_len] fp64.                     */
 /* ------------------------------------------------------------------------- */
@@ -777,8 +779,7 @@ int orc_runtime_mc(int32_t variant, int32_t P, int32_t Kmin, int32_t Kmax, const
                    double *sum, double *sumsq, double *per_trial)
 {
     if (P < 1 || Kmin < 1 || Kmax < Kmin || chain_len < 1 || ntrials < 0) return 1;
-    if (variant != ORC_K_BATCH_SYNC && Kmax > P) return 1;
-    if (variant == ORC_K_BATCH_ASYNC) return 1;
+    if (variant != ORC_K_BATCH_SYNC && variant != ORC_K_BATCH_ASYNC && Kmax > P) return 1;
     const int32_t nK = Kmax - Kmin + 1;
     double *first = (double *)malloc(sizeof(double) * P);
     double *f = (double *)malloc(sizeof(double) * P);
@@ -788,6 +789,34 @@ int orc_runtime_mc(int32_t variant, int32_t P, int32_t Kmin, int32_t Kmax, const
     for (int64_t q = 0; q < ntrials; ++q) {
         uint32_t trial = (uint32_t)(trial0 + q);
         for (int32_t i = 0; i < P; ++i) first[i] = (double)mc_delay(dist, seed, trial, P, 0, i, 0, 0);
+        if (variant == ORC_K_BATCH_ASYNC) {
+            /* No worker ever waits: each pushes mini-batch after mini-batch, whatever K is (the
+             * K-th pusher of an update restarts at its own finish time, which is the update time).
+             * The pushes of all workers, merged in time order, are one sequence p_1 <= p_2 <= ...
+             * shared by every K, and update l of K-batch-async happens at push l*K (the
+             * superposition of renewal processes in the proof of Lemma 5):
+             * T_l = p_{lK} - p_{(l-1)K}.  Worker i's n-th delay is keyed by (worker i, version n). */
+            const int64_t npush = (int64_t)chain_len * Kmax;
+            double *push = (double *)malloc(sizeof(double) * (size_t)(npush + 1));
+            push[0] = 0.0;
+            for (int32_t i = 0; i < P; ++i) { f[i] = first[i]; r[i] = 0; }
+            for (int64_t n = 1; n <= npush; ++n) {
+                int32_t i = argmin_free(f, NULL, P);
+                push[n] = f[i];
+                r[i] += 1;
+                f[i] = f[i] + (double)mc_delay(dist, seed, trial, P, 0, i, 0, (uint32_t)r[i]);
+            }
+            for (int32_t K = Kmin; K <= Kmax; ++K)
+                for (int32_t l = 0; l < chain_len; ++l) {
+                    double T = push[(int64_t)(l + 1) * K] - push[(int64_t)l * K];
+                    int64_t cell = (int64_t)(K - Kmin) * chain_len + l;
+                    if (sum) sum[cell] += T;
+                    if (sumsq) sumsq[cell] += T * T;
+                    if (per_trial) per_trial[(q * nK + (K - Kmin)) * chain_len + l] = T;
+                }
+            free(push);
+            continue;
+        }
         for (int32_t K = Kmin; K <= Kmax; ++K) {
             double t = 0.0;
             for (int32_t i = 0; i < P; ++i) f[i] = first[i];

@@ -182,6 +182,41 @@ __global__ __launch_bounds__(64) void mc_kernel(McArgs a) {
             const int w = q * 64 + lane;
             base[q] = (w < P) ? (double)delay(a.dist, a.seed, kMonteCarlo, 0, trial, P, 1, w, 0, 0) : inf64();
         }
+        if (a.variant == kBatchAsync) {
+            // No worker ever waits, whatever K is: the pushes of all workers merged in time order are one sequence
+            // shared by every K, and update l happens at push l K (the superposition of renewal processes behind
+            // Lemma 5).  The sequence goes to LDS; worker w's n-th delay is keyed by (worker w, version n).
+            double* push = acc + 2 * cells_max;
+            const int npush = L * a.Kmax;
+            double key[NQ];
+            uint32_t started[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) { key[q] = base[q]; started[q] = 0; }
+            if (lane == 0) push[0] = 0.0;
+            for (int n = 1; n <= npush; ++n) {
+                const Best b = wave_argmin<NQ>(key, lane);
+                if (lane == 0) push[n] = b.key;
+                if ((b.id & 63) == lane) {
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q)
+                        if ((b.id >> 6) == q) {
+                            started[q] += 1;
+                            key[q] = key[q] + (double)delay(a.dist, a.seed, kMonteCarlo, 0, trial, P, 1, b.id, 0, started[q]);
+                        }
+                }
+            }
+            __syncthreads();
+            for (int c = lane; c < cells; c += 64) {       // one lane per (K, update) cell of this block
+                const int kk = c / L, l = c - kk * L;
+                const int K = a.Kmin + slice + kk * a.nslices;
+                const double T = push[(l + 1) * K] - push[l * K];
+                acc[2 * c] += T;
+                acc[2 * c + 1] += T * T;
+                if (a.per_trial) a.per_trial[(q0 * nK + (K - a.Kmin)) * L + l] = T;
+            }
+            __syncthreads();
+            continue;
+        }
         double sorted0[NQ];
 #pragma unroll
         for (int q = 0; q < NQ; ++q) sorted0[q] = base[q];
@@ -260,9 +295,9 @@ extern "C" ssgd_status ssgd_runtime_mc(int32_t variant, int32_t P, int32_t Kmin,
                                        double* var, double* sum, double* sumsq, double* per_trial) {
     if (!dist || dist->kind == SSGD_TABLE || dist->kind < 0 || dist->kind > SSGD_PARETO) { mc_fail("invalid distribution"); return SSGD_EINVAL; }
     if ((dist->kind != SSGD_PARETO && !(dist->rate > 0)) || (dist->kind == SSGD_PARETO && (!(dist->alpha > 0) || !(dist->scale > 0)))) { mc_fail("invalid distribution parameters"); return SSGD_EINVAL; }
-    if (variant != SSGD_K_SYNC && variant != SSGD_K_BATCH_SYNC && variant != SSGD_K_ASYNC) { mc_fail("unsupported variant"); return SSGD_EINVAL; }
+    if (variant < SSGD_K_SYNC || variant > SSGD_K_BATCH_ASYNC) { mc_fail("unknown variant"); return SSGD_EINVAL; }
     if (P < 1 || P > kMaxWorkers || Kmin < 1 || Kmax < Kmin || chain_len < 1 || trials < 1 || trial0 < 0 || trial0 + trials > (1ll << 32)) { mc_fail("P, K range, chain_len or trials out of range"); return SSGD_EINVAL; }
-    if (variant != SSGD_K_BATCH_SYNC && Kmax > P) { mc_fail("K must not exceed P"); return SSGD_EINVAL; }
+    if (variant != SSGD_K_BATCH_SYNC && variant != SSGD_K_BATCH_ASYNC && Kmax > P) { mc_fail("K must not exceed P"); return SSGD_EINVAL; }
     if (Kmax > 65535) { mc_fail("K too large"); return SSGD_EINVAL; }
     const int nK = Kmax - Kmin + 1;
     const int64_t cells = (int64_t)nK * chain_len;
@@ -270,8 +305,9 @@ extern "C" ssgd_status ssgd_runtime_mc(int32_t variant, int32_t P, int32_t Kmin,
     int nslices = 1;
     while (nslices < nK && (int64_t)((nK + nslices - 1) / nslices) * chain_len * 16 > 5120) ++nslices;
     const int64_t cells_max = (int64_t)((nK + nslices - 1) / nslices) * chain_len;
-    const size_t lds = sizeof(double) * 2 * cells_max;
-    if (lds > 64 * 1024) { mc_fail("chain_len too large for one launch"); return SSGD_EINVAL; }
+    size_t lds = sizeof(double) * 2 * cells_max;
+    if (variant == SSGD_K_BATCH_ASYNC) lds += sizeof(double) * ((size_t)chain_len * Kmax + 1);   // the push sequence of a trial
+    if (lds > 64 * 1024) { mc_fail("chain_len (K-batch-async: chain_len * Kmax) too large for one launch"); return SSGD_EINVAL; }
     if (per_trial && trials * cells > (1ll << 27)) { mc_fail("per_trial output limited to 2^27 values"); return SSGD_EINVAL; }
     hipStream_t st = (hipStream_t)hip_stream;
     McArgs a{};

@@ -331,6 +331,8 @@ def test_config2_softmax_kbatch_sync_full_size(ssgd, oracle, torch_cuda, mixture
     ("k_async", 128, 128, ("pareto", 2.5, 1.0)), ("k_async", 5, 5, ("exp", 1.0)), ("k_async", 200, 200, ("pareto", 2.5, 1.0)),
     ("k_sync", 128, 128, ("pareto", 2.5, 1.0)), ("k_sync", 64, 64, ("exp", 2.0)),
     ("k_batch_sync", 6, 9, ("exp", 1.5)), ("k_batch_sync", 70, 20, ("shifted_exp", 0.2, 1.0)),
+    ("k_batch_async", 128, 128, ("pareto", 2.0, 1.0)), ("k_batch_async", 6, 9, ("exp", 1.5)),
+    ("k_batch_async", 200, 40, ("shifted_exp", 1.0, 1.0)),
 ])
 def test_mc_trials_bit_exact(ssgd, oracle, torch_cuda, variant, P, Kmax, spec):
     gd, od = dist_pair(ssgd, oracle, spec)
@@ -358,6 +360,18 @@ def test_mc_closed_forms_at_scale(ssgd, torch_cuda):
     s = ssgd.runtime_mc("k_async", P, 1, P, ssgd.delay_dist("shifted_exp", 0.2, 1.0), n, L, seed=2)
     assert np.all(np.abs(s["mean"][:, 0] - (0.2 + H)) <= 5 * np.sqrt(V / n))
     assert np.all(s["mean"][:, 1:] <= (0.2 + H)[:, None] + 5 * np.sqrt(s["var"][:, 1:] / n))
+
+
+def test_mc_kbatch_async_closed_form_at_scale(ssgd, torch_cuda):
+    """Lemma 5 / Theorem 2 at P=128: with Exp(mu) delays every inter-update time of K-batch-async is Erlang(K, P mu),
+    mean K/(P mu), variance K/(P mu)^2, for all K and every update of the chain; 2e5 trials."""
+    P, n, L, mu = 128, 200000, 8, 2.0
+    Ks = np.arange(1, P + 1)
+    r = ssgd.runtime_mc("k_batch_async", P, 1, P, ssgd.delay_dist("exp", mu), n, L, seed=4)
+    mean, var = Ks / (P * mu), Ks / (P * mu) ** 2
+    for l in range(L):
+        assert np.all(np.abs(r["mean"][:, l] - mean) <= 5 * np.sqrt(var / n))
+        assert np.all(np.abs(r["var"][:, l] / var - 1) < 0.05)
 
 
 # ---------------------------------------------------------------------------------------------

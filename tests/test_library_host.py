@@ -71,7 +71,8 @@ def test_runtime_mc_rejects_invalid_arguments(L):
     args = lambda **k: (k.get("variant", ssgd.K_ASYNC), k.get("P", 8), k.get("Kmin", 1), k.get("Kmax", 8), C.byref(d),
                         0, k.get("trials", 10), k.get("chain", 2), 0, None, None, None, None, None, None)
     for bad in (dict(P=0), dict(P=300), dict(Kmin=0), dict(Kmax=9), dict(trials=0), dict(chain=0),
-                dict(variant=ssgd.K_BATCH_ASYNC), dict(Kmax=128, P=128, chain=5000)):
+                dict(variant=7), dict(Kmax=128, P=128, chain=5000),
+                dict(variant=ssgd.K_BATCH_ASYNC, Kmax=128, P=128, chain=64)):
         assert L.ssgd_runtime_mc(*args(**bad)) == ssgd.EINVAL
 
 

@@ -204,6 +204,56 @@ def test_kbatch_sync_exp_is_erlang(oracle):
         assert np.all(np.abs(r["var"][:, l] / var - 1) < 0.12)
 
 
+def test_kbatch_async_exp_is_erlang_at_every_update(oracle):
+    """Lemma 5 with exponential delays: the pushes of P workers are P independent Poisson processes of rate mu,
+    merged a Poisson process of rate P mu, so every inter-update time of K-batch-async is Erlang(K, P mu):
+    mean K/(P mu), the form of Theorem 2, and variance K/(P mu)^2, from the first update on."""
+    P, mu, n, L = 6, 1.5, 20000, 4
+    Kmax = 9                                  # mini-batches, not workers: K may exceed P
+    r = oracle.runtime_mc("k_batch_async", P, 1, Kmax, oracle.Dist("exp", mu), n, L, seed=31)
+    Ks = np.arange(1, Kmax + 1)
+    mean, var = Ks / (P * mu), Ks / (P * mu) ** 2
+    for l in range(L):
+        assert _sem_ok(r["mean"][:, l], var, mean, n)
+        assert np.all(np.abs(r["var"][:, l] / var - 1) < 0.12)
+
+
+@pytest.mark.parametrize("spec,ex,vx", [(("exp", 2.0), 0.5, 0.25), (("shifted_exp", 0.3, 1.0), 1.3, 1.0),
+                                        (("pareto", 2.5, 1.0), 2.5 / 1.5, 2.5 / (1.5 ** 2 * 0.5))])
+def test_kbatch_async_single_worker_sums_k_delays(oracle, spec, ex, vx):
+    """P = 1: the only worker pushes back to back, so T_l is the sum of K consecutive i.i.d. delays for every l
+    and every distribution: mean K E[X] (Lemma 5 with P = 1, exact at every update), variance K Var[X]."""
+    n, L, Kmax = 40000, 3, 4
+    r = oracle.runtime_mc("k_batch_async", 1, 1, Kmax, oracle.Dist(*spec), n, L, seed=32)
+    Ks = np.arange(1, Kmax + 1)
+    for l in range(L):
+        assert _sem_ok(r["mean"][:, l], Ks * vx, Ks * ex, n)
+
+
+def test_kbatch_async_updates_of_k_tile_the_push_sequence(oracle):
+    """One push sequence serves every K: the first two updates of K together are the first update of 2K, trial by
+    trial, and T grows with K."""
+    d = oracle.Dist("pareto", 2.5, 1.0)
+    pt = oracle.runtime_mc("k_batch_async", 5, 1, 8, d, 60, 4, seed=33, per_trial=True)["per_trial"]
+    for K in (1, 2, 3, 4):
+        assert np.allclose(pt[:, K - 1, 0] + pt[:, K - 1, 1], pt[:, 2 * K - 1, 0], rtol=1e-13, atol=0)
+        assert np.allclose(pt[:, K - 1, :4].sum(axis=1), pt[:, 2 * K - 1, :2].sum(axis=1), rtol=1e-13, atol=0)
+    assert np.all(np.diff(pt[:, :, 0], axis=1) >= 0)
+    # the first push is the earliest of the P fresh delays, which is also T_1 of K-sync with K = 1
+    ks = oracle.runtime_mc("k_sync", 5, 1, 1, d, 60, 1, seed=33, per_trial=True)["per_trial"]
+    assert np.array_equal(pt[:, 0, 0], ks[:, 0, 0])
+
+
+@pytest.mark.parametrize("spec,ex", [(("shifted_exp", 1.0, 1.0), 2.0), (("pareto", 2.0, 1.0), 2.0)])
+def test_kbatch_async_long_run_mean_is_k_ex_over_p(oracle, spec, ex):
+    """Lemma 5 for the two distributions of Fig. 6: in the limit of many iterations E[T] = K E[X] / P.  The mean
+    over updates 9..40 of a chain (past the synchronised start) is within 3 % of it."""
+    P, K, L, n = 8, 4, 40, 3000
+    r = oracle.runtime_mc("k_batch_async", P, K, K, oracle.Dist(*spec), n, L, seed=34)
+    late = r["mean"][0, 8:].mean()
+    assert abs(late / (K * ex / P) - 1) < 0.03, late
+
+
 def test_new_longer_than_used_bounds_shifted_exp(oracle):
     """Lemma 3: K-async E[T] <= E[X_{K:P}]; Lemma 2: K-batch-sync E[T] <= K E[X_{1:P}];
     Lemma 4: with P = nK, E[T_1 + ... + T_n] <= Delta + sum_{i<n} E[X~_{K:(P-iK)}]."""
