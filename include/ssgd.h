@@ -148,6 +148,11 @@ ssgd_status ssgd_set_params(ssgd_ctx *ctx, int32_t replica, const float *w_in);
 /* Force K for the following updates (1 <= K <= Kmax); AdaSync keeps running. */
 ssgd_status ssgd_force_K(ssgd_ctx *ctx, int32_t K);
 
+/* The objective F(w) = (1/N) sum_n f(w, xi_n) of Eq. (1) over the whole data set at the replica's
+ * current parameters (what the paper's error-versus-time curves plot), one streaming pass over
+ * X.  loss_out: HOST.  Linear models with d % 4 == 0; else SSGD_EINVAL. */
+ssgd_status ssgd_full_loss(ssgd_ctx *ctx, int32_t replica, double *loss_out);
+
 /* The mini-batch each worker of a K-async run has in flight (Sec. 2.2: a worker that is not
  * among the K selected keeps computing on the parameters it read): version read tau_i, ordinal,
  * absolute finish time f_i.  HOST arrays of P entries, each nullable.  SSGD_EINVAL for the

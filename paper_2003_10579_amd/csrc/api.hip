@@ -528,6 +528,30 @@ ssgd_status ssgd_force_K(ssgd_ctx* c, int32_t K) {
     return SSGD_OK;
 }
 
+ssgd_status ssgd_full_loss(ssgd_ctx* c, int32_t replica, double* loss_out) {
+    if (!c || !loss_out) return fail(c, SSGD_EINVAL, "null argument");
+    if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
+    if (c->broken) return fail(c, SSGD_ESTATE, "context is unusable after a device error");
+    const int C = c->model.kind == SSGD_LSQ ? 1 : c->model.classes;
+    if (c->model.kind == SSGD_MLP2 || !full_loss_supports(c->model.kind, c->model.d, C))
+        return fail(c, SSGD_EINVAL, "the full objective is built for the linear models with d % 4 == 0");
+    HIP_OK(c, hipSetDevice(c->device));
+    const int blocks = std::max(1, c->cu_count);
+    DevBuf partial;
+    HIP_OK(c, partial.alloc(sizeof(double) * blocks));
+    hipError_t e = launch_full_loss(c->model.kind, c->model.X, c->model.y, c->model.N, c->model.d, C,
+                                    c->params.as<float>() + (int64_t)replica * c->nw, partial.as<double>(), blocks, c->stream);
+    std::vector<double> h(blocks);
+    if (e == hipSuccess) e = hipMemcpyAsync(h.data(), partial.p, sizeof(double) * blocks, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    partial.release();
+    if (e != hipSuccess) return fail(c, SSGD_EDEVICE, std::string("full objective: ") + hipGetErrorString(e));
+    double s = 0.0;
+    for (double v : h) s += v;
+    *loss_out = s / (double)c->model.N;
+    return SSGD_OK;
+}
+
 ssgd_status ssgd_get_workers(ssgd_ctx* c, int32_t replica, int32_t* tau, int32_t* ord, double* finish) {
     if (!c) return fail(nullptr, SSGD_EINVAL, "null context");
     if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");

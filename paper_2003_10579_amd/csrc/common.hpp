@@ -115,4 +115,10 @@ size_t linear_tile_lds_bytes(int C, int S);
 int linear_tile_resident_groups(size_t lds_bytes);
 hipError_t launch_linear_tile(const LinArgs& a, hipStream_t s);
 
+// Objective over the whole data set for one parameter vector of a linear model (full_loss.hip): partial sums of the
+// per-sample losses, one fp64 per workgroup.
+bool full_loss_supports(int kind, int d, int C);
+hipError_t launch_full_loss(int kind, const float* X, const void* y, int64_t N, int d, int C, const float* w, double* partial,
+                            int blocks, hipStream_t s);
+
 }  // namespace ssgd

@@ -4,6 +4,8 @@ Bars: delays, sample ids, selections, staleness, ordinals and clock values bit-e
 averaged gradients within 1e-5 relative (2-norm) in fp32; parameters after J updates within 1e-3
 relative.
 """
+import math
+
 import numpy as np
 import pytest
 
@@ -700,3 +702,32 @@ def test_kbatch_async_unsupported_shapes_are_refused(ssgd, torch_cuda):
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
     with pytest.raises(ssgd.SsgdError):
         ssgd.Context("lsq", Xd, yd, 4, 2, 8, "k_batch_async", ssgd.delay_dist("exp", 1.0), 0.01)
+
+
+# ------------------------------------------------------------------------------- objective over the whole data set
+
+@pytest.mark.parametrize("kind,N,d,classes", [
+    ("softmax", 1500, 320, 10), ("softmax", 1001, 132, 3), ("softmax", 37, 64, 16), ("lsq", 4096, 64, 1),
+    ("lsq", 777, 100, 1), ("softmax", 2000, 3072, 10),
+])
+def test_full_objective_against_the_oracle(ssgd, oracle, torch_cuda, kind, N, d, classes):
+    """F(w) of Eq. (1) after some training, and at w = 0 where the softmax objective is ln(classes) for any data."""
+    torch = torch_cuda
+    if kind == "lsq":
+        X, y, _ = synth.lsq_data(N, d, 41)
+    else:
+        X, y = synth.mixture_data(N, d, classes, seed=41)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    ctx = ssgd.Context(kind, Xd, yd, 4, 2, 8, "k_sync", ssgd.delay_dist("exp", 1.0), 0.05 if kind == "softmax" else 0.01,
+                       seed=42, classes=classes, replicas=2)
+    M = oracle.Model(kind, X, y, classes=classes)
+    f0 = ctx.full_loss(0)
+    assert abs(f0 - M.full_loss(np.zeros(ctx.nw, dtype=np.float32))) <= 1e-6 * max(1.0, abs(f0))
+    if kind == "softmax":
+        assert abs(f0 - math.log(classes)) < 1e-6
+    ctx.run(30)
+    for r in (0, 1):
+        g, o = ctx.full_loss(r), M.full_loss(ctx.params(r))
+        assert abs(g - o) <= 2e-6 * max(1.0, abs(o)), (r, g, o)
+    assert ctx.full_loss(0) != ctx.full_loss(1)
+    ctx.close()
