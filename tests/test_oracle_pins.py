@@ -612,6 +612,28 @@ def test_lsq_converges_to_normal_equation_optimum(oracle):
     assert abs(M.full_loss(tr.params()) - F(tr.params().astype(np.float64))) < 1e-12
 
 
+def test_softmax_objective_special_cases(oracle):
+    """Eq. (1) for softmax regression: ln(classes) at w = 0 whatever the data; unchanged when the same constant is
+    added to every class bias; and, with all weights zero and only the biases set, the cross-entropy between the
+    label frequencies and softmax(b), whatever the samples are."""
+    C_, d, N = 5, 7, 300
+    X, y = synth.mixture_data(N, d, C_, seed=9)
+    M = oracle.Model("softmax", X, y, classes=C_)
+    nw = C_ * d + C_
+    assert abs(M.full_loss(np.zeros(nw, dtype=np.float32)) - math.log(C_)) < 1e-12
+    rng = np.random.default_rng(3)
+    w = (0.3 * rng.standard_normal(nw)).astype(np.float32)
+    shifted = w.copy()
+    shifted[C_ * d:] += np.float32(0.75)
+    assert abs(M.full_loss(w) - M.full_loss(shifted)) < 1e-6
+    b = rng.standard_normal(C_).astype(np.float32)
+    only_bias = np.zeros(nw, dtype=np.float32)
+    only_bias[C_ * d:] = b
+    freq = np.bincount(y, minlength=C_) / N
+    logp = b.astype(np.float64) - np.log(np.sum(np.exp(b.astype(np.float64))))
+    assert abs(M.full_loss(only_bias) + float(freq @ logp)) < 1e-12
+
+
 # --------------------------------------------------------------------------- AdaSync
 
 def test_adasync_plateau_rule(oracle):
