@@ -146,6 +146,62 @@ __global__ __launch_bounds__(64) void schedule_kernel(SchedArgs a) {
         }
         key[0] = mine; tau[0] = mytau;
     }
+    if (!TABLE && a.variant == kAsync && K >= 8 && 18 * K >= P * NQ && (NQ > 1 || P > 16) && !(a.interval_t > 0.0)) {
+        // K-async with many contributors per update: K rounds of a wave-wide argmin (0.4 us each) cost more than
+        // ranking every worker's finish time against all P of them (one pass over the workers, whatever K is: 22 us
+        // at P = 256), which also gives the K earliest in consume-list order.
+        for (; done < a.count; ++done) {
+            const int64_t j = a.j0 + done;
+            double nd[NQ];
+            int rank[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const int w = lane + 64 * q;
+                nd[q] = (w < P) ? (double)draw_delay(w, 0, (uint32_t)j + 1u) : 0.0;
+                rank[q] = 0;
+            }
+#pragma unroll
+            for (int qo = 0; qo < NQ; ++qo) {
+                const long long bits = __double_as_longlong(key[qo]);
+                const int lim = min(64, P - 64 * qo);                  // workers held in register qo
+                for (int l = 0; l < lim; ++l) {
+                    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, l);
+                    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((unsigned long long)bits >> 32), l);
+                    const double other = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+                    const int wo = l + 64 * qo;
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q) rank[q] += before(other, wo, key[q], lane + 64 * q) ? 1 : 0;
+                }
+            }
+            // the K-th earliest finish time is the time of the update
+            double t_new = 0.0;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const unsigned long long m = __ballot(lane + 64 * q < P && rank[q] == K - 1);
+                if (m != 0ull) {
+                    const int l = __builtin_ctzll(m);
+                    const long long bits = __double_as_longlong(key[q]);
+                    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, l);
+                    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((unsigned long long)bits >> 32), l);
+                    t_new = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const int w = lane + 64 * q;
+                if (w < P && rank[q] < K) {
+                    tr_sel[j * Kcap + rank[q]] = w; tr_tau[j * Kcap + rank[q]] = tau[q]; tr_ord[j * Kcap + rank[q]] = 0;
+                    tau[q] = (int32_t)(j + 1);
+                    key[q] = t_new + nd[q];
+                }
+            }
+            for (int l = K + lane; l < Kcap; l += 64) {
+                tr_sel[j * Kcap + l] = -1; tr_tau[j * Kcap + l] = -1; tr_ord[j * Kcap + l] = -1;
+            }
+            if (lane == 0) { tr_t[j] = t_new; tr_K[j] = K; }
+            clock = t_new;
+        }
+    }
     for (; done < a.count; ++done) {
         const int64_t j = a.j0 + done;
         const uint32_t ver = (uint32_t)j;

@@ -80,6 +80,8 @@ def _tiny(torch, N=64, d=8, seed=0):
     ("k_sync", 4, 2, ("exp", 1.0)), ("k_sync", 100, 37, ("pareto", 2.5, 1.0)), ("k_sync", 256, 256, ("exp", 1.0)),
     ("k_async", 8, 2, ("shifted_exp", 0.5, 1.0)), ("k_async", 1, 1, ("exp", 1.0)), ("k_async", 65, 9, ("pareto", 2.5, 1.0)),
     ("k_async", 256, 8, ("shifted_exp", 0.5, 1.0)), ("k_async", 256, 255, ("exp", 3.0)),
+    ("k_async", 16, 5, ("exp", 1.0)), ("k_async", 64, 16, ("pareto", 2.5, 1.0)), ("k_async", 200, 40, ("shifted_exp", 0.2, 1.0)),
+    ("k_async", 17, 16, ("exp", 1.0)),
     ("k_batch_sync", 64, 16, ("pareto", 2.5, 1.0)), ("k_batch_sync", 3, 7, ("exp", 1.0)), ("k_batch_sync", 130, 1, ("exp", 1.0)),
 ])
 def test_schedule_bit_exact(ssgd, oracle, torch_cuda, variant, P, K, spec):
