@@ -62,7 +62,7 @@ def mc_rate(ssgd):
     """Monte-Carlo runtime estimator (config 3 shape: P=128, every K, K-async chains of 8 updates, Exp(1))."""
     dist = ssgd.delay_dist("exp", 1.0)
     ssgd.runtime_mc("k_async", 128, 1, 128, dist, 2000, 8, seed=1)
-    trials = 100000
+    trials = 1000000
     t0 = time.perf_counter()
     ssgd.runtime_mc("k_async", 128, 1, 128, dist, trials, 8, seed=1)
     return trials / (time.perf_counter() - t0)
