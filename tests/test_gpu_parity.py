@@ -733,3 +733,31 @@ def test_full_objective_against_the_oracle(ssgd, oracle, torch_cuda, kind, N, d,
         assert abs(g - o) <= 2e-6 * max(1.0, abs(o)), (r, g, o)
     assert ctx.full_loss(0) != ctx.full_loss(1)
     ctx.close()
+
+
+def test_error_runtime_frontier_orders_the_variants(ssgd, torch_cuda):
+    """The four variants at the same K on the same problem (Sec. 3, Table 1): per update K-batch-async is the
+    fastest and K-sync the slowest; the synchronous variants only use fresh gradients, the asynchronous ones do not;
+    and every run ends above the optimum of the least-squares objective."""
+    from paper_2003_10579_amd import frontier
+    torch = torch_cuda
+    X, y, _ = synth.lsq_data(2048, 132, 3)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    X64, y64 = X.astype(np.float64), y.astype(np.float64)
+    w_opt = np.linalg.solve(X64.T @ X64, X64.T @ y64)
+    f_star = 0.5 * float(np.mean((X64 @ w_opt - y64) ** 2))
+    recs = frontier.frontier(ssgd, Xd, yd, f_star, 8, [2, 4], 8, 0.01, 300, 6, ("shifted_exp", 1.0, 1.0), seed=1)
+    by = {(r["variant"], r["K"]): r for r in recs}
+    for K in (2, 4):
+        ts = [by[(v, K)]["time_per_update"] for v in ("k_batch_async", "k_async", "k_sync")]
+        assert ts[0] < ts[1] < ts[2], ts
+        assert by[("k_batch_sync", K)]["time_per_update"] <= by[("k_sync", K)]["time_per_update"]      # Lemma 2
+        for v in ("k_sync", "k_batch_sync"):
+            assert by[(v, K)]["p0"] == 1.0 and by[(v, K)]["mean_staleness"] == 0.0
+        for v in ("k_async", "k_batch_async"):
+            assert 0.0 < by[(v, K)]["p0"] < 1.0 and by[(v, K)]["mean_staleness"] > 0.0
+    assert all(r["mean_gap"] > 0 for r in recs)
+    # more contributors per update: each update takes longer (Lemma 1, Lemma 3) ...
+    assert by[("k_sync", 4)]["time_per_update"] > by[("k_sync", 2)]["time_per_update"]
+    # ... and for the asynchronous variants the gradients used are less stale
+    assert by[("k_async", 4)]["mean_staleness"] < by[("k_async", 2)]["mean_staleness"]
