@@ -66,6 +66,8 @@ struct MlpArgs {
     float* loss;               // [S]          sum of the sample losses
     int32_t* ylab;             // [S][MP]      labels (-1: no sample)
     float* agg_out;            // nullable
+    float* dw_part;            // [nsplit][H][d] partial first-layer gradient sums when the slots are split over workgroups
+    int32_t nsplit;
 };
 
 // worker and mini-batch ordinal of record r of the compute list of version v, and its slot
@@ -126,7 +128,9 @@ __global__ __launch_bounds__(256) void mlp_gather_kernel(MlpArgs a) {
 // BWD: rows = hidden units, columns = input features, depth = 64 samples of every consumed slot.
 // BT x BT output tile per workgroup (128: four waves of 64 x 64; 64: four waves of 32 x 32, for launches
 // that would otherwise leave most CUs idle).
-template <bool FWD, int BT>
+// SPLIT (gradient contraction only): blockIdx.z takes a share of the consumed slots and leaves its partial sum in
+// dw_part; mlp_w1_update_kernel adds the shares in order and applies the update.
+template <bool FWD, int BT, bool SPLIT = false>
 __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     constexpr int WT = BT / 2;          // rows and columns per wave
     constexpr int NF = WT / 32;         // 32 x 32 MFMA tiles per wave and dimension
@@ -137,7 +141,12 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bm = blockIdx.x, bn = blockIdx.y;
     const int d = a.d, H = a.H;
-    const int stages = FWD ? d / KT : a.Kv;
+    int stage0 = 0, stages = FWD ? d / KT : a.Kv;
+    if constexpr (SPLIT) {
+        const int per = (a.Kv + a.nsplit - 1) / a.nsplit;
+        stage0 = blockIdx.z * per;
+        stages = max(0, min(per, a.Kv - stage0));
+    }
 
     // global -> LDS: BT rows x 8 chunks of 16 bytes per operand; thread -> chunk tid % 8 of rows tid / 8 + 32 i
     const int lchunk = tid & 7, lrow = tid >> 3;
@@ -187,12 +196,14 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    fetch(0);
-    stash(0);
+    if (stages > 0) {
+        fetch(stage0);
+        stash(0);
+    }
     __syncthreads();
     for (int st = 0; st < stages; ++st) {
         const int buf = st & 1;
-        if (st + 1 < stages) fetch(st + 1);
+        if (st + 1 < stages) fetch(stage0 + st + 1);
 #pragma unroll
         for (int kk = 0; kk < KT / 16; ++kk) {
             bf16x8 fa[NF], fb[NF];
@@ -243,6 +254,9 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
                 for (int c = 0; c < 4; ++c) { const float z = v[c] + b1[c]; h[c] = z > 0.0f ? z : 0.0f; }
                 *reinterpret_cast<f32x4*>(a.hbuf + ((int64_t)slot_of[row / MP] * MP + (row % MP)) * H + n) = h;
             }
+        } else if constexpr (SPLIT) {
+            const int64_t p = (int64_t)(bm * BT + row) * d + bn * BT + 4 * c4;
+            *reinterpret_cast<f32x4*>(a.dw_part + (int64_t)blockIdx.z * H * d + p) = v;
         } else {
             const int64_t p = (int64_t)(bm * BT + row) * d + bn * BT + 4 * c4;
             f32x4 w = *reinterpret_cast<const f32x4*>(a.params + p);
@@ -253,6 +267,24 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
             *reinterpret_cast<uint2*>(a.w1r + p) = make_uint2((uint32_t)wb[0] | ((uint32_t)wb[1] << 16), (uint32_t)wb[2] | ((uint32_t)wb[3] << 16));
             if (a.agg_out) *reinterpret_cast<f32x4*>(a.agg_out + p) = v * invK;
         }
+    }
+}
+
+// ---- first-layer update from the partial sums of a split gradient contraction: shares added in order --------
+__global__ __launch_bounds__(256) void mlp_w1_update_kernel(MlpArgs a) {
+    const int64_t n4 = (int64_t)a.H * a.d / 4;
+    const float scale = a.lr / (float)a.Kv, invK = 1.0f / (float)a.Kv;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < n4; q += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t p = 4 * q;
+        f32x4 v = *reinterpret_cast<const f32x4*>(a.dw_part + p);
+        for (int sp = 1; sp < a.nsplit; ++sp) v += *reinterpret_cast<const f32x4*>(a.dw_part + (int64_t)sp * a.H * a.d + p);
+        f32x4 w = *reinterpret_cast<const f32x4*>(a.params + p);
+        unsigned short wb[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { w[c] -= scale * v[c]; wb[c] = bf16_bits(w[c]); }
+        *reinterpret_cast<f32x4*>(a.params + p) = w;
+        *reinterpret_cast<uint2*>(a.w1r + p) = make_uint2((uint32_t)wb[0] | ((uint32_t)wb[1] << 16), (uint32_t)wb[2] | ((uint32_t)wb[3] << 16));
+        if (a.agg_out) *reinterpret_cast<f32x4*>(a.agg_out + p) = v * invK;
     }
 }
 
@@ -434,6 +466,7 @@ __global__ void mlp_init_kernel(float* params, uint64_t seed, int64_t nw, int64_
 
 // operand double buffer; the epilogue's fp32 tile [BT][BT + 4] fits inside it
 size_t contract_lds(int bt) { return (size_t)4 * bt * LDT * 2; }
+constexpr int kMaxSplit = 8;     // shares of the consumed slots in the split gradient contraction
 
 struct DevMem {
     void* p = nullptr;
@@ -449,7 +482,7 @@ struct MlpState {
     int S = 0;
     int64_t nw = 0;
     int prevK = 0;          // size of the consume list of the last update run (records of the next K-async step)
-    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab;
+    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, dw_part;
     hipStream_t stream = nullptr;
 };
 
@@ -484,6 +517,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(s->d2.alloc(sizeof(float) * S * MP * 16));
     TRY(s->loss.alloc(sizeof(float) * S));
     TRY(s->ylab.alloc(sizeof(int32_t) * S * MP));
+    TRY(s->dw_part.alloc(sizeof(float) * kMaxSplit * (size_t)n1));
     TRY(hipMemsetAsync(s->xb.p, 0, 2 * S * MP * a.d, stream));
     TRY(hipMemsetAsync(s->xbt.p, 0, 2 * S * MP * a.d, stream));
     TRY(hipMemsetAsync(s->hbuf.p, 0, sizeof(float) * S * MP * a.H, stream));
@@ -497,12 +531,14 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     a.xb = (unsigned short*)s->xb.p; a.xbt = (unsigned short*)s->xbt.p; a.hbuf = (float*)s->hbuf.p;
     a.d1t = (unsigned short*)s->d1t.p; a.gb1 = (float*)s->gb1.p; a.gw2 = (float*)s->gw2.p; a.gb2 = (float*)s->gb2.p;
     a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p; a.d2 = (float*)s->d2.p;
+    a.dw_part = (float*)s->dw_part.p; a.nsplit = 1;
     const float bound1 = (float)(1.0 / sqrt((double)a.d)), bound2 = (float)(1.0 / sqrt((double)a.H));
     hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
     TRY(hipGetLastError());
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 128, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
 #undef TRY
     *out = s;
     return hipSuccess;
@@ -548,7 +584,15 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
         }
         // the gradient contraction always uses the small tiles: 384 workgroups instead of 96 matter more than the
         // reuse inside a larger tile
-        hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64), dim3(256), contract_lds(64), stream, a);
+        if (a.Kv >= 64) {
+            // many slots: 128 x 128 tiles (half the operand traffic of the small ones), the slots split into shares so
+            // that the chip is still full; the shares are added, in order, by the update kernel
+            a.nsplit = std::min(kMaxSplit, a.Kv / 16);
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3(a.H / 128, a.d / 128, a.nsplit), dim3(256), contract_lds(128), stream, a);
+            hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
+        } else {
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64), dim3(256), contract_lds(64), stream, a);
+        }
         hipLaunchKernelGGL(mlp_small_update_kernel, dim3(24), dim3(256), 0, stream, a);
         if (launches) *launches += 1;
     }
@@ -606,7 +650,8 @@ float* mlp_params(MlpState* s) { return s ? (float*)s->params.p : nullptr; }
 
 void mlp_destroy(MlpState* s) {
     if (!s) return;
-    DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss, &s->ylab};
+    DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss, &s->ylab,
+                      &s->dw_part};
     for (DevMem* b : bufs) b->release();
     delete s;
 }
