@@ -763,3 +763,12 @@ def test_error_runtime_frontier_orders_the_variants(ssgd, torch_cuda):
     assert by[("k_sync", 4)]["time_per_update"] > by[("k_sync", 2)]["time_per_update"]
     # ... and for the asynchronous variants the gradients used are less stale
     assert by[("k_async", 4)]["mean_staleness"] < by[("k_async", 2)]["mean_staleness"]
+
+
+def test_speedups_of_theorems_1_and_2(ssgd, torch_cuda):
+    """Theorem 1 (fully asynchronous against fully synchronous SGD: P (1 + 1/2 + ... + 1/P) for exponential delays) and
+    Theorem 2 (K-async against K-batch-async: P E[X_{K:P}] / (K E[X])) from the Monte-Carlo estimator, within 2 %."""
+    from paper_2003_10579_amd import speedup
+    for rec in speedup.speedups(ssgd, ("exp", 1.0), Ps=(4, 32, 128), trials=100000, seed=3):
+        assert abs(rec["sync_over_async"] / rec["theorem1_closed_form"] - 1) < 0.02, rec
+        assert abs(rec["k_async_over_k_batch_async"] / rec["theorem2_closed_form"] - 1) < 0.02, rec
