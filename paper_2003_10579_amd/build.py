@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssgd.so")
 SOURCES = ["api.hip", "schedule.hip", "linear.hip", "linear_tile.hip", "full_loss.hip", "mlp.hip", "mc.hip"]
 HEADERS = ["common.hpp", "rng.hpp", "mlp.hpp", os.path.join("..", "..", "include", "ssgd.h")]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # event-process arithmetic (clock sums, AdaSync rule) must round like plain IEEE operations
 NO_CONTRACT = {"schedule.hip": ["-ffp-contract=off"], "mc.hip": ["-ffp-contract=off"], "api.hip": ["-ffp-contract=off"]}

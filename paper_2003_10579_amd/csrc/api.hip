@@ -315,6 +315,8 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
 
 }  // namespace
 
+// the C ABI is all the library exports (everything else is built with hidden visibility)
+#pragma GCC visibility push(default)
 extern "C" {
 
 ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m, int32_t variant,
@@ -566,6 +568,7 @@ ssgd_status ssgd_get_workers(ssgd_ctx* c, int32_t replica, int32_t* tau, int32_t
     return SSGD_OK;
 }
 
+extern "C++" {
 namespace {
 
 // Snapshot layout: header, then the trace of the updates done (replica by replica), then every device buffer that
@@ -604,6 +607,7 @@ StateHeader make_header(ssgd_ctx* c) {
 }
 
 }  // namespace
+}  // extern "C++"
 
 ssgd_status ssgd_state_bytes(ssgd_ctx* c, int64_t* bytes) {
     if (!c || !bytes) return fail(c, SSGD_EINVAL, "null argument");
@@ -758,3 +762,4 @@ void ssgd_destroy(ssgd_ctx* c) {
 }
 
 }  // extern "C"
+#pragma GCC visibility pop

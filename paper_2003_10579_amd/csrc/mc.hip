@@ -289,7 +289,7 @@ namespace {
 void mc_fail(const std::string& m) { set_global_error(m); }
 }  // namespace
 
-extern "C" ssgd_status ssgd_runtime_mc(int32_t variant, int32_t P, int32_t Kmin, int32_t Kmax,
+extern "C" __attribute__((visibility("default"))) ssgd_status ssgd_runtime_mc(int32_t variant, int32_t P, int32_t Kmin, int32_t Kmax,
                                        const ssgd_delay_dist* dist, int64_t trial0, int64_t trials,
                                        int32_t chain_len, uint64_t seed, void* hip_stream, double* mean,
                                        double* var, double* sum, double* sumsq, double* per_trial) {

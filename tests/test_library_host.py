@@ -27,6 +27,17 @@ def test_exports_every_declared_symbol(L):
         assert getattr(L, name) is not None
 
 
+def test_exports_nothing_but_the_c_abi(L):
+    import shutil
+    import subprocess
+    if shutil.which("nm") is None:
+        pytest.skip("nm not available")
+    out = subprocess.run(["nm", "-D", "--defined-only", ssgd._LIB_PATH], capture_output=True, text=True, check=True).stdout
+    # functions defined by the library itself ("T"); weak instantiations of standard-library templates do not count
+    defined = {line.split()[-1] for line in out.splitlines() if len(line.split()) >= 3 and line.split()[-2] == "T"}
+    assert defined == set(ssgd.EXPORTS), defined ^ set(ssgd.EXPORTS)
+
+
 def _model(kind=ssgd.SOFTMAX, d=8, classes=3, X=0x1000, y=0x1000, N=10, hidden=0, bf16=0):
     m = ssgd.ModelDesc()
     m.kind, m.d, m.classes, m.hidden, m.bf16, m.X, m.y, m.N = kind, d, classes, hidden, bf16, X, y, N
