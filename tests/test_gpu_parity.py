@@ -772,3 +772,23 @@ def test_speedups_of_theorems_1_and_2(ssgd, torch_cuda):
     for rec in speedup.speedups(ssgd, ("exp", 1.0), Ps=(4, 32, 128), trials=100000, seed=3):
         assert abs(rec["sync_over_async"] / rec["theorem1_closed_form"] - 1) < 0.02, rec
         assert abs(rec["k_async_over_k_batch_async"] / rec["theorem2_closed_form"] - 1) < 0.02, rec
+
+
+def test_kbatch_async_with_plateau_doubling(ssgd, oracle, torch_cuda):
+    """AdaSync by plateau doubling on top of K-batch-async: K grows from 1 to 8 during the run (record lists of every
+    size, windows closing mid-segment); trace, K sequence and parameters against the oracle."""
+    torch = torch_cuda
+    X, y = synth.mixture_data(800, 260, 4, seed=51)
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.2, 1.0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    ada = dict(mode=1, K0=1, Kmax=8, window=20, rel_tol=0.5)
+    ctx = ssgd.Context("softmax", Xd, yd, 10, 1, 12, "k_batch_async", gd, 0.05, seed=52, classes=4, adasync=ada)
+    tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=4), 10, 1, 12, "k_batch_async", od, 0.05, seed=52, adasync=ada)
+    ctx.run(170)
+    tr.run(170)
+    g, o = ctx.trace(), tr.trace()
+    assert o["K"][-1] == 8 and o["K"][0] == 1
+    assert_trace_equal(g, o)
+    assert np.allclose(g["loss"], o["loss"], rtol=2e-4, atol=1e-6)
+    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
+    ctx.close()
