@@ -105,7 +105,9 @@ typedef struct {
  * is enqueued there.  `adasync` may be NULL (mode 0).
  * Limits: 1 <= K <= P <= 256 for K-sync / K-async, 1 <= K <= 256 for the batch
  * variants, m >= 1, d >= 1, classes <= 16 for SOFTMAX; MLP2 needs replicas == 1,
- * d % 32 == 0, hidden % 64 == 0.  Invalid arguments give SSGD_EINVAL and leave *out untouched. */
+ * bf16 = 1, m <= 64, d % 128 == 0, hidden % 128 == 0 and runs K-sync, K-batch-sync and K-async;
+ * SSGD_K_BATCH_ASYNC has the limits given with the enumeration.  Invalid arguments give
+ * SSGD_EINVAL and leave *out untouched. */
 ssgd_status ssgd_create(const ssgd_model *model, int32_t P, int32_t K, int32_t m, int32_t variant,
                         const ssgd_delay_dist *dist, double lr, uint64_t seed, int32_t replicas,
                         const ssgd_adasync *adasync, void *hip_stream, ssgd_ctx **out);

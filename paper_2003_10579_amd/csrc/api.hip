@@ -357,7 +357,7 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
     } else if (model->kind == SSGD_MLP2) {
         if (model->classes < 2 || model->classes > kClassPad || model->hidden < 64 || model->hidden % 64 || model->d % 32 || replicas != 1)
             return fail(nullptr, SSGD_EINVAL, "MLP needs 2..16 classes, hidden % 64 == 0, d % 32 == 0, replicas == 1");
-        if (variant != SSGD_K_ASYNC && variant != SSGD_K_SYNC) return fail(nullptr, SSGD_EINVAL, "MLP supports K-sync and K-async");
+        if (variant == SSGD_K_BATCH_ASYNC) return fail(nullptr, SSGD_EINVAL, "MLP supports K-sync, K-batch-sync and K-async");
     } else {
         return fail(nullptr, SSGD_EINVAL, "unknown model kind");
     }

@@ -571,7 +571,7 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
         a.v = v0 + q;
         a.Kv = Ks[(size_t)q];
         a.nrec = (a.variant == kAsync) ? (a.v == 0 ? a.P : (q == 0 ? prevK : Ks[(size_t)q - 1])) : a.Kv;
-        if (a.Kv < 1 || a.Kv > a.Kcap || a.nrec < 0 || a.nrec > a.P) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return fail(hipErrorInvalidValue, "inconsistent K in the trace"); }
+        if (a.Kv < 1 || a.Kv > a.Kcap || a.nrec < 0 || a.nrec > s->S) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return fail(hipErrorInvalidValue, "inconsistent K in the trace"); }
         if (a.nrec > 0) {
             hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
             // small tiles while the large ones would not fill the chip

@@ -409,6 +409,7 @@ def test_mlp_initial_parameters_bit_exact(ssgd, oracle, torch_cuda):
     ("k_sync", 4, 2, 64, 256, 10, 128),
     ("k_sync", 6, 3, 20, 128, 3, 256),        # m < 64: zero rows in every block
     ("k_async", 6, 2, 32, 384, 10, 128),
+    ("k_batch_sync", 3, 5, 16, 128, 4, 128),  # a worker contributes more than once (K > P)
     ("k_sync", 80, 64, 4, 128, 5, 128),       # 64 slots per update: the gradient contraction is split into four shares
     ("k_async", 100, 90, 3, 256, 4, 128),     # five shares of 18 slots; ranked selection in the schedule
 ])
@@ -421,7 +422,7 @@ def test_mlp_gradients_teacher_forced(ssgd, oracle, torch_cuda, variant, P, K, m
     agg = torch.zeros(ctx.nw, dtype=torch.float32, device="cuda")
     worst = 0.0
     for j in range(25 if K < 64 else 8):
-        if variant == "k_sync":
+        if variant != "k_async":
             ctx.set_params(tr.params())
         ctx.step(agg)
         worst = max(worst, rel(agg.cpu().numpy(), tr.step()))
