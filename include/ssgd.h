@@ -152,7 +152,10 @@ ssgd_status ssgd_force_K(ssgd_ctx *ctx, int32_t K);
 
 /* The objective F(w) = (1/N) sum_n f(w, xi_n) of Eq. (1) over the whole data set at the replica's
  * current parameters (what the paper's error-versus-time curves plot), one streaming pass over
- * X.  loss_out: HOST.  Linear models with d % 4 == 0; else SSGD_EINVAL. */
+ * X.  loss_out: HOST.  Linear models need d % 4 == 0 (else SSGD_EINVAL) and evaluate in fp32
+ * with fp64 sums.  The two-layer network evaluates with the forward pass of its trainer (inputs,
+ * W1 and W2 at their bf16 values, fp32 accumulation), through temporary device buffers that the
+ * call allocates and frees (SSGD_ENOMEM if they do not fit); mini-batches in flight are untouched. */
 ssgd_status ssgd_full_loss(ssgd_ctx *ctx, int32_t replica, double *loss_out);
 
 /* The mini-batch each worker of a K-async run has in flight (Sec. 2.2: a worker that is not

@@ -535,8 +535,16 @@ ssgd_status ssgd_full_loss(ssgd_ctx* c, int32_t replica, double* loss_out) {
     if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
     if (c->broken) return fail(c, SSGD_ESTATE, "context is unusable after a device error");
     const int C = c->model.kind == SSGD_LSQ ? 1 : c->model.classes;
-    if (c->model.kind == SSGD_MLP2 || !full_loss_supports(c->model.kind, c->model.d, C))
-        return fail(c, SSGD_EINVAL, "the full objective is built for the linear models with d % 4 == 0");
+    if (c->model.kind == SSGD_MLP2) {
+        HIP_OK(c, hipSetDevice(c->device));
+        std::string msg;
+        hipError_t em = mlp_full_loss(c->mlp, loss_out, c->stream, &msg);
+        if (em == hipErrorOutOfMemory) return fail(c, SSGD_ENOMEM, "full objective: " + msg);
+        if (em != hipSuccess) return fail(c, SSGD_EDEVICE, "full objective: " + msg);
+        return SSGD_OK;
+    }
+    if (!full_loss_supports(c->model.kind, c->model.d, C))
+        return fail(c, SSGD_EINVAL, "the full objective of the linear models needs d % 4 == 0");
     HIP_OK(c, hipSetDevice(c->device));
     const int blocks = std::max(1, c->cu_count);
     DevBuf partial;

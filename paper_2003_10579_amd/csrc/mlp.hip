@@ -68,11 +68,14 @@ struct MlpArgs {
     float* agg_out;            // nullable
     float* dw_part;            // [nsplit][H][d] partial first-layer gradient sums when the slots are split over workgroups
     int32_t nsplit;
+    int64_t eval_base;         // >= 0: objective evaluation; record r holds data rows eval_base + 64 r .. + 63 in slot r
 };
 
 // worker and mini-batch ordinal of record r of the compute list of version v, and its slot
 __device__ __forceinline__ void record_of(const MlpArgs& a, int r, int& worker, int& ordinal, int& slot) {
-    if (a.variant == kAsync) {
+    if (a.eval_base >= 0) {
+        worker = 0; ordinal = 0; slot = r;
+    } else if (a.variant == kAsync) {
         worker = (a.v == 0) ? r : a.tr.sel[(a.v - 1) * a.tr.Kcap + r];
         ordinal = 0;
         slot = worker;
@@ -95,7 +98,12 @@ __global__ __launch_bounds__(256) void mlp_gather_kernel(MlpArgs a) {
     record_of(a, r, worker, ordinal, slot);
     if (tid < MP) {
         uint32_t id = 0xFFFFFFFFu;
-        if (tid < a.m) id = batch_index(a.seed, 0u, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)tid, a.N);
+        if (a.eval_base >= 0) {
+            const int64_t row = a.eval_base + (int64_t)r * MP + tid;
+            if (row < (int64_t)a.N) id = (uint32_t)row;
+        } else if (tid < a.m) {
+            id = batch_index(a.seed, 0u, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)tid, a.N);
+        }
         ids[tid] = id;
         if (cb == 0) a.ylab[slot * MP + tid] = (id == 0xFFFFFFFFu) ? -1 : a.y[id];
     }
@@ -113,6 +121,7 @@ __global__ __launch_bounds__(256) void mlp_gather_kernel(MlpArgs a) {
         for (int q = 0; q < 4; ++q) tr_tile[4 * c4 + q][s] = b[q];
     }
     __syncthreads();
+    if (a.xbt == nullptr) return;       // objective evaluation: no gradient contraction follows
     // transposed copy: column c of the block, 64 samples = 128 bytes; 8 threads per column, 16 bytes each
     for (int q = tid; q < 128 * 8; q += 256) {
         const int c = q >> 3, part = q & 7;
@@ -531,7 +540,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     a.xb = (unsigned short*)s->xb.p; a.xbt = (unsigned short*)s->xbt.p; a.hbuf = (float*)s->hbuf.p;
     a.d1t = (unsigned short*)s->d1t.p; a.gb1 = (float*)s->gb1.p; a.gw2 = (float*)s->gw2.p; a.gb2 = (float*)s->gb2.p;
     a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p; a.d2 = (float*)s->d2.p;
-    a.dw_part = (float*)s->dw_part.p; a.nsplit = 1;
+    a.dw_part = (float*)s->dw_part.p; a.nsplit = 1; a.eval_base = -1;
     const float bound1 = (float)(1.0 / sqrt((double)a.d)), bound2 = (float)(1.0 / sqrt((double)a.H));
     hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
     TRY(hipGetLastError());
@@ -607,6 +616,53 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
     (void)ws;
     return hipSuccess;
 }
+
+// Objective over the whole data set with the forward pass of the trainer (bf16 operands in the first contraction,
+// W2 at its bf16 values, fp32 accumulation): the data set goes through the gather, forward and output kernels in
+// blocks of 64 rows per slot, into buffers of its own so that the mini-batches in flight are untouched; the
+// per-slot sums are added on the host in fp64, in row order.
+hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::string* msg) {
+    auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
+    MlpArgs a = s->a;
+    const int64_t N = (int64_t)a.N, nslot = (N + MP - 1) / MP;
+    const int E = (int)std::min<int64_t>(nslot, 256);
+    DevMem xb, hbuf, d2, loss, ylab;
+    auto release = [&]() { xb.release(); hbuf.release(); d2.release(); loss.release(); ylab.release(); };
+    hipError_t e = hipSuccess;
+    if (e == hipSuccess) e = xb.alloc(2 * (size_t)E * MP * a.d);
+    if (e == hipSuccess) e = hbuf.alloc(sizeof(float) * (size_t)E * MP * a.H);
+    if (e == hipSuccess) e = d2.alloc(sizeof(float) * (size_t)E * MP * 16);
+    if (e == hipSuccess) e = loss.alloc(sizeof(float) * (size_t)E);
+    if (e == hipSuccess) e = ylab.alloc(sizeof(int32_t) * (size_t)E * MP);
+    if (e != hipSuccess) { release(); return fail(e, "allocating the evaluation buffers"); }
+    a.xb = (unsigned short*)xb.p; a.xbt = nullptr; a.hbuf = (float*)hbuf.p; a.d2 = (float*)d2.p;
+    a.loss = (float*)loss.p; a.ylab = (int32_t*)ylab.p;
+    a.d1t = nullptr; a.gb1 = nullptr; a.gw2 = nullptr; a.gb2 = nullptr; a.agg_out = nullptr;
+    a.m = MP; a.v = 0; a.Kv = 1;
+    const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
+    hipLaunchKernelGGL(mlp_refresh_kernel, dim3(1024), dim3(256), 0, stream, a.params, a.w1r, a.w2r, n1, off2, n2);
+    std::vector<float> h((size_t)E);
+    double total = 0.0;
+    for (int64_t s0 = 0; s0 < nslot && e == hipSuccess; s0 += E) {
+        a.eval_base = s0 * MP;
+        a.nrec = (int)std::min<int64_t>(E, nslot - s0);
+        hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
+        if (((a.nrec + 1) / 2) * (a.H / 128) >= 192)
+            hipLaunchKernelGGL((mlp_contract_kernel<true, 128>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
+        else
+            hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
+        hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipMemcpyAsync(h.data(), a.loss, sizeof(float) * a.nrec, hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e == hipSuccess) for (int q = 0; q < a.nrec; ++q) total += (double)h[(size_t)q];
+    }
+    release();
+    if (e != hipSuccess) return fail(e, "evaluating the objective");
+    *out = total / (double)N;
+    return hipSuccess;
+}
+
 
 // Everything a later update depends on: parameters (fp32 master and operand copies) and the factors of the
 // mini-batches in flight, slot by slot.

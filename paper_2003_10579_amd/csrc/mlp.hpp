@@ -15,6 +15,8 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
 hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n, float* agg_out,
                            hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg);
 float* mlp_params(MlpState* s);
+// Objective over the whole data set at the current parameters, with the trainer's forward pass.
+hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::string* msg);
 // Snapshot of everything later updates depend on (host memory; the stream must be idle).
 int64_t mlp_state_bytes(MlpState* s);
 hipError_t mlp_get_state(MlpState* s, unsigned char* host);

@@ -738,6 +738,33 @@ def test_full_objective_against_the_oracle(ssgd, oracle, torch_cuda, kind, N, d,
     ctx.close()
 
 
+@pytest.mark.parametrize("N,d,classes,hidden,variant", [
+    (1000, 256, 10, 128, "k_async"),       # 16 slots, the last one ragged
+    (20000, 128, 5, 256, "k_sync"),        # 313 slots: two passes of the evaluation buffers, the large forward tiles
+    (37, 128, 16, 128, "k_async"),         # less than one slot
+])
+def test_full_objective_of_the_two_layer_network(ssgd, oracle, torch_cuda, N, d, classes, hidden, variant):
+    """F(w) of Eq. (1) for the MLP with the forward pass of the trainer (bf16 operands), against the oracle's
+    objective with the same rounding; evaluating in the middle of a K-async run must not disturb the run."""
+    X, y = synth.mixture_data(N, d, classes, seed=43)
+    ctx, tr = _mlp_pair(ssgd, oracle, torch_cuda, X, y, 8, 2, 16, variant, ("exp", 1.0), 0.05, classes, hidden, seed=5)
+    M = oracle.Model("mlp2", X, y, classes=classes, hidden=hidden, bf16=1)
+    g, o = ctx.full_loss(0), M.full_loss(ctx.params())
+    assert abs(g - o) <= 1e-5 * max(1.0, abs(o)), (g, o)
+    ctx.run(20)
+    g, o = ctx.full_loss(0), M.full_loss(ctx.params())
+    assert abs(g - o) <= 1e-5 * max(1.0, abs(o)), (g, o)
+    assert ctx.full_loss(0) == g                      # repeatable
+    ctx.run(20)                                       # the mini-batches in flight were left alone
+    tr.run(40)
+    assert_trace_equal(ctx.trace(), tr.trace())
+    assert rel(ctx.params(), tr.params()) <= MLP_PARAM_TOL
+    other, _ = _mlp_pair(ssgd, oracle, torch_cuda, X, y, 8, 2, 16, variant, ("exp", 1.0), 0.05, classes, hidden, seed=5)
+    other.run(40)
+    assert np.array_equal(other.params(), ctx.params())
+    ctx.close(); other.close()
+
+
 def test_error_runtime_frontier_orders_the_variants(ssgd, torch_cuda):
     """The four variants at the same K on the same problem (Sec. 3, Table 1): per update K-batch-async is the
     fastest and K-sync the slowest; the synchronous variants only use fresh gradients, the asynchronous ones do not;
