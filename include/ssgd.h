@@ -53,9 +53,10 @@ typedef enum {
     SSGD_K_BATCH_SYNC = 1, /* first K mini-batches; a finished worker starts another at w_j */
     SSGD_K_ASYNC = 2,      /* Eq. (3): first K of P workers, nobody is cancelled, stale w */
     SSGD_K_BATCH_ASYNC = 3 /* first K mini-batches, nobody is cancelled: a worker that pushes re-reads the
-                              current parameters and starts its next mini-batch at once.  Linear models
-                              with 128 < d, d % 4 == 0, at most 15 classes, m <= 64, K <= 32 and
-                              P + K - 1 <= 64; fixed K or AdaSync mode 1; else SSGD_EINVAL */
+                              current parameters and starts its next mini-batch at once.  Fixed K or
+                              AdaSync mode 1.  Linear models: 128 < d, d % 4 == 0, at most 15 classes,
+                              m <= 64, K <= 32 and P + K - 1 <= 64; MLP2: its usual limits, K <= 256;
+                              else SSGD_EINVAL */
 } ssgd_variant;
 
 /* Delay X of one mini-batch on one worker (Sec. 3.1).
@@ -105,7 +106,7 @@ typedef struct {
  * is enqueued there.  `adasync` may be NULL (mode 0).
  * Limits: 1 <= K <= P <= 256 for K-sync / K-async, 1 <= K <= 256 for the batch
  * variants, m >= 1, d >= 1, classes <= 16 for SOFTMAX; MLP2 needs replicas == 1,
- * bf16 = 1, m <= 64, d % 128 == 0, hidden % 128 == 0 and runs K-sync, K-batch-sync and K-async;
+ * bf16 = 1, m <= 64, d % 128 == 0, hidden % 128 == 0;
  * SSGD_K_BATCH_ASYNC has the limits given with the enumeration.  Invalid arguments give
  * SSGD_EINVAL and leave *out untouched. */
 ssgd_status ssgd_create(const ssgd_model *model, int32_t P, int32_t K, int32_t m, int32_t variant,

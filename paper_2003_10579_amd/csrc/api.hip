@@ -342,13 +342,13 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
     if ((variant == SSGD_K_SYNC || variant == SSGD_K_ASYNC) && Kcap > P) return fail(nullptr, SSGD_EINVAL, "K must not exceed P");
     if (Kcap > kMaxWorkers) return fail(nullptr, SSGD_EINVAL, "K must not exceed 256");
     if (variant == SSGD_K_BATCH_ASYNC) {
-        // this variant runs through the steady-state kernel of the linear models only
+        if (ada.mode >= 2) return fail(nullptr, SSGD_EINVAL, "K-batch-async runs with a fixed K or plateau doubling");
+        // the linear models run this variant through the steady-state kernel only
         const int32_t mp = (m + 3) / 4 * 4;
         const int32_t classes = model->kind == SSGD_LSQ ? 1 : model->classes;
-        if (model->kind == SSGD_MLP2 || model->d <= 128 || model->d % 4 != 0 || classes > 15 || mp > 64 || Kcap > 32 ||
-            P + Kcap - 1 > 64 || ada.mode >= 2)
-            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models with 128 < d, d % 4 == 0, at most 15 classes, m <= 64, "
-                                             "K <= 32, P + K - 1 <= 64, fixed K or plateau doubling");
+        if (model->kind != SSGD_MLP2 && (model->d <= 128 || model->d % 4 != 0 || classes > 15 || mp > 64 || Kcap > 32 || P + Kcap - 1 > 64))
+            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models need 128 < d, d % 4 == 0, at most 15 classes, m <= 64, "
+                                             "K <= 32, P + K - 1 <= 64");
     }
     if (model->kind == SSGD_LSQ) {
         if (model->bf16) return fail(nullptr, SSGD_EINVAL, "bf16 is for the MLP only");
@@ -357,7 +357,6 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
     } else if (model->kind == SSGD_MLP2) {
         if (model->classes < 2 || model->classes > kClassPad || model->hidden < 64 || model->hidden % 64 || model->d % 32 || replicas != 1)
             return fail(nullptr, SSGD_EINVAL, "MLP needs 2..16 classes, hidden % 64 == 0, d % 32 == 0, replicas == 1");
-        if (variant == SSGD_K_BATCH_ASYNC) return fail(nullptr, SSGD_EINVAL, "MLP supports K-sync, K-batch-sync and K-async");
     } else {
         return fail(nullptr, SSGD_EINVAL, "unknown model kind");
     }

@@ -69,12 +69,36 @@ struct MlpArgs {
     float* dw_part;            // [nsplit][H][d] partial first-layer gradient sums when the slots are split over workgroups
     int32_t nsplit;
     int64_t eval_base;         // >= 0: objective evaluation; record r holds data rows eval_base + 64 r .. + 63 in slot r
+    int32_t* plan;             // K-batch-async: slot bookkeeping and the lists of the current update (layout: PlanView)
+    int32_t S;                 // slots
+};
+
+// K-batch-async keeps P mini-batches in flight and consumes up to K per update, some of them started during the
+// same update by a worker whose older mini-batch that update also consumes: slots are handed out from a free list,
+// one per started mini-batch, and return to it at the start of the next update's plan.
+struct PlanView {
+    int32_t* meta;         // [0] free slots, [1] slots to free at the next plan, [2] set if the free list ran dry
+    int32_t* wslot;        // [P]         slot of the worker's mini-batch in flight
+    int32_t* freel;        // [S]         stack of free slots
+    int32_t* pending;      // [Kcap]      slots consumed by the last planned update
+    int32_t* rec_worker;   // [S]         mini-batches that start at the planned version, in event order
+    int32_t* rec_ord;      // [S]
+    int32_t* rec_slot;     // [S]
+    int32_t* cons_slot;    // [Kcap]      slots of the K gradients of the update, in arrival order
+    __host__ __device__ PlanView(int32_t* p, int P, int S, int Kcap) {
+        meta = p; wslot = meta + 4; freel = wslot + P; pending = freel + S; rec_worker = pending + Kcap;
+        rec_ord = rec_worker + S; rec_slot = rec_ord + S; cons_slot = rec_slot + S;
+    }
+    static size_t words(int P, int S, int Kcap) { return 4 + (size_t)P + 4 * (size_t)S + 2 * (size_t)Kcap; }
 };
 
 // worker and mini-batch ordinal of record r of the compute list of version v, and its slot
 __device__ __forceinline__ void record_of(const MlpArgs& a, int r, int& worker, int& ordinal, int& slot) {
     if (a.eval_base >= 0) {
         worker = 0; ordinal = 0; slot = r;
+    } else if (a.variant == kBatchAsync) {
+        const PlanView pl(a.plan, a.P, a.S, a.Kcap);
+        worker = pl.rec_worker[r]; ordinal = pl.rec_ord[r]; slot = pl.rec_slot[r];
     } else if (a.variant == kAsync) {
         worker = (a.v == 0) ? r : a.tr.sel[(a.v - 1) * a.tr.Kcap + r];
         ordinal = 0;
@@ -86,7 +110,47 @@ __device__ __forceinline__ void record_of(const MlpArgs& a, int r, int& worker, 
     }
 }
 __device__ __forceinline__ int consumed_slot(const MlpArgs& a, int l) {
+    if (a.variant == kBatchAsync) return PlanView(a.plan, a.P, a.S, a.Kcap).cons_slot[l];
     return a.variant == kAsync ? a.tr.sel[a.v * a.tr.Kcap + l] : l;
+}
+
+// ---- K-batch-async: the lists of update v from its trace row (Sec. 2.2: the K earliest mini-batches, whoever
+// computed them).  Mini-batches that start at version v: at v = 0 every worker's first one, later the one of the
+// worker whose push triggered update v - 1; then, for each of the first K - 1 pushes of update v, the next mini-batch
+// of the pushing worker (ordinal: how many it has started at this version).  Sequential, a few dozen entries.
+__global__ void mlp_batch_plan_kernel(MlpArgs a) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const PlanView pl(a.plan, a.P, a.S, a.Kcap);
+    int nfree = pl.meta[0];
+    const int npend = pl.meta[1];
+    for (int i = 0; i < npend; ++i) pl.freel[nfree++] = pl.pending[i];
+    const int64_t v = a.v;
+    const int Kc = a.tr.Kcap, K = a.Kv;
+    int nrec = 0;
+    bool dry = false;
+    auto start = [&](int worker, int ordinal) {
+        if (nfree <= 0 || nrec >= a.S) { dry = true; return; }
+        const int slot = pl.freel[--nfree];
+        pl.wslot[worker] = slot;
+        pl.rec_worker[nrec] = worker; pl.rec_ord[nrec] = ordinal; pl.rec_slot[nrec] = slot;
+        ++nrec;
+    };
+    if (v == 0) {
+        for (int w = 0; w < a.P; ++w) start(w, 0);
+    } else {
+        const int Kprev = a.tr.K[v - 1];
+        start(a.tr.sel[(v - 1) * Kc + Kprev - 1], 0);
+    }
+    for (int l = 0; l < K; ++l) {
+        const int w = a.tr.sel[v * Kc + l];
+        const int slot = pl.wslot[w];
+        pl.cons_slot[l] = slot;
+        pl.pending[l] = slot;
+        if (l + 1 < K) start(w, a.tr.tau[v * Kc + l] == (int32_t)v ? a.tr.ord[v * Kc + l] + 1 : 0);
+    }
+    pl.meta[0] = nfree;
+    pl.meta[1] = K;
+    if (dry) pl.meta[2] = 1;
 }
 
 // ---- gather: one workgroup per (record, block of 128 columns) ---------------------------------
@@ -491,7 +555,7 @@ struct MlpState {
     int S = 0;
     int64_t nw = 0;
     int prevK = 0;          // size of the consume list of the last update run (records of the next K-async step)
-    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, dw_part;
+    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, dw_part, plan;
     hipStream_t stream = nullptr;
 };
 
@@ -507,7 +571,8 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     MlpArgs& a = s->a;
     a.d = model.d; a.H = model.hidden; a.C = model.classes; a.P = P; a.m = m; a.variant = variant; a.Kcap = Kcap;
     a.X = model.X; a.y = (const int32_t*)model.y; a.N = (uint32_t)model.N; a.seed = seed; a.lr = (float)lr;
-    s->S = (variant == kAsync) ? P : Kcap;
+    s->S = (variant == kAsync) ? P : (variant == kBatchAsync ? P + Kcap : Kcap);
+    a.S = s->S;
     const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
     s->nw = off2 + n2 + a.C;
     const size_t S = (size_t)s->S;
@@ -527,6 +592,17 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(s->loss.alloc(sizeof(float) * S));
     TRY(s->ylab.alloc(sizeof(int32_t) * S * MP));
     TRY(s->dw_part.alloc(sizeof(float) * kMaxSplit * (size_t)n1));
+    {
+        // every slot free (popped in the order 0, 1, ...), no worker has a mini-batch yet
+        std::vector<int32_t> h(PlanView::words(P, s->S, Kcap), 0);
+        TRY(s->plan.alloc(sizeof(int32_t) * h.size()));
+        PlanView pl(h.data(), P, s->S, Kcap);
+        pl.meta[0] = s->S;
+        for (int i = 0; i < P; ++i) pl.wslot[i] = -1;
+        for (int i = 0; i < s->S; ++i) pl.freel[i] = s->S - 1 - i;
+        TRY(hipMemcpy(s->plan.p, h.data(), sizeof(int32_t) * h.size(), hipMemcpyHostToDevice));
+        a.plan = (int32_t*)s->plan.p;
+    }
     TRY(hipMemsetAsync(s->xb.p, 0, 2 * S * MP * a.d, stream));
     TRY(hipMemsetAsync(s->xbt.p, 0, 2 * S * MP * a.d, stream));
     TRY(hipMemsetAsync(s->hbuf.p, 0, sizeof(float) * S * MP * a.H, stream));
@@ -580,7 +656,9 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
         a.v = v0 + q;
         a.Kv = Ks[(size_t)q];
         a.nrec = (a.variant == kAsync) ? (a.v == 0 ? a.P : (q == 0 ? prevK : Ks[(size_t)q - 1])) : a.Kv;
+        if (a.variant == kBatchAsync) a.nrec = (a.v == 0 ? a.P : 1) + a.Kv - 1;
         if (a.Kv < 1 || a.Kv > a.Kcap || a.nrec < 0 || a.nrec > s->S) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return fail(hipErrorInvalidValue, "inconsistent K in the trace"); }
+        if (a.variant == kBatchAsync) hipLaunchKernelGGL(mlp_batch_plan_kernel, dim3(1), dim3(64), 0, stream, a);
         if (a.nrec > 0) {
             hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
             // small tiles while the large ones would not fill the chip
@@ -613,6 +691,12 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
     if (e != hipSuccess) return fail(e, "running the segment");
     e = hipGetLastError();
     if (e != hipSuccess) return fail(e, "launching the segment");
+    if (a.variant == kBatchAsync) {
+        int32_t meta[4] = {0, 0, 0, 0};
+        e = hipMemcpy(meta, a.plan, sizeof(meta), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(e, "reading the slot plan");
+        if (meta[2] != 0) return fail(hipErrorInvalidValue, "the slot pool of K-batch-async ran dry: inconsistent trace");
+    }
     (void)ws;
     return hipSuccess;
 }
@@ -668,7 +752,7 @@ hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::stri
 // mini-batches in flight, slot by slot.
 static std::vector<DevMem*> mlp_state_buffers(MlpState* s) {
     return {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss,
-            &s->ylab};
+            &s->ylab, &s->plan};
 }
 
 int64_t mlp_state_bytes(MlpState* s) {
@@ -707,7 +791,7 @@ float* mlp_params(MlpState* s) { return s ? (float*)s->params.p : nullptr; }
 void mlp_destroy(MlpState* s) {
     if (!s) return;
     DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss, &s->ylab,
-                      &s->dw_part};
+                      &s->dw_part, &s->plan};
     for (DevMem* b : bufs) b->release();
     delete s;
 }

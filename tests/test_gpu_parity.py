@@ -412,17 +412,22 @@ def test_mlp_initial_parameters_bit_exact(ssgd, oracle, torch_cuda):
     ("k_batch_sync", 3, 5, 16, 128, 4, 128),  # a worker contributes more than once (K > P)
     ("k_sync", 80, 64, 4, 128, 5, 128),       # 64 slots per update: the gradient contraction is split into four shares
     ("k_async", 100, 90, 3, 256, 4, 128),     # five shares of 18 slots; ranked selection in the schedule
+    ("k_batch_async", 6, 3, 16, 256, 5, 128),  # mini-batches started and consumed inside one update
+    ("k_batch_async", 3, 5, 64, 128, 4, 128),  # K > P: a worker pushes several times per update
+    ("k_batch_async", 40, 70, 4, 128, 3, 128), # 109 records at version 0, split gradient contraction
+    ("k_batch_async", 5, 1, 64, 128, 16, 128), # K = 1: fully asynchronous SGD
 ])
 def test_mlp_gradients_teacher_forced(ssgd, oracle, torch_cuda, variant, P, K, m, d, classes, hidden):
     """Every update's averaged gradient against the oracle's.  K-sync is teacher-forced (the oracle's iterate is
-    loaded before each step); K-async runs free, its in-flight factors depend on earlier iterates."""
+    loaded before each step); the asynchronous variants run free, their in-flight factors depend on earlier
+    iterates."""
     torch = torch_cuda
     X, y = synth.mixture_data(2000, d, classes, seed=4)
     ctx, tr = _mlp_pair(ssgd, oracle, torch, X, y, P, K, m, variant, ("shifted_exp", 0.5, 1.0), 0.05, classes, hidden, seed=5)
     agg = torch.zeros(ctx.nw, dtype=torch.float32, device="cuda")
     worst = 0.0
     for j in range(25 if K < 64 else 8):
-        if variant != "k_async":
+        if variant not in ("k_async", "k_batch_async"):
             ctx.set_params(tr.params())
         ctx.step(agg)
         worst = max(worst, rel(agg.cpu().numpy(), tr.step()))
@@ -441,6 +446,24 @@ def test_mlp_kasync_training_run(ssgd, oracle, torch_cuda):
     assert_trace_equal(ctx.trace(), tr.trace())
     pr = rel(ctx.params(), tr.params())
     print(f"MLP parameter error after 150 updates {pr:.3e}")
+    assert pr <= MLP_PARAM_TOL, pr
+    assert np.allclose(ctx.trace()["loss"], tr.trace()["loss"], rtol=5e-3, atol=1e-4)
+    ctx.close()
+
+
+def test_mlp_kbatch_async_training_run_with_plateau_doubling(ssgd, oracle, torch_cuda):
+    """K-batch-async on the MLP, free-running for 120 updates while AdaSync doubles K (2 -> 8) on plateaus: the slot
+    of every mini-batch in flight survives the changes of K."""
+    X, y = synth.mixture_data(3000, 256, 10, seed=8)
+    ada = {"mode": 1, "K0": 2, "Kmax": 8, "window": 15, "rel_tol": 0.5}
+    ctx, tr = _mlp_pair(ssgd, oracle, torch_cuda, X, y, 12, 2, 32, "k_batch_async", ("shifted_exp", 0.5, 1.0), 0.05, 10, 128,
+                        seed=3, adasync=ada)
+    ctx.run(50); ctx.run(70)
+    tr.run(120)
+    assert_trace_equal(ctx.trace(), tr.trace())
+    assert ctx.trace()["K"].max() > 2
+    pr = rel(ctx.params(), tr.params())
+    print(f"MLP K-batch-async parameter error after 120 updates {pr:.3e}")
     assert pr <= MLP_PARAM_TOL, pr
     assert np.allclose(ctx.trace()["loss"], tr.trace()["loss"], rtol=5e-3, atol=1e-4)
     ctx.close()
@@ -635,12 +658,13 @@ def test_snapshot_resume_continues_the_same_run(ssgd, oracle, torch_cuda, kind, 
         c.close()
 
 
-def test_mlp_snapshot_resume(ssgd, oracle, torch_cuda):
+@pytest.mark.parametrize("variant,K", [("k_async", 2), ("k_batch_async", 4)])
+def test_mlp_snapshot_resume(ssgd, oracle, torch_cuda, variant, K):
     torch = torch_cuda
     X, y = synth.mixture_data(600, 256, 5, seed=15)
     gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
-    mk = lambda: ssgd.Context("mlp2", Xd, yd, 6, 2, 16, "k_async", gd, 0.05, seed=16, classes=5, hidden=128, bf16=1)
+    mk = lambda: ssgd.Context("mlp2", Xd, yd, 6, K, 16, variant, gd, 0.05, seed=16, classes=5, hidden=128, bf16=1)
     a = mk()
     a.run(9)
     blob = a.get_state()
