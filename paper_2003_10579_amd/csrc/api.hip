@@ -188,6 +188,8 @@ ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, boo
         a.agg_out = agg_out;
         a.pair_cus = 0; a.pair_layers = 0;
         a.shared_cus = (a.replicas * c->G > c->cu_count) ? 1 : 0;
+        a.prof_wave = 0; a.prof_a = -1; a.prof_b = -1; a.prof_base = (int64_t)c->R * c->G * 20;
+        if (const char* e = getenv("SSGD_PHASE_PROFILE")) (void)sscanf(e, "%d,%d,%d", &a.prof_a, &a.prof_b, &a.prof_wave);
         if (tile && a.replicas == per_launch && c->cu_count % 8 == 0 && resident % c->cu_count == 0 && !getenv("SSGD_NO_PAIRING")) {
             a.pair_cus = c->cu_count / 8;
             a.pair_layers = resident / c->cu_count;
@@ -434,8 +436,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         HIP_C(c->xcc_ids.alloc(sizeof(int32_t) * R * c->G));
         HIP_C(hipMemsetAsync(c->xcc_ids.p, 0xFF, sizeof(int32_t) * R * c->G, c->stream));
         if (getenv("SSGD_PHASE_PROFILE")) {
-            HIP_C(c->prof.alloc(sizeof(unsigned long long) * R * c->G * 20));
-            HIP_C(hipMemsetAsync(c->prof.p, 0, sizeof(unsigned long long) * R * c->G * 20, c->stream));
+            HIP_C(c->prof.alloc(sizeof(unsigned long long) * R * c->G * 22));
+            HIP_C(hipMemsetAsync(c->prof.p, 0, sizeof(unsigned long long) * R * c->G * 22, c->stream));
         }
         HIP_C(c->arrive.alloc(sizeof(unsigned int) * kArriveStride * R));
         HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * R, c->stream));
@@ -736,14 +738,14 @@ void ssgd_destroy(ssgd_ctx* c) {
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
     if (c->prof.p) {
-        // diagnostics requested through SSGD_PHASE_PROFILE: mean shader-clock cycles per phase and update
-        std::vector<unsigned long long> h((size_t)c->R * c->G * 20);
-        if (hipMemcpy(h.data(), c->prof.p, h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost) == hipSuccess && c->j > 0) {
-            double tot[20] = {0};
-            for (size_t q = 0; q < h.size(); ++q) tot[q % 20] += (double)h[q];
-            fprintf(stderr, "ssgd phase profile (cycles per update per workgroup):");
-            for (int q = 0; q < 20; ++q) fprintf(stderr, " p%d=%.0f", q, tot[q] / ((double)c->R * c->G * (double)c->j));
-            fprintf(stderr, "\n");
+        // diagnostics requested through SSGD_PHASE_PROFILE=a,b[,wave]: mean cycles per update between mark a and the
+        // next mark b of one wave per workgroup (marks below 16: compute waves, from 16: loader waves)
+        std::vector<unsigned long long> h((size_t)c->R * c->G * 2);
+        if (hipMemcpy(h.data(), c->prof.as<unsigned long long>() + (size_t)c->R * c->G * 20, h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost) == hipSuccess && c->j > 0) {
+            double tot[2] = {0, 0};
+            for (size_t q = 0; q < h.size(); ++q) tot[q % 2] += (double)h[q];
+            fprintf(stderr, "ssgd phase profile %s: %.0f cycles per update and workgroup\n", getenv("SSGD_PHASE_PROFILE"),
+                    (tot[0] + tot[1]) / ((double)c->R * c->G * (double)c->j));
         }
     }
     if (c->xcc_ids.p && getenv("SSGD_DEBUG")) {

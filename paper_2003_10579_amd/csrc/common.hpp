@@ -99,11 +99,13 @@ struct LinArgs {
     // CUs.  Polling for the exchange then pauses longer between rounds: the re-reads of a waiting workgroup compete
     // with the memory operations of the one it shares the CU with.
     int32_t shared_cus;
+    int32_t prof_wave, prof_a, prof_b;   // diagnostics: wave and the pair of marks of the phase profile
+    int64_t prof_base;                   // first word of the steady-state kernel's part of prof
     // Steady-state kernel: 1 for a synchronous variant whose iteration does not fit one 64-row tile.  The rows of the
     // K mini-batches are then taken 64 at a time, each tile through the whole forward / exchange / backward schedule,
     // the gradient summed over the tiles and the update applied after the last one.
     int32_t chunked;
-    unsigned long long* prof;   // nullable diagnostics: [R][G][20] shader-clock cycles spent per phase
+    unsigned long long* prof;   // nullable diagnostics: [R][G][20] cycles per phase (general kernel), then [R][G][2] cycles of the profiled interval (steady-state kernel: compute wave, loader wave)
 };
 int linear_max_resident_groups(int nbw, size_t lds_bytes);
 size_t linear_lds_bytes(int nbw, int C, int S, bool parks);

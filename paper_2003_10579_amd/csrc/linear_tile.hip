@@ -161,10 +161,16 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         int q_sel = -1, q_tau = -1, q_ord = 0;   // lane l: entry l of the consume list of a later version, in flight
         int cur_sel = -1;                        // consume list of the version before the one being prepared
 
-        uint32_t lph[4] = {0, 0, 0, 0}, lprev = 0;
-        const bool lprof = PROF && tid == NTC;
+        // diagnostics: cycles between passing mark prof_a and the next passing of mark prof_b, summed in scalar registers
+        uint32_t lp_acc = 0, lp_t0 = 0;
+        const bool lprof = PROF && lw == a.prof_wave;
         auto lmark = [&](int q) {
-            if constexpr (PROF) { if (lprof) { const uint32_t now = (uint32_t)clock64(); lph[q] += now - lprev; lprev = now; } }
+            if constexpr (PROF) {
+                if (lprof) {
+                    if (16 + q == a.prof_a) lp_t0 = (uint32_t)clock64();
+                    if (16 + q == a.prof_b) lp_acc += (uint32_t)clock64() - lp_t0;
+                }
+            }
         };
 
         auto issue_lists = [&](int64_t ver) {
@@ -346,7 +352,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         for (int64_t step = 0; step < a.nsteps; ++step) {
             const int tiles = h_tiles;               // of update a.v0 + step
             for (int t = 0; t < tiles; ++t) {
-                if constexpr (PROF) { if (lprof) lprev = (uint32_t)clock64(); }
+                lmark(4);
                 const int flags = (t + 1 == tiles ? 1 : 0) | (t == 0 ? 2 : 0);
                 publish(flags);
                 lmark(0);
@@ -367,8 +373,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             }
         }
         if constexpr (PROF) {
-            if (lprof)
-                for (int q = 0; q < 4; ++q) a.prof[((int64_t)rep * G + slice) * 20 + 16 + q] += lph[q];
+            if (lprof && lane == 0) a.prof[(int64_t)a.prof_base + ((int64_t)rep * G + slice) * 2 + 1] += lp_acc;
         }
         lds_barrier();                               // the compute waves' last LDS writes
         return;
@@ -445,16 +450,21 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     const int slice_bytes = a.maxrows * 16 * 4;
 
     uint32_t n_fenced = 0, n_fast = 0;       // exchanges of each kind so far in this launch
-    uint32_t ph[14] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, tprev = 0;   // 32-bit cycle counts: fewer registers
-    const bool profiling = PROF && tid == 0;
+    uint32_t p_acc = 0, p_t0 = 0;            // diagnostics, as in the loader waves
+    const bool profiling = PROF && wave == a.prof_wave;
     auto mark = [&](int phase) {
-        if constexpr (PROF) { if (profiling) { const uint32_t now = (uint32_t)clock64(); ph[phase] += now - tprev; tprev = now; } }
+        if constexpr (PROF) {
+            if (profiling) {
+                if (phase == a.prof_a) p_t0 = (uint32_t)clock64();
+                if (phase == a.prof_b) p_acc += (uint32_t)clock64() - p_t0;
+            }
+        }
     };
 
     float gsum[16];          // this thread's part of sum_l g_l of the update in progress: gsum[4 vv + c]
     for (int64_t step = 0; step < a.nsteps; ++step) {
       for (bool last_tile = false; !last_tile;) {           // the tiles of update a.v0 + step
-        if constexpr (PROF) { if (profiling) tprev = (uint32_t)clock64(); }
+        mark(14);
         lds_barrier();                                      // TU
         mark(0);
         const bool fast = L.ctl[1] != 0;
@@ -691,6 +701,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             if (z_qd == 3) dl.w = loss * inv_m;
             *reinterpret_cast<f32x4*>(L.zbuf + z_row * 16 + 4 * z_qd) = dl;
         }
+        mark(13);
         lds_barrier();                                      // D
         if (L.ctl[0] != 0) return;   // uniform: every thread reads the same LDS word
         mark(5);
@@ -885,8 +896,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
       }
     }
     if constexpr (PROF) {
-        if (profiling)
-            for (int q = 0; q < 14; ++q) a.prof[((int64_t)rep * G + slice) * 20 + q] += ph[q];
+        if (profiling && lane == 0) a.prof[(int64_t)a.prof_base + ((int64_t)rep * G + slice) * 2] += p_acc;
     }
     lds_barrier();
 
