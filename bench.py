@@ -135,6 +135,14 @@ def main():
                      "algorithmic_bytes_per_launch": per_launch_bytes},
     }
     out["roofline"]["traffic"] = measured_traffic(R, J)
+    # what a plain streaming read of the same data set reaches on this device, beside the published peak
+    stream_gbs = ssgd.stream_read_rate(Xd, passes=10) / 1e9
+    out["roofline"]["stream_read_GBps"] = stream_gbs
+    out["roofline"]["frac_of_stream_read"] = achieved / stream_gbs
+    if out["roofline"]["traffic"]:
+        # the counted HBM-side bytes (sample rows plus the round trip of the parked gradients) against the same ceiling
+        out["roofline"]["traffic_GBps"] = out["roofline"]["traffic"] / (kms / kn * 1e-3) / 1e9
+        out["roofline"]["traffic_frac_of_stream_read"] = out["roofline"]["traffic_GBps"] / stream_gbs
     out["config"]["mc_trials_per_s"] = mc_rate(ssgd)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(X, y, spec)

@@ -200,6 +200,13 @@ ssgd_status ssgd_debug_delays(const ssgd_delay_dist *dist, const uint32_t *bits,
 ssgd_status ssgd_debug_batch(uint64_t seed, uint32_t replica, uint32_t worker, uint32_t ordinal,
                              uint32_t version, int32_t m, int64_t N, uint32_t *out);
 
+/* Measurement aid (the achievable ceiling that Sec. 6-style throughput figures of the HBM-bound paths are
+ * set against): `passes` plain streaming reads of `bytes` bytes at `data` (DEVICE, 16-byte aligned), timed
+ * with HIP events on hip_stream; *bytes_per_s (HOST) receives bytes read per second.  The buffer is only
+ * read.  SSGD_EINVAL for a null or misaligned buffer, bytes < 16 or passes < 1. */
+ssgd_status ssgd_stream_read_rate(const void *data, int64_t bytes, int32_t passes, void *hip_stream,
+                                  double *bytes_per_s);
+
 /* Text of the last error of a context (ctx may be NULL: last error of a call
  * that has no context).  Valid until the next call on that context. */
 const char *ssgd_last_error(const ssgd_ctx *ctx);

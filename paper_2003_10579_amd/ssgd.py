@@ -21,7 +21,8 @@ EXPORTS = [
     "ssgd_create", "ssgd_run", "ssgd_reserve_trace", "ssgd_step", "ssgd_param_count", "ssgd_updates_done", "ssgd_current_K",
     "ssgd_trace_width", "ssgd_get_trace", "ssgd_get_params", "ssgd_set_params", "ssgd_force_K",
     "ssgd_get_workers", "ssgd_state_bytes", "ssgd_get_state", "ssgd_set_state", "ssgd_full_loss",
-    "ssgd_runtime_mc", "ssgd_debug_delays", "ssgd_debug_batch", "ssgd_last_error", "ssgd_last_kernel_ms",
+    "ssgd_runtime_mc", "ssgd_debug_delays", "ssgd_debug_batch", "ssgd_stream_read_rate", "ssgd_last_error",
+    "ssgd_last_kernel_ms",
     "ssgd_destroy",
 ]
 
@@ -95,6 +96,7 @@ def lib():
         L.ssgd_debug_delays.argtypes = [C.POINTER(DelayDist), C.c_void_p, C.c_int64, C.c_void_p]
         L.ssgd_debug_batch.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32,
                                        C.c_int64, C.c_void_p]
+        L.ssgd_stream_read_rate.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.ssgd_last_error.restype = C.c_char_p
         L.ssgd_last_error.argtypes = [C.c_void_p]
         L.ssgd_last_kernel_ms.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -259,6 +261,16 @@ def debug_delays(dist, bits):
     out = np.zeros(bits.size, dtype=np.float32)
     _check(lib().ssgd_debug_delays(C.byref(dist), bits.ctypes.data, bits.size, out.ctypes.data))
     return out
+
+
+def stream_read_rate(tensor, passes=10, stream=None):
+    """Bytes per second of a plain streaming read of a device tensor (the achievable HBM ceiling)."""
+    import torch
+    handle = (stream or torch.cuda.current_stream()).cuda_stream
+    out = C.c_double(0.0)
+    _check(lib().ssgd_stream_read_rate(C.c_void_p(tensor.data_ptr()), tensor.numel() * tensor.element_size(), passes,
+                                       C.c_void_p(handle), C.byref(out)))
+    return out.value
 
 
 def debug_batch(seed, replica, worker, ordinal, version, m, N):

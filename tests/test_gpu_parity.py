@@ -844,3 +844,14 @@ def test_kbatch_async_with_plateau_doubling(ssgd, oracle, torch_cuda):
     assert np.allclose(g["loss"], o["loss"], rtol=2e-4, atol=1e-6)
     assert rel(ctx.params(), tr.params()) <= PARAM_TOL
     ctx.close()
+
+
+def test_stream_read_rate_is_plausible(ssgd, torch_cuda):
+    """The plain read kernel behind the 'achievable ceiling' figure: between 1 and 8 TB/s on 256 MB, and an
+    invalid buffer is refused."""
+    torch = torch_cuda
+    x = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+    rate = ssgd.stream_read_rate(x, passes=5)
+    assert 1.0e12 < rate < 8.0e12, rate
+    with pytest.raises(ssgd.SsgdError):
+        ssgd.stream_read_rate(x[1:], passes=1)          # not 16-byte aligned
