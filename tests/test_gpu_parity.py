@@ -180,6 +180,37 @@ def test_lsq_parity_small(ssgd, oracle, torch_cuda, variant, P, K, m, d):
     _run_pair(ssgd, oracle, torch_cuda, "lsq", X, y, P, K, m, variant, ("exp", 1.0), 0.01, 150, seed=4)
 
 
+@pytest.mark.parametrize("kind,variant,P,K,m,N,d,classes", [
+    ("lsq", "k_sync", 1, 1, 1, 50, 4, 1),             # serial SGD on single samples
+    ("softmax", "k_async", 1, 1, 3, 40, 8, 2),        # one worker: never stale
+    ("lsq", "k_async", 3, 2, 4, 1, 12, 1),            # a data set of one sample: every index is 0
+    ("lsq", "k_sync", 256, 256, 1, 300, 16, 1),       # the largest number of workers, all of them waited for
+    ("softmax", "k_batch_sync", 2, 256, 1, 64, 8, 3), # ordinals up to 255 on two workers
+    ("softmax", "k_async", 256, 1, 2, 500, 260, 10),  # fully asynchronous, staleness in the hundreds
+])
+def test_degenerate_and_extreme_shapes(ssgd, oracle, torch_cuda, kind, variant, P, K, m, N, d, classes):
+    if kind == "lsq":
+        X, y, _ = synth.lsq_data(N, d, 9)
+    else:
+        X, y = synth.mixture_data(N, d, classes, seed=9)
+    _run_pair(ssgd, oracle, torch_cuda, kind, X, y, P, K, m, variant, ("exp", 1.0), 0.01, 30, seed=2, classes=classes,
+              check_steps=30)
+
+
+def test_run_of_zero_updates_changes_nothing(ssgd, torch_cuda):
+    torch = torch_cuda
+    X, y, _ = synth.lsq_data(200, 16, 5)
+    ctx = ssgd.Context("lsq", torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(), 4, 2, 8, "k_async",
+                       ssgd.delay_dist("exp", 1.0), 0.01, seed=1)
+    ctx.run(0)
+    assert ctx.updates == 0 and not ctx.params().any()
+    ctx.run(5)
+    before = ctx.params().copy()
+    ctx.run(0)
+    assert ctx.updates == 5 and np.array_equal(ctx.params(), before)
+    ctx.close()
+
+
 def test_replicas_are_independent_runs(ssgd, oracle, torch_cuda):
     """Replica r of one context == a single-replica oracle run keyed by r; 19 replicas span three
     launch groups of eight."""
