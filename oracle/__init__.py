@@ -77,6 +77,7 @@ def lib():
         L.orc_minibatch_grad.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.orc_full_loss.restype = C.c_double
         L.orc_full_loss.argtypes = [C.POINTER(_Model), C.c_void_p]
+        L.orc_full_grad.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p]
         L.orc_init_params.argtypes = [C.POINTER(_Model), C.c_uint64, C.c_void_p]
         L.orc_create.restype = C.c_void_p
         L.orc_create.argtypes = [C.POINTER(_Model), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -185,6 +186,13 @@ class Model:
     def full_loss(self, w):
         w = np.ascontiguousarray(w, dtype=np.float32)
         return float(lib().orc_full_loss(C.byref(self.c), w.ctypes.data))
+
+    def full_grad(self, w):
+        """Gradient of the objective over the whole data set (Eq. (1)), fp64."""
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        out = np.zeros(self.nw, dtype=np.float64)
+        lib().orc_full_grad(C.byref(self.c), w.ctypes.data, out.ctypes.data)
+        return out
 
 
 _VARIANTS = {"k_sync": K_SYNC, "k_batch_sync": K_BATCH_SYNC, "k_async": K_ASYNC,

@@ -378,6 +378,25 @@ double orc_full_loss(const orc_model *M, const float *w)
     return total / (double)M->N;
 }
 
+/* Gradient of the full-data objective, grad F(w) = (1/N) sum_n grad f(w, xi_n)
+ * (Eq. (1); the quantity the staleness bound of Sec. 5.1 is stated in), fp64:
+ * the mini-batch gradients of consecutive blocks, weighted by their sizes. */
+void orc_full_grad(const orc_model *M, const float *w, double *grad_out)
+{
+    const int64_t nw = orc_param_count(M);
+    double *g = (double *)malloc(sizeof(double) * (size_t)nw);
+    uint32_t idx[64];
+    for (int64_t q = 0; q < nw; ++q) grad_out[q] = 0.0;
+    for (int64_t n0 = 0; n0 < M->N; n0 += 64) {
+        int32_t cnt = (int32_t)((M->N - n0) < 64 ? (M->N - n0) : 64);
+        for (int32_t s = 0; s < cnt; ++s) idx[s] = (uint32_t)(n0 + s);
+        (void)orc_minibatch_grad(M, w, idx, cnt, g);
+        for (int64_t q = 0; q < nw; ++q) grad_out[q] += g[q] * cnt;
+    }
+    for (int64_t q = 0; q < nw; ++q) grad_out[q] /= (double)M->N;
+    free(g);
+}
+
 /* ------------------------------------------------------------------------- */
 /* The event process and the parameter-server loop.                           */
 /* ------------------------------------------------------------------------- */

@@ -634,6 +634,39 @@ def test_softmax_objective_special_cases(oracle):
     assert abs(M.full_loss(only_bias) + float(freq @ logp)) < 1e-12
 
 
+def test_full_gradient_pins(oracle):
+    """grad F of Eq. (1): zero at the least-squares optimum of the normal equations and equal to X^T (X w - y) / N
+    elsewhere (written with numpy, fp64); for softmax at w = 0 the bias part is 1/classes minus the label frequencies
+    and the weight part is the class-mean difference (1/N) sum_n (1/classes - [y_n = c]) x_n; and central differences
+    of the objective reproduce every sampled component."""
+    X, y, _ = synth.lsq_data(500, 12, 4)
+    M = oracle.Model("lsq", X, y)
+    X64, y64 = X.astype(np.float64), y.astype(np.float64)
+    w_opt = np.linalg.solve(X64.T @ X64, X64.T @ y64)
+    g_opt = M.full_grad(w_opt.astype(np.float32))
+    assert np.abs(g_opt).max() < 1e-6                   # the fp32 rounding of w_opt, nothing more
+    rng = np.random.default_rng(8)
+    w = rng.standard_normal(12).astype(np.float32)
+    want = X64.T @ (X64 @ w.astype(np.float64) - y64) / 500
+    assert np.allclose(M.full_grad(w), want, rtol=1e-12, atol=1e-14)
+
+    C_, d, N = 4, 6, 333                                # N is not a multiple of the 64-row blocks
+    Xs, ys = synth.mixture_data(N, d, C_, seed=10)
+    S = oracle.Model("softmax", Xs, ys, classes=C_)
+    g0 = S.full_grad(np.zeros(C_ * d + C_, dtype=np.float32))
+    onehot = np.eye(C_)[ys]
+    assert np.allclose(g0[C_ * d:], 1.0 / C_ - onehot.mean(axis=0), atol=1e-14)
+    assert np.allclose(g0[:C_ * d].reshape(C_, d), (1.0 / C_ - onehot).T @ Xs.astype(np.float64) / N, atol=1e-13)
+    ws = (0.2 * rng.standard_normal(C_ * d + C_)).astype(np.float32)
+    g = S.full_grad(ws)
+    for q in rng.choice(ws.size, size=8, replace=False):
+        h = 2.0 ** -7                                   # exactly representable steps: w +- h are fp32 numbers
+        up, dn = ws.copy(), ws.copy()
+        up[q] += np.float32(h); dn[q] -= np.float32(h)
+        fd = (S.full_loss(up) - S.full_loss(dn)) / (float(up[q]) - float(dn[q]))
+        assert abs(fd - g[q]) < 2e-4 * max(1.0, abs(g[q])), (q, fd, g[q])
+
+
 # --------------------------------------------------------------------------- AdaSync
 
 def test_adasync_plateau_rule(oracle):
