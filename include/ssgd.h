@@ -159,6 +159,14 @@ ssgd_status ssgd_force_K(ssgd_ctx *ctx, int32_t K);
  * call allocates and frees (SSGD_ENOMEM if they do not fit); mini-batches in flight are untouched. */
 ssgd_status ssgd_full_loss(ssgd_ctx *ctx, int32_t replica, double *loss_out);
 
+/* The gradient of that objective, grad F(w) = (1/N) sum_n grad f(w, xi_n), at the replica's current
+ * parameters: the quantity in which the staleness bound of Sec. 5.1 is stated
+ * (E||grad F(w_j) - grad F(w_tau)||^2 <= gamma E||grad F(w_j)||^2).  grad_out: HOST, |w| floats in the
+ * layout of the parameters.  Two passes over X in fp32 with fp64 sums over chunks of samples, through
+ * temporary device buffers (SSGD_ENOMEM if they do not fit).  Linear models with d % 4 == 0, else
+ * SSGD_EINVAL. */
+ssgd_status ssgd_full_gradient(ssgd_ctx *ctx, int32_t replica, float *grad_out);
+
 /* The mini-batch each worker of a K-async run has in flight (Sec. 2.2: a worker that is not
  * among the K selected keeps computing on the parameters it read): version read tau_i, ordinal,
  * absolute finish time f_i.  HOST arrays of P entries, each nullable.  SSGD_EINVAL for the

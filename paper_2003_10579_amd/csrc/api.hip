@@ -579,6 +579,27 @@ ssgd_status ssgd_full_loss(ssgd_ctx* c, int32_t replica, double* loss_out) {
     return SSGD_OK;
 }
 
+ssgd_status ssgd_full_gradient(ssgd_ctx* c, int32_t replica, float* grad_out) {
+    if (!c || !grad_out) return fail(c, SSGD_EINVAL, "null argument");
+    if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
+    if (c->broken) return fail(c, SSGD_ESTATE, "context is unusable after a device error");
+    const int C = c->model.kind == SSGD_LSQ ? 1 : c->model.classes;
+    if (c->model.kind == SSGD_MLP2 || !full_grad_supports(c->model.kind, c->model.d, C))
+        return fail(c, SSGD_EINVAL, "the full gradient is built for the linear models with d % 4 == 0");
+    HIP_OK(c, hipSetDevice(c->device));
+    DevBuf scratch, out;
+    hipError_t e = scratch.alloc(sizeof(float) * (size_t)full_grad_scratch_floats(c->model.N, c->model.d, C, nullptr));
+    if (e == hipSuccess) e = out.alloc(sizeof(float) * (size_t)c->nw);
+    if (e != hipSuccess) { scratch.release(); out.release(); return fail(c, SSGD_ENOMEM, "full gradient: device allocation failed"); }
+    e = launch_full_grad(c->model.kind, c->model.X, c->model.y, c->model.N, c->model.d, C,
+                         c->params.as<float>() + (int64_t)replica * c->nw, scratch.as<float>(), out.as<float>(), c->cu_count, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(grad_out, out.p, sizeof(float) * (size_t)c->nw, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    scratch.release(); out.release();
+    if (e != hipSuccess) return fail(c, SSGD_EDEVICE, std::string("full gradient: ") + hipGetErrorString(e));
+    return SSGD_OK;
+}
+
 ssgd_status ssgd_get_workers(ssgd_ctx* c, int32_t replica, int32_t* tau, int32_t* ord, double* finish) {
     if (!c) return fail(nullptr, SSGD_EINVAL, "null context");
     if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");

@@ -117,6 +117,11 @@ size_t linear_tile_lds_bytes(int C, int S);
 int linear_tile_resident_groups(size_t lds_bytes);
 hipError_t launch_linear_tile(const LinArgs& a, hipStream_t s);
 
+// Gradient of that objective (full_grad.hip): `scratch` holds full_grad_scratch_floats floats, `out` |w| floats (device).
+bool full_grad_supports(int kind, int d, int C);
+int64_t full_grad_scratch_floats(int64_t N, int d, int C, int* chunks_out);
+hipError_t launch_full_grad(int kind, const float* X, const void* y, int64_t N, int d, int C, const float* w,
+                            float* scratch, float* out, int cus, hipStream_t s);
 // Objective over the whole data set for one parameter vector of a linear model (full_loss.hip): partial sums of the
 // per-sample losses, one fp64 per workgroup.
 bool full_loss_supports(int kind, int d, int C);

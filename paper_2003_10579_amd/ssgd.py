@@ -21,6 +21,7 @@ EXPORTS = [
     "ssgd_create", "ssgd_run", "ssgd_reserve_trace", "ssgd_step", "ssgd_param_count", "ssgd_updates_done", "ssgd_current_K",
     "ssgd_trace_width", "ssgd_get_trace", "ssgd_get_params", "ssgd_set_params", "ssgd_force_K",
     "ssgd_get_workers", "ssgd_state_bytes", "ssgd_get_state", "ssgd_set_state", "ssgd_full_loss",
+    "ssgd_full_gradient",
     "ssgd_runtime_mc", "ssgd_debug_delays", "ssgd_debug_batch", "ssgd_stream_read_rate", "ssgd_last_error",
     "ssgd_last_kernel_ms",
     "ssgd_destroy",
@@ -87,6 +88,7 @@ def lib():
         L.ssgd_set_params.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.ssgd_force_K.argtypes = [C.c_void_p, C.c_int32]
         L.ssgd_full_loss.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]
+        L.ssgd_full_gradient.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.ssgd_get_workers.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ssgd_state_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         L.ssgd_get_state.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
@@ -197,6 +199,11 @@ class Context:
         v = C.c_double()
         _check(lib().ssgd_full_loss(self.h, replica, C.byref(v)), self.h)
         return v.value
+
+    def full_gradient(self, replica=0):
+        g = np.zeros(self.nw, dtype=np.float32)
+        _check(lib().ssgd_full_gradient(self.h, replica, g.ctypes.data), self.h)
+        return g
 
     def workers(self, replica=0):
         tau = np.zeros(self.P, dtype=np.int32)

@@ -820,6 +820,64 @@ def test_full_objective_of_the_two_layer_network(ssgd, oracle, torch_cuda, N, d,
     ctx.close(); other.close()
 
 
+@pytest.mark.parametrize("kind,N,d,classes", [
+    ("softmax", 1500, 320, 10), ("softmax", 1001, 132, 3), ("softmax", 37, 64, 16), ("lsq", 4096, 64, 1),
+    ("lsq", 777, 100, 1), ("softmax", 20000, 3072, 10),
+])
+def test_full_gradient_against_the_oracle(ssgd, oracle, torch_cuda, kind, N, d, classes):
+    """grad F of Eq. (1) at w = 0 and after some training, both replicas, against the oracle's fp64 gradient."""
+    torch = torch_cuda
+    if kind == "lsq":
+        X, y, _ = synth.lsq_data(N, d, 44)
+    else:
+        X, y = synth.mixture_data(N, d, classes, seed=44)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    ctx = ssgd.Context(kind, Xd, yd, 4, 2, 8, "k_sync", ssgd.delay_dist("exp", 1.0), 0.05 if kind == "softmax" else 0.01,
+                       seed=45, classes=classes, replicas=2)
+    M = oracle.Model(kind, X, y, classes=classes)
+    assert rel(ctx.full_gradient(0), M.full_grad(np.zeros(ctx.nw, dtype=np.float32))) <= 1e-5
+    ctx.run(25)
+    for r in (0, 1):
+        e = rel(ctx.full_gradient(r), M.full_grad(ctx.params(r)))
+        assert e <= 1e-5, (r, e)
+    assert not np.array_equal(ctx.full_gradient(0), ctx.full_gradient(1))
+    ctx.close()
+
+
+def test_staleness_gamma_estimate(ssgd, oracle, torch_cuda):
+    """gamma of Sec. 5.1 from the driver: zero for a synchronous variant (every gradient is fresh), positive and
+    growing with the staleness for K-async (K = 1 against K = P / 2 at P = 8), and equal to the same ratio formed
+    from the oracle's fp64 gradients at the iterates of the run."""
+    from paper_2003_10579_amd import staleness_gamma
+    torch = torch_cuda
+    X, y, _ = synth.lsq_data(1024, 132, 6)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    spec = ("exp", 1.0)
+    sync = staleness_gamma.gamma_estimate(ssgd, Xd, yd, 8, 4, 8, "k_sync", spec, 0.01, 40, 2, seed=3)
+    assert sync["gamma"] == 0.0 and sync["p0"] == 1.0
+    a1, params = staleness_gamma.gamma_estimate(ssgd, Xd, yd, 8, 1, 8, "k_async", spec, 0.01, 60, 2, seed=3, keep_params=True)
+    a4 = staleness_gamma.gamma_estimate(ssgd, Xd, yd, 8, 4, 8, "k_async", spec, 0.01, 60, 2, seed=3)
+    assert a1["gamma"] > a4["gamma"] > 0.0, (a1["gamma"], a4["gamma"])
+    assert a1["mean_staleness"] > a4["mean_staleness"] and a1["p0"] < a4["p0"]
+    # the same statistic from the oracle's gradients and the oracle's own schedule
+    M = oracle.Model("lsq", X, y)
+    gd, od = dist_pair(ssgd, oracle, spec)
+    num = den = 0.0
+    used = 0
+    for r in range(2):
+        tr = oracle.Trainer(M, 8, 1, 8, "k_async", od, 0.01, seed=3, replica=r)
+        tr.run(60)
+        st = tr.trace()["staleness"]
+        g = [M.full_grad(w) for w in params[r]]
+        for j in range(60):
+            den += float(g[j] @ g[j])
+            s = int(st[j, 0])
+            num += float((g[j] - g[j - s]) @ (g[j] - g[j - s]))
+            used += 1
+    want = (num / used) / (den / 120)
+    assert abs(a1["gamma"] - want) <= 1e-4 * want, (a1["gamma"], want)
+
+
 def test_error_runtime_frontier_orders_the_variants(ssgd, torch_cuda):
     """The four variants at the same K on the same problem (Sec. 3, Table 1): per update K-batch-async is the
     fastest and K-sync the slowest; the synchronous variants only use fresh gradients, the asynchronous ones do not;
