@@ -54,7 +54,7 @@ typedef enum {
     SSGD_K_ASYNC = 2,      /* Eq. (3): first K of P workers, nobody is cancelled, stale w */
     SSGD_K_BATCH_ASYNC = 3 /* first K mini-batches, nobody is cancelled: a worker that pushes re-reads the
                               current parameters and starts its next mini-batch at once.  Fixed K or
-                              AdaSync mode 1.  Linear models: 128 < d, d % 4 == 0, at most 15 classes,
+                              AdaSync mode 1.  Linear models: d % 4 == 0, at most 15 classes,
                               m <= 64, K <= 32 and P + K - 1 <= 64; MLP2: its usual limits, K <= 256;
                               else SSGD_EINVAL */
 } ssgd_variant;

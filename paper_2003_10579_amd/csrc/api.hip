@@ -364,8 +364,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         // the linear models run this variant through the steady-state kernel only
         const int32_t mp = (m + 3) / 4 * 4;
         const int32_t classes = model->kind == SSGD_LSQ ? 1 : model->classes;
-        if (model->kind != SSGD_MLP2 && (model->d <= 128 || model->d % 4 != 0 || classes > 15 || mp > 64 || Kcap > 32 || P + Kcap - 1 > 64))
-            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models need 128 < d, d % 4 == 0, at most 15 classes, m <= 64, "
+        if (model->kind != SSGD_MLP2 && (model->d % 4 != 0 || classes > 15 || mp > 64 || Kcap > 32 || P + Kcap - 1 > 64))
+            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models need d % 4 == 0, at most 15 classes, m <= 64, "
                                              "K <= 32, P + K - 1 <= 64");
     }
     if (model->kind == SSGD_LSQ) {
@@ -427,6 +427,7 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         const int d = model->d;
         c->nbw = d <= 64 ? 1 : (d <= 128 ? 2 : 4);
         if (const char* e = getenv("SSGD_NBW")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->nbw = v; }
+        if (variant == SSGD_K_BATCH_ASYNC) c->nbw = 4;   // only the steady-state kernel runs this variant: one wide slice for small d
         const int SL = 64 * c->nbw;
         c->G = (d + SL - 1) / SL;
         const bool async = variant == SSGD_K_ASYNC || variant == SSGD_K_BATCH_ASYNC;   // gradients are parked per worker
