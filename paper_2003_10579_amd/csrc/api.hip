@@ -40,6 +40,7 @@ struct ssgd_ctx {
     double lr = 0;
     uint64_t seed = 0;
     hipStream_t stream = nullptr;
+    hipStream_t side = nullptr;     // second stream for the schedule of the network's next piece (default priority)
     int device = 0;
     int64_t nw = 0;
     int32_t Kcap = 0, S = 0, G = 0, nbw = 0, maxrows = 0, table_ord = 1;
@@ -285,15 +286,50 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
         sa.tr = c->tr; sa.ws = c->ws; sa.dist = c->dist; sa.seed = c->seed; sa.P = c->P; sa.variant = c->variant;
         sa.table_ord = c->table_ord; sa.replica0 = 0; sa.j0 = c->j; sa.count = seg;
         sa.interval_t = (c->ada.mode >= 2) ? c->ada.interval_t : 0.0;
-        launch_schedule(sa, c->R, c->stream);
-        HIP_OK(c, hipGetLastError());
+        // The schedule does not depend on the numerics (K changes only between segments here), so for the network, whose
+        // updates are separate launches, it is written piece by piece on a second stream while the gradient kernels of
+        // the piece before run: a single wavefront beside kernels that fill the chip.
+        constexpr int64_t kPiece = 64;
+        const bool pipelined = c->model.kind == SSGD_MLP2 && c->ada.mode < 2 && seg > kPiece;
+        if (pipelined) {
+            if (!c->side) HIP_OK(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+            hipEvent_t before = nullptr;
+            HIP_OK(c, hipEventCreateWithFlags(&before, hipEventDisableTiming));
+            hipError_t e = hipEventRecord(before, c->stream);
+            if (e == hipSuccess) e = hipStreamWaitEvent(c->side, before, 0);
+            std::vector<hipEvent_t> written;
+            for (int64_t off = 0; off < seg && e == hipSuccess; off += kPiece) {
+                sa.j0 = c->j + off; sa.count = std::min(kPiece, seg - off);
+                launch_schedule(sa, c->R, c->side);
+                hipEvent_t ev = nullptr;
+                e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+                if (e == hipSuccess) { written.push_back(ev); e = hipEventRecord(ev, c->side); }
+            }
+            std::string msg;
+            size_t k = 0;
+            for (int64_t off = 0; off < seg && e == hipSuccess; off += kPiece, ++k) {
+                e = hipStreamWaitEvent(c->stream, written[k], 0);
+                if (e == hipSuccess)
+                    e = mlp_run_segment(c->mlp, c->tr, c->ws, c->j + off, std::min(kPiece, seg - off), agg_out, c->stream,
+                                        &c->last_ms, &c->last_launches, &msg);
+            }
+            if (e != hipSuccess) (void)hipStreamSynchronize(c->side);
+            (void)hipEventDestroy(before);
+            for (hipEvent_t ev : written) (void)hipEventDestroy(ev);
+            if (e != hipSuccess) { c->broken = true; return fail(c, SSGD_EDEVICE, "mlp segment: " + (msg.empty() ? std::string(hipGetErrorString(e)) : msg)); }
+        } else {
+            launch_schedule(sa, c->R, c->stream);
+            HIP_OK(c, hipGetLastError());
+        }
         if (c->ada.mode >= 2) {
             int64_t nd = 0;
             HIP_OK(c, hipMemcpyAsync(&nd, c->ws.n_done, sizeof(nd), hipMemcpyDeviceToHost, c->stream));
             HIP_OK(c, hipStreamSynchronize(c->stream));
             seg = nd;
         }
-        if (c->model.kind == SSGD_MLP2) {
+        if (pipelined) {
+            // done above
+        } else if (c->model.kind == SSGD_MLP2) {
             std::string msg;
             hipError_t e = mlp_run_segment(c->mlp, c->tr, c->ws, c->j, seg, agg_out, c->stream, &c->last_ms, &c->last_launches, &msg);
             if (e != hipSuccess) { c->broken = true; return fail(c, SSGD_EDEVICE, "mlp segment: " + msg); }
@@ -834,6 +870,7 @@ void ssgd_destroy(ssgd_ctx* c) {
             }
     }
     if (c->mlp) mlp_destroy(c->mlp);
+    if (c->side) (void)hipStreamDestroy(c->side);
     DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,
                       &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx, &c->ws_F0,
                       &c->ws_intstart, &c->ws_crossed, &c->ws_ndone, &c->params, &c->park, &c->park_small, &c->zpart, &c->zx,

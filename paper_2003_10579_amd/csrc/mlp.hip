@@ -66,8 +66,10 @@ struct MlpArgs {
     float* loss;               // [S]          sum of the sample losses
     int32_t* ylab;             // [S][MP]      labels (-1: no sample)
     float* agg_out;            // nullable
-    float* dw_part;            // [nsplit][H][d] partial first-layer gradient sums when the slots are split over workgroups
+    float* dw_part;            // [nsplit][H][d] partial first-layer gradient sums when the slots are split over workgroups;
+                               // also [fsplit][nrec][MP][H] partial hidden-layer sums when the depth of the forward pass is split
     int32_t nsplit;
+    int32_t fsplit;            // shares of the depth d in the forward contraction of few records
     int64_t eval_base;         // >= 0: objective evaluation; record r holds data rows eval_base + 64 r .. + 63 in slot r
     int32_t* plan;             // K-batch-async: slot bookkeeping and the lists of the current update (layout: PlanView)
     int32_t S;                 // slots
@@ -201,8 +203,10 @@ __global__ __launch_bounds__(256) void mlp_gather_kernel(MlpArgs a) {
 // BWD: rows = hidden units, columns = input features, depth = 64 samples of every consumed slot.
 // BT x BT output tile per workgroup (128: four waves of 64 x 64; 64: four waves of 32 x 32, for launches
 // that would otherwise leave most CUs idle).
-// SPLIT (gradient contraction only): blockIdx.z takes a share of the consumed slots and leaves its partial sum in
-// dw_part; mlp_w1_update_kernel adds the shares in order and applies the update.
+// SPLIT: blockIdx.z takes a share of the depth and leaves its partial sum in dw_part.  Gradient contraction: shares of
+// the consumed slots, mlp_w1_update_kernel adds them in order and applies the update.  Forward pass of few records
+// (a launch of a few dozen workgroups that each walk the whole depth d is bound by the latency of its loads): shares
+// of d, mlp_fwd_finish_kernel adds them in order, then bias and ReLU.
 template <bool FWD, int BT, bool SPLIT = false>
 __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     constexpr int WT = BT / 2;          // rows and columns per wave
@@ -216,9 +220,10 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     const int d = a.d, H = a.H;
     int stage0 = 0, stages = FWD ? d / KT : a.Kv;
     if constexpr (SPLIT) {
-        const int per = (a.Kv + a.nsplit - 1) / a.nsplit;
+        const int total = FWD ? d / KT : a.Kv, shares = FWD ? a.fsplit : a.nsplit;
+        const int per = (total + shares - 1) / shares;
         stage0 = blockIdx.z * per;
-        stages = max(0, min(per, a.Kv - stage0));
+        stages = max(0, min(per, total - stage0));
     }
 
     // global -> LDS: BT rows x 8 chunks of 16 bytes per operand; thread -> chunk tid % 8 of rows tid / 8 + 32 i
@@ -317,7 +322,11 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     for (int q = tid; q < BT * C4; q += 256) {
         const int row = q / C4, c4 = q % C4;
         const f32x4 v = *reinterpret_cast<const f32x4*>(Cs + row * LDC + 4 * c4);
-        if (FWD) {
+        if (FWD && SPLIT) {
+            const int r = RPT * bm + row / MP;
+            if (r < a.nrec)
+                *reinterpret_cast<f32x4*>(a.dw_part + (((int64_t)blockIdx.z * a.nrec + r) * MP + (row % MP)) * H + bn * BT + 4 * c4) = v;
+        } else if (FWD) {
             const int r = RPT * bm + row / MP;
             if (r < a.nrec) {
                 const int n = bn * BT + 4 * c4;
@@ -343,6 +352,26 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     }
 }
 
+// ---- hidden activations from the partial sums of a split forward pass: shares added in order, bias, ReLU --------
+__global__ __launch_bounds__(256) void mlp_fwd_finish_kernel(MlpArgs a) {
+    const int H = a.H, h4 = H / 4;
+    const int64_t total = (int64_t)a.nrec * MP * h4;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (int64_t)gridDim.x * blockDim.x) {
+        const int n = 4 * (int)(q % h4);
+        const int64_t rr = q / h4;                      // record * MP + row
+        const int r = (int)(rr / MP), row = (int)(rr % MP);
+        int worker, ordinal, slot;
+        record_of(a, r, worker, ordinal, slot);
+        f32x4 v = *reinterpret_cast<const f32x4*>(a.dw_part + rr * H + n);
+        for (int z = 1; z < a.fsplit; ++z) v += *reinterpret_cast<const f32x4*>(a.dw_part + ((int64_t)z * a.nrec * MP + rr) * H + n);
+        const f32x4 b1 = *reinterpret_cast<const f32x4*>(a.params + (int64_t)H * a.d + n);
+        f32x4 h;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { const float zc = v[c] + b1[c]; h[c] = zc > 0.0f ? zc : 0.0f; }
+        *reinterpret_cast<f32x4*>(a.hbuf + ((int64_t)slot * MP + row) * H + n) = h;
+    }
+}
+
 // ---- first-layer update from the partial sums of a split gradient contraction: shares added in order --------
 __global__ __launch_bounds__(256) void mlp_w1_update_kernel(MlpArgs a) {
     const int64_t n4 = (int64_t)a.H * a.d / 4;
@@ -364,6 +393,9 @@ __global__ __launch_bounds__(256) void mlp_w1_update_kernel(MlpArgs a) {
 // ---- layer 2 and softmax: one workgroup per record; wave w takes rows 16 w .. 16 w + 15 -------------
 // Z2 = H W2^T is a 16 x 16 x H contraction per wave on the fp32 MFMA units (H is not rounded, so this
 // layer runs in fp32): operand lane -> (row or class lane % 16, 4 hidden units starting at 16 kk + 4 (lane / 16)).
+// With one workgroup per record the kernel is a chain of load latencies: what the epilogue needs from memory is
+// asked for first, and eight 16-unit blocks of h and W2 are in flight at a time.  (Staging W2 in LDS, or sixteen
+// waves per record with the hidden units split four ways, did not shorten it.)
 __global__ __launch_bounds__(256) void mlp_output_kernel(MlpArgs a) {
     __shared__ float wsum[4];
     const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -373,22 +405,33 @@ __global__ __launch_bounds__(256) void mlp_output_kernel(MlpArgs a) {
     const int cls = lane & 15, kq = lane >> 4;
     const float* hp = a.hbuf + ((int64_t)slot * MP + 16 * wave + (lane & 15)) * H + 4 * kq;
     const float* wp = a.w2r + (int64_t)min(cls, C - 1) * H + 4 * kq;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int kk = 0; kk < H / 16; ++kk) {
-        const f32x4 hv = *reinterpret_cast<const f32x4*>(hp + 16 * kk);
-        const f32x4 wv = *reinterpret_cast<const f32x4*>(wp + 16 * kk);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv.x, wv.x, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv.y, wv.y, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv.z, wv.z, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv.w, wv.w, acc, 0, 0, 0);
-    }
-    // result: lane holds class lane % 16 of rows 4 (lane / 16) + e, e < 4 (classes past C repeat class C-1: unused)
     const float b2 = a.params[(int64_t)H * a.d + H + (int64_t)C * H + min(cls, C - 1)];
+    int labs[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) labs[e] = a.ylab[slot * MP + 16 * wave + 4 * kq + e];
+    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < H / 16; k0 += 8) {        // H is a multiple of 128
+        f32x4 hv[8], wv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            hv[u] = *reinterpret_cast<const f32x4*>(hp + 16 * (k0 + u));
+            wv[u] = *reinterpret_cast<const f32x4*>(wp + 16 * (k0 + u));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[u].x, wv[u].x, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[u].y, wv[u].y, acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[u].z, wv[u].z, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[u].w, wv[u].w, acc1, 0, 0, 0);
+        }
+    }
+    const f32x4 acc = acc0 + acc1;
+    // result: lane holds class lane % 16 of rows 4 (lane / 16) + e, e < 4 (classes past C repeat class C-1: unused)
     float lsum = 0.0f;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const int s = 16 * wave + 4 * kq + e;
-        const int lab = a.ylab[slot * MP + s];
+        const int lab = labs[e];
         const bool ok = s < m && lab >= 0;
         const float z = acc[e] + b2;
         float zmax = cls < C ? z : -3.0e38f;
@@ -616,7 +659,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     a.xb = (unsigned short*)s->xb.p; a.xbt = (unsigned short*)s->xbt.p; a.hbuf = (float*)s->hbuf.p;
     a.d1t = (unsigned short*)s->d1t.p; a.gb1 = (float*)s->gb1.p; a.gw2 = (float*)s->gw2.p; a.gb2 = (float*)s->gb2.p;
     a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p; a.d2 = (float*)s->d2.p;
-    a.dw_part = (float*)s->dw_part.p; a.nsplit = 1; a.eval_base = -1;
+    a.dw_part = (float*)s->dw_part.p; a.nsplit = 1; a.fsplit = 1; a.eval_base = -1;
     const float bound1 = (float)(1.0 / sqrt((double)a.d)), bound2 = (float)(1.0 / sqrt((double)a.H));
     hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
     TRY(hipGetLastError());
@@ -624,6 +667,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 128, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 64, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
 #undef TRY
     *out = s;
     return hipSuccess;
@@ -662,10 +706,17 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
         if (a.nrec > 0) {
             hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
             // small tiles while the large ones would not fill the chip
-            if (((a.nrec + 1) / 2) * (a.H / 128) >= 192)
+            const int wgs64 = a.nrec * (a.H / 64);
+            if (((a.nrec + 1) / 2) * (a.H / 128) >= 192) {
                 hipLaunchKernelGGL((mlp_contract_kernel<true, 128>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
-            else
+            } else if (wgs64 <= 128 && (int64_t)a.nrec * MP * a.H * 4 <= (int64_t)kMaxSplit * a.H * a.d) {
+                // few records: the depth is split so that the chip is full and no workgroup walks all of d
+                a.fsplit = std::max(2, std::min(4, 512 / wgs64));
+                hipLaunchKernelGGL((mlp_contract_kernel<true, 64, true>), dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), contract_lds(64), stream, a);
+                hipLaunchKernelGGL(mlp_fwd_finish_kernel, dim3(std::min(1024, (a.nrec * MP * (a.H / 4) + 255) / 256)), dim3(256), 0, stream, a);
+            } else {
                 hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
+            }
             hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
             hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
         }
