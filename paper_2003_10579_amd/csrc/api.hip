@@ -400,9 +400,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         // the linear models run this variant through the steady-state kernel only
         const int32_t mp = (m + 3) / 4 * 4;
         const int32_t classes = model->kind == SSGD_LSQ ? 1 : model->classes;
-        if (model->kind != SSGD_MLP2 && (model->d % 4 != 0 || classes > 15 || mp > 64 || Kcap > 32 || P + Kcap - 1 > 64))
-            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models need d % 4 == 0, at most 15 classes, m <= 64, "
-                                             "K <= 32, P + K - 1 <= 64");
+        if (model->kind != SSGD_MLP2 && (model->d % 4 != 0 || classes > 15 || mp > 64 || Kcap > 32))
+            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models need d % 4 == 0, at most 15 classes, m <= 64, K <= 32");
     }
     if (model->kind == SSGD_LSQ) {
         if (model->bf16) return fail(nullptr, SSGD_EINVAL, "bf16 is for the MLP only");
@@ -471,6 +470,11 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         const int C = model->kind == SSGD_LSQ ? 1 : model->classes;
         c->maxrows = 64 * chunks_for(async ? std::max(P, Kcap) : Kcap, c->mp);
         c->lds_bytes = linear_lds_bytes(c->nbw, C, c->S, async);
+        if (variant == SSGD_K_BATCH_ASYNC) {
+            // the general kernel is never used for this variant; what has to fit is the steady-state kernel's LDS
+            if (linear_tile_lds_bytes(C, c->S) > 160 * 1024) return bail(SSGD_EINVAL, "too many gradient slots for the LDS of one workgroup");
+            c->lds_bytes = std::min<size_t>(c->lds_bytes, 160 * 1024);
+        }
         if (c->lds_bytes > 160 * 1024) return bail(SSGD_EINVAL, "too many gradient slots for the LDS of one workgroup");
         c->resident_groups = linear_max_resident_groups(c->nbw, c->lds_bytes);
         if (c->resident_groups < c->G) return bail(SSGD_EINVAL, "d is too large for a co-resident cluster of workgroups");

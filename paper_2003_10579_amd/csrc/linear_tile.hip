@@ -183,7 +183,12 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         };
         // The lists of version `ver` (in flight in q_*) become the description of its tiles.
         int h_worker = -1, h_ord = 0, h_nrec = 0, h_tiles = 1;
-        int h_recword = 0, h_nstale = 0;         // K-batch-async: all records of the version, tile by tile below
+        // K-batch-async: the records of a version are described piecewise (version 0 has P + K - 1 of them):
+        // the first `h_first` start a worker's mini-batch 0 (version 0: worker = record index; later: the worker whose
+        // push triggered the update before), record h_first + j is the restart after push j of this update (lane j)
+        int h_first = 0, h_trig = 0, h_trig_fresh = 0, h_nstale = 0;
+        int h_rw = 0, h_ro = 0, h_rf = 0;        // lane j: worker, ordinal, consumed-by-this-update flag of restart j
+        int h_csel = -1, h_ctau = -1, h_cord = 0;   // lane l: entry l of the consume list of the version
         const int rpt = ROWS / mp;               // K-batch-async: whole records per tile
         auto take_lists = [&](int64_t ver, bool more) {
             const int l_sel = q_sel, l_tau = q_tau, l_ord = q_ord;
@@ -199,19 +204,21 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 // Mini-batches that start at version ver: at ver = 0 every worker's first one, later the one of the
                 // worker whose push triggered update ver - 1; then, for each of the first K - 1 pushes of update ver,
                 // the next mini-batch of the pushing worker (ordinal: how many it has started at this version).
-                // Record r sits in lane r.
                 const int Kprev = __popcll(__ballot(cur_sel >= 0));
-                const int first = (ver == 0) ? a.P : 1;
-                nrec = first + K - 1;
-                const int l = min(max(lane - first, 0), 63);
-                const int p_sel = __shfl(l_sel, l, 64), p_tau = __shfl(l_tau, l, 64), p_ord = __shfl(l_ord, l, 64);
-                const int trigger = (ver == 0) ? lane : __builtin_amdgcn_readlane(cur_sel, max(Kprev - 1, 0));
-                rec_slot = (lane < first) ? trigger : p_sel;
-                rec_ord = (lane < first) ? 0 : ((p_tau == (int32_t)ver) ? p_ord + 1 : 0);
-                fr = 0;     // consumed by update ver itself?
-                for (int q = 0; q < K; ++q)
-                    if (__builtin_amdgcn_readlane(l_sel, q) == rec_slot && __builtin_amdgcn_readlane(l_tau, q) == (int32_t)ver &&
-                        __builtin_amdgcn_readlane(l_ord, q) == rec_ord) fr = 1;
+                h_first = (ver == 0) ? a.P : 1;
+                nrec = h_first + K - 1;
+                h_trig = (ver == 0) ? 0 : __builtin_amdgcn_readlane(cur_sel, max(Kprev - 1, 0));
+                h_rw = l_sel;
+                h_ro = (l_tau == (int32_t)ver) ? l_ord + 1 : 0;
+                h_rf = 0;          // is restart `lane` consumed by update ver itself?  and the trigger's mini-batch?
+                h_trig_fresh = 0;
+                for (int q = 0; q < K; ++q) {
+                    const int cs = __builtin_amdgcn_readlane(l_sel, q), ct = __builtin_amdgcn_readlane(l_tau, q),
+                              co = __builtin_amdgcn_readlane(l_ord, q);
+                    if (ct == (int32_t)ver && cs == h_rw && co == h_ro) h_rf = 1;
+                    if (ct == (int32_t)ver && cs == h_trig && co == 0) h_trig_fresh = 1;
+                }
+                h_csel = l_sel; h_ctau = l_tau; h_cord = l_ord;
             }
             n_K = K;
             // parked gradients that update ver consumes: entries whose version is older, compacted
@@ -226,35 +233,57 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 n_rec_word = (lane == 0) ? (1 << 16) : 0;
             } else {
                 n_nrec = nrec;
-                n_rec_word = (lane < nrec) ? (rec_slot | (fr << 16)) : 0;
+                n_rec_word = (lane < nrec) ? (rec_slot | (fr << 16)) : 0;      // K-batch-async: set per tile below
             }
-            h_worker = BATCH ? rec_slot : (async ? cur_sel : l_sel);      // lane r: worker of record r
+            h_worker = async ? cur_sel : l_sel;      // lane r: worker of record r (not K-batch-async)
             h_ord = rec_ord;
             h_nrec = nrec;
             h_tiles = chunked ? max(1, (nrec * mp + ROWS - 1) / ROWS) : 1;
             if constexpr (BATCH) {
-                h_recword = n_rec_word;
                 h_nstale = n_nstale;
                 h_tiles = max(1, (nrec + rpt - 1) / rpt);
             }
             cur_sel = l_sel;
             asm volatile("" : "+v"(n_stale), "+v"(n_stale_pos), "+v"(n_rec_word), "+v"(cur_sel), "+v"(h_worker), "+v"(h_ord) : : "memory");
+            if constexpr (BATCH) asm volatile("" : "+v"(h_rw), "+v"(h_ro), "+v"(h_rf), "+v"(h_csel), "+v"(h_ctau), "+v"(h_cord) : : "memory");
             if (more) issue_lists(ver + 1);
         };
         // Tile `t` of version `ver`: sample ids and labels; leaves the gathers in flight.
         auto make_tile = [&](int64_t ver, int t) {
             int rec = r_of, smp = s_of;
             if (chunked) { const int q = t * ROWS + lane; rec = q / mp; smp = q - rec * mp; }
+            int worker, ordinal;
             if constexpr (BATCH) {
                 // records t * rpt .. of the version; the parked part of the update comes with the first tile
-                rec = (r_of < rpt) ? t * rpt + r_of : 64;
+                rec = (r_of < rpt) ? t * rpt + r_of : 0x7FFFFFF;
                 n_nrec = min(rpt, h_nrec - t * rpt);
-                n_rec_word = __shfl(h_recword, min(t * rpt + lane, 63), 64);
-                if (lane >= n_nrec) n_rec_word = 0;
                 n_nstale = (t == 0) ? h_nstale : 0;
+                // worker, ordinal and consumed-by-this-update flag of record q
+                auto describe = [&](int q, int& w, int& o, int& f) {
+                    const int j = min(max(q - h_first, 0), 63);
+                    const int rw = __shfl(h_rw, j, 64), ro = __shfl(h_ro, j, 64), rf = __shfl(h_rf, j, 64);
+                    if (q >= h_first) { w = rw; o = ro; f = rf; }
+                    else if (ver != 0) { w = h_trig; o = 0; f = h_trig_fresh; }
+                    else { w = q; o = 0; f = -1; }          // version 0: looked up below
+                };
+                int fr;
+                describe(rec, worker, ordinal, fr);
+                int qw, qo, qf;
+                describe(t * rpt + lane, qw, qo, qf);
+                if (ver == 0) {
+                    // every worker's first mini-batch: consumed by update 0 if the list holds (worker, version 0, ordinal 0)
+                    const int Kv = n_K;
+                    int hit = 0;
+                    for (int e = 0; e < Kv; ++e)
+                        if (__builtin_amdgcn_readlane(h_csel, e) == qw && __builtin_amdgcn_readlane(h_ctau, e) == 0 &&
+                            __builtin_amdgcn_readlane(h_cord, e) == 0) hit = 1;
+                    if (qf < 0) qf = hit;
+                }
+                n_rec_word = (lane < n_nrec) ? (qw | (qf << 16)) : 0;
+            } else {
+                worker = __shfl(h_worker, min(rec, 63), 64);
+                ordinal = __shfl(h_ord, min(rec, 63), 64);
             }
-            const int worker = __shfl(h_worker, min(rec, 63), 64);
-            const int ordinal = __shfl(h_ord, min(rec, 63), 64);
             row_id = kNoRow;
             row_lab = 0.0f;
             if (smp < m && rec < h_nrec) {
@@ -950,8 +979,8 @@ bool linear_tile_supports(const LinArgs& a, int max_records) {
     if (a.chunked && a.variant == kAsync) return false;
     if ((uint64_t)a.N * (uint64_t)a.d * 4u >= (1ull << 32)) return false;   // one buffer descriptor spans the sample matrix
     if (a.variant == kBatchAsync) {
-        // whole records per tile, every record of a version in one lane each (version 0: P + K - 1 of them)
-        if (a.mp > ROWS || a.P + a.tr.Kcap - 1 > 64) return false;
+        // whole records per tile; the consume list and the restarts of an update sit in one lane each
+        if (a.mp > ROWS) return false;
         return linear_tile_lds_bytes(a.C, a.S) <= 160 * 1024;
     }
     if (a.agg_out != nullptr) return false;

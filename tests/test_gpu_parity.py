@@ -719,6 +719,9 @@ def test_mlp_snapshot_resume(ssgd, oracle, torch_cuda, variant, K):
     ("softmax", 12, 3, 64, 516, 15, ("exp", 2.5)),                # one record per tile: 14 tiles at version 0
     ("lsq", 4, 2, 16, 64, 1, ("exp", 1.0)),                       # config 0's shape: a single, mostly empty slice
     ("softmax", 6, 3, 8, 20, 4, ("shifted_exp", 0.5, 1.0)),       # d = 20
+    ("softmax", 64, 16, 32, 320, 10, ("pareto", 2.5, 1.0)),       # config 2's workers and K: 79 records at version 0
+    ("lsq", 200, 3, 8, 64, 1, ("exp", 1.0)),                      # 202 records at version 0, 8 per tile
+    ("softmax", 130, 32, 64, 260, 3, ("exp", 1.0)),               # one record per tile, 161 tiles at version 0, K = 32
 ])
 def test_kbatch_async_parity(ssgd, oracle, torch_cuda, kind, P, K, m, d, classes, spec):
     """K-batch-async (Sec. 2.2): delays, selections, ordinals and staleness bit for bit, per-update averaged gradients
@@ -762,8 +765,8 @@ def test_kbatch_async_unsupported_shapes_are_refused(ssgd, torch_cuda):
     torch = torch_cuda
     X, y, _ = synth.lsq_data(64, 66, 1)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
-    for P, K, m, cols in ((4, 2, 8, 66), (4, 2, 100, 64), (64, 2, 8, 64), (8, 33, 8, 64)):
-        # d % 4 != 0; m > 64; P + K - 1 > 64; K > 32
+    for P, K, m, cols in ((4, 2, 8, 66), (4, 2, 100, 64), (8, 33, 8, 64)):
+        # d % 4 != 0; m > 64; K > 32
         Xc = Xd[:, :cols].contiguous()
         with pytest.raises(ssgd.SsgdError):
             ssgd.Context("lsq", Xc, yd, P, K, m, "k_batch_async", ssgd.delay_dist("exp", 1.0), 0.01)
