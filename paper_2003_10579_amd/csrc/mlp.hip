@@ -218,6 +218,13 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bm = blockIdx.x, bn = blockIdx.y;
     const int d = a.d, H = a.H;
+    // gradient contraction: the slots of the consumed gradients are read once, not once per stage in front of the
+    // operand loads that depend on them
+    __shared__ int slot_list[FWD ? 1 : 256];
+    if constexpr (!FWD) {
+        for (int l = tid; l < a.Kv; l += 256) slot_list[l] = consumed_slot(a, l);
+        __syncthreads();
+    }
     int stage0 = 0, stages = FWD ? d / KT : a.Kv;
     if constexpr (SPLIT) {
         const int total = FWD ? d / KT : a.Kv, shares = FWD ? a.fsplit : a.nsplit;
@@ -241,11 +248,11 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     }
     auto a_ptr = [&](int row, int stage) -> const unsigned short* {
         if (FWD) return a.xb + ((int64_t)slot_of[row / MP] * MP + (row % MP)) * d + stage * KT;
-        return a.d1t + ((int64_t)consumed_slot(a, stage) * H + bm * BT + row) * MP;
+        return a.d1t + ((int64_t)slot_list[FWD ? 0 : stage] * H + bm * BT + row) * MP;
     };
     auto b_ptr = [&](int row, int stage) -> const unsigned short* {
         if (FWD) return a.w1r + (int64_t)(bn * BT + row) * d + stage * KT;
-        return a.xbt + ((int64_t)consumed_slot(a, stage) * d + bn * BT + row) * MP;
+        return a.xbt + ((int64_t)slot_list[FWD ? 0 : stage] * d + bn * BT + row) * MP;
     };
     u16x8 ra[LP], rb[LP];
     auto fetch = [&](int stage) {
