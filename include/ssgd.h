@@ -160,7 +160,7 @@ ssgd_status ssgd_force_K(ssgd_ctx *ctx, int32_t K);
 ssgd_status ssgd_full_loss(ssgd_ctx *ctx, int32_t replica, double *loss_out);
 
 /* The gradient of that objective, grad F(w) = (1/N) sum_n grad f(w, xi_n), at the replica's current
- * parameters: the quantity in which the staleness bound of Sec. 5.1 is stated
+ * parameters: the quantity in which the staleness bound (fifth assumption of Sec. 4.1) is stated
  * (E||grad F(w_j) - grad F(w_tau)||^2 <= gamma E||grad F(w_j)||^2).  grad_out: HOST, |w| floats in the
  * layout of the parameters.  Two passes over X in fp32 with fp64 sums over chunks of samples, through
  * temporary device buffers (SSGD_ENOMEM if they do not fit).  Linear models with d % 4 == 0, else
@@ -179,9 +179,11 @@ ssgd_status ssgd_get_workers(ssgd_ctx *ctx, int32_t replica, int32_t *tau, int32
  * mini-batches in flight, which were taken at parameters that no longer exist.  It is an opaque
  * HOST buffer of ssgd_state_bytes() bytes (the size grows with the trace); ssgd_set_state accepts
  * it only on a context created with the same model shape, P, m, variant, replicas, seed and
- * AdaSync mode (else SSGD_EINVAL, context unchanged), replaces that context's state and trace,
- * and the updates that follow are those the original context would have run.  The data set is
- * not part of the snapshot. */
+ * AdaSync mode and only if its size fits the number of updates its header states (else
+ * SSGD_EINVAL, context unchanged), replaces that context's state and trace, and the updates that
+ * follow are those the original context would have run.  A device error while the state is
+ * copied leaves the context unusable (SSGD_ESTATE from then on).  The data set is not part of
+ * the snapshot. */
 ssgd_status ssgd_state_bytes(ssgd_ctx *ctx, int64_t *bytes);
 ssgd_status ssgd_get_state(ssgd_ctx *ctx, void *host_buf, int64_t bytes);
 ssgd_status ssgd_set_state(ssgd_ctx *ctx, const void *host_buf, int64_t bytes);

@@ -379,7 +379,7 @@ double orc_full_loss(const orc_model *M, const float *w)
 }
 
 /* Gradient of the full-data objective, grad F(w) = (1/N) sum_n grad f(w, xi_n)
- * (Eq. (1); the quantity the staleness bound of Sec. 5.1 is stated in), fp64:
+ * (Eq. (1); the quantity the staleness bound, the fifth assumption of Sec. 4.1, is stated in), fp64:
  * the mini-batch gradients of consecutive blocks, weighted by their sizes. */
 void orc_full_grad(const orc_model *M, const float *w, double *grad_out)
 {

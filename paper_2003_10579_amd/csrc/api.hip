@@ -156,6 +156,8 @@ ssgd_status grow_trace(ssgd_ctx* c, int64_t need) {
     int64_t cap = std::max<int64_t>(need, std::max<int64_t>(256, 2 * c->tr.cap));
     const int64_t R = c->R, W = c->Kcap, old = c->tr.cap, used = c->j;
     DevBuf nt, nl, nk, ns, na, no;
+    // the new arrays are released again if an allocation or a copy fails: the old trace stays in place
+    struct Temps { DevBuf* b[6]; bool keep = false; ~Temps() { if (!keep) for (DevBuf* q : b) q->release(); } } temps{{&nt, &nl, &nk, &ns, &na, &no}};
     HIP_OK(c, nt.alloc(sizeof(double) * R * cap));
     HIP_OK(c, nl.alloc(sizeof(float) * R * cap));
     HIP_OK(c, nk.alloc(sizeof(int32_t) * R * cap));
@@ -173,6 +175,7 @@ ssgd_status grow_trace(ssgd_ctx* c, int64_t need) {
             HIP_OK(c, hipMemcpy(no.as<int32_t>() + r * cap * W, c->tr.ord + r * old * W, sizeof(int32_t) * used * W, hipMemcpyDeviceToDevice));
         }
     }
+    temps.keep = true;
     c->tr_t.release(); c->tr_loss.release(); c->tr_K.release(); c->tr_sel.release(); c->tr_tau.release(); c->tr_ord.release();
     c->tr_t = nt; c->tr_loss = nl; c->tr_K = nk; c->tr_sel = ns; c->tr_tau = na; c->tr_ord = no;
     c->tr.t = nt.as<double>(); c->tr.loss = nl.as<float>(); c->tr.K = nk.as<int32_t>();
@@ -408,8 +411,10 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
     } else if (model->kind == SSGD_SOFTMAX) {
         if (model->classes < 2 || model->classes > kClassPad || model->bf16) return fail(nullptr, SSGD_EINVAL, "softmax needs 2..16 classes, bf16 = 0");
     } else if (model->kind == SSGD_MLP2) {
-        if (model->classes < 2 || model->classes > kClassPad || model->hidden < 64 || model->hidden % 64 || model->d % 32 || replicas != 1)
-            return fail(nullptr, SSGD_EINVAL, "MLP needs 2..16 classes, hidden % 64 == 0, d % 32 == 0, replicas == 1");
+        // the same limits as mlp_create, so that every invalid shape is refused here, before anything is allocated
+        if (model->classes < 2 || model->classes > kClassPad || model->hidden < 128 || model->hidden % 128 || model->d % 128 ||
+            replicas != 1 || !model->bf16 || m > 64)
+            return fail(nullptr, SSGD_EINVAL, "MLP needs 2..16 classes, hidden % 128 == 0, d % 128 == 0, m <= 64, bf16 = 1, replicas == 1");
     } else {
         return fail(nullptr, SSGD_EINVAL, "unknown model kind");
     }
@@ -457,7 +462,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
     if (model->kind == SSGD_MLP2) {
         std::string msg;
         hipError_t e = mlp_create(&c->mlp, *model, P, m, variant, Kcap, lr, seed, c->stream, &msg);
-        if (e != hipSuccess) return bail(e == hipErrorOutOfMemory ? SSGD_ENOMEM : SSGD_EDEVICE, "mlp_create: " + msg);
+        if (e != hipSuccess)
+            return bail(e == hipErrorOutOfMemory ? SSGD_ENOMEM : (e == hipErrorInvalidValue ? SSGD_EINVAL : SSGD_EDEVICE), "mlp_create: " + msg);
     } else {
         const int d = model->d;
         c->nbw = d <= 64 ? 1 : (d <= 128 ? 2 : 4);
@@ -742,15 +748,22 @@ ssgd_status ssgd_set_state(ssgd_ctx* c, const void* host_buf, int64_t bytes) {
         h.m != mine.m || h.variant != mine.variant || h.R != mine.R || h.Kcap != mine.Kcap || h.S != mine.S || h.G != mine.G ||
         h.ada_mode != mine.ada_mode || h.N != mine.N || h.nw != mine.nw || h.seed != mine.seed || h.mlp_bytes != mine.mlp_bytes)
         return fail(c, SSGD_EINVAL, "the snapshot was taken from a context of another configuration");
-    if (h.j < 0 || h.total_bytes > bytes) return fail(c, SSGD_EINVAL, "truncated state snapshot");
+    // Everything the header claims is checked against this context before the context is touched: the number of
+    // updates must be one whose trace fits the buffer handed in, and the total must be what this configuration
+    // writes for that many updates.
+    const int64_t per_update = trace_bytes(c, 1);
+    int64_t fixed = (int64_t)sizeof(StateHeader) + h.mlp_bytes;
+    for (DevBuf* b : state_buffers(c)) fixed += (int64_t)b->bytes;
+    if (h.j < 0 || h.total_bytes > bytes || h.total_bytes < fixed || (h.total_bytes - fixed) / per_update < h.j ||
+        fixed + trace_bytes(c, h.j) != h.total_bytes)
+        return fail(c, SSGD_EINVAL, "truncated or malformed state snapshot");
     HIP_OK(c, hipSetDevice(c->device));
     HIP_OK(c, hipStreamSynchronize(c->stream));
-    c->j = 0;     // nothing of the old trace is kept
-    ssgd_status st = grow_trace(c, h.j);
+    // room for the snapshot's trace; the updates done so far stay valid until the copies below begin
+    ssgd_status st = grow_trace(c, std::max(h.j, c->j));
     if (st != SSGD_OK) return st;
-    int64_t expect = (int64_t)sizeof(StateHeader) + trace_bytes(c, h.j) + h.mlp_bytes;
-    for (DevBuf* b : state_buffers(c)) expect += (int64_t)b->bytes;
-    if (expect != h.total_bytes) return fail(c, SSGD_EINVAL, "state snapshot of unexpected size");
+    // from here on a failed copy leaves a mixture of two runs behind: the context is marked unusable
+    struct Guard { ssgd_ctx* c; bool ok = false; ~Guard() { if (!ok) c->broken = true; } } guard{c};
     const unsigned char* in = static_cast<const unsigned char*>(host_buf);
     size_t off = sizeof(h);
     const int64_t j = h.j, W = c->Kcap, cap = c->tr.cap;
@@ -769,6 +782,7 @@ ssgd_status ssgd_set_state(ssgd_ctx* c, const void* host_buf, int64_t bytes) {
     if (c->mlp) HIP_OK(c, mlp_set_state(c->mlp, in + off));
     c->j = h.j;
     c->win_cnt = h.win_cnt;
+    guard.ok = true;
     return SSGD_OK;
 }
 

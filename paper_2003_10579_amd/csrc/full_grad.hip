@@ -1,5 +1,5 @@
 // Gradient of the objective over the whole data set, grad F(w) = (1/N) sum_n grad f(w, xi_n) (Eq. (1)), for the
-// linear models: the quantity in which the staleness bound of Sec. 5.1 is stated
+// linear models: the quantity in which the staleness bound (fifth assumption of Sec. 4.1) is stated
 // (E||grad F(w_j) - grad F(w_tau)||^2 <= gamma E||grad F(w_j)||^2).  Two streaming passes over the sample matrix:
 //   1. delta[n][c] = softmax(W x_n + b)_c - [y_n = c]  (least squares: x_n . w - y_n), 16 floats per sample;
 //   2. G[c][col] = sum_n delta[n][c] X[n][col], a thread per column (the bias is one more column of ones), the

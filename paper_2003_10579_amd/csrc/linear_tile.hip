@@ -983,7 +983,6 @@ bool linear_tile_supports(const LinArgs& a, int max_records) {
         if (a.mp > ROWS) return false;
         return linear_tile_lds_bytes(a.C, a.S) <= 160 * 1024;
     }
-    if (a.agg_out != nullptr) return false;
     if (a.variant == kAsync && a.v0 < 1) return false;    // step 0 of K-async starts all P workers
     return linear_tile_lds_bytes(a.C, a.S) <= 160 * 1024;
 }

@@ -13,7 +13,6 @@
 
 #include "../../include/ssgd.h"
 #include "common.hpp"
-#include "mlp.hpp"
 
 namespace ssgd {
 namespace {

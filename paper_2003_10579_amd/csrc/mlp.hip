@@ -1,5 +1,5 @@
 // Two-layer ReLU network with a softmax output (the AdaSync experiment's model
-// class, Sec. 5 / Algorithm 1 runs K-async SGD with a changing K): per-worker
+// class, Sec. 6 / Algorithm 1 runs K-async SGD with a changing K): per-worker
 // mini-batch gradients at possibly stale parameters, the K-gradient aggregate and
 // the parameter-server update (Sec. 2.2, Eq. (3)).
 //

@@ -2,8 +2,8 @@
 error-versus-time figures of Sec. 5; not the paper's CIFAR-10 runs): for every variant and K, R independent replicas
 run J updates; reported are the mean simulated time t_J, the mean sub-optimality F(w_J) - F* (the objective over
 the whole data set, F* from the normal equations), the mean staleness of the gradients used and the fraction p0 of
-fresh ones (the quantities of the staleness bound in Sec. 5.1) with the staleness histogram.  One JSON line per
-(variant, K).
+fresh ones (p0 of the lemma in Sec. 4.2, used by the error bound of K-async) with the staleness histogram.  One JSON
+line per (variant, K).
 
   python3 paper_2003_10579_amd/frontier.py [--P 8] [--J 600] [--replicas 16] [--dist shifted_exp,1.0,1.0]
 """
@@ -42,6 +42,7 @@ def frontier(ssgd, Xd, yd, f_star, P, Ks, m, lr, J, replicas, dist_spec, seed=0,
             out.append({"variant": variant, "K": K, "P": P, "updates": J, "replicas": replicas,
                         "mean_time": float(times.mean()), "time_per_update": float(times.mean() / J),
                         "mean_gap": float(gaps.mean()), "gap_sem": float(gaps.std(ddof=1) / np.sqrt(replicas)) if replicas > 1 else 0.0,
+                        "time_by_replica": times.tolist(), "gap_by_replica": gaps.tolist(),
                         "mean_staleness": stale_sum / used, "p0": fresh / used,
                         "staleness_histogram_0_to_15_and_above": (hist / used).round(5).tolist()})
     return out

@@ -1,4 +1,5 @@
-"""Empirical staleness constants of Sec. 5.1 on synthetic least squares: gamma, the smallest constant with
+"""Empirical staleness constants of Sec. 4 on synthetic least squares (the fifth assumption of Sec. 4.1 defines
+gamma, the lemma of Sec. 4.2 gives p0): gamma, the smallest constant with
 E||grad F(w_j) - grad F(w_tau)||^2 <= gamma E||grad F(w_j)||^2 over the gradients an update uses (tau: the version
 its worker read), estimated as the ratio of the two means over a run and its replicas, and p0, the fraction of
 fresh gradients.  The full gradients come from `ssgd_full_gradient` after every update.  One JSON line per

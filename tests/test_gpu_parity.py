@@ -14,7 +14,11 @@ from paper_2003_10579_amd import synth
 pytestmark = pytest.mark.gpu
 
 GRAD_TOL = 1e-5
-PARAM_TOL = 1e-3
+PARAM_TOL = 1e-3          # the bar the task states for the parameters after J updates
+# What fp32 arithmetic supports on the linear models (products and sums of length <= 3072 against fp64;
+# the objective is convex, so rounding differences do not grow): asserted wherever the run is fp32.
+FP32_PARAM_TOL = 1e-5
+FP32_LOSS_RTOL = 2e-5
 
 
 @pytest.fixture(scope="module")
@@ -121,7 +125,8 @@ def test_schedule_table_ties_and_dead_worker(ssgd, oracle, torch_cuda):
 def _run_pair(ssgd, oracle, torch, kind, X, y, P, K, m, variant, spec, lr, J, seed=0, classes=1, check_steps=40):
     """Per-step averaged gradients (teacher-forced from the oracle's iterate where the variant keeps no
     in-flight gradients, i.e. the sync variants; free-running otherwise), then a free run of J updates
-    for the trace and the final parameters."""
+    for the trace and the final parameters.  Single updates go through the same kernels as whole runs:
+    the steady-state kernel wherever the shape allows it (from update 1 on for K-async)."""
     gd, od = dist_pair(ssgd, oracle, spec)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
     mk_ctx = lambda: ssgd.Context(kind, Xd, yd, P, K, m, variant, gd, lr, seed=seed, classes=classes)
@@ -148,8 +153,8 @@ def _run_pair(ssgd, oracle, torch, kind, X, y, P, K, m, variant, spec, lr, J, se
     pr = rel(ctx.params(), tr.params())
     print(f"worst per-step gradient error {worst:.3e}, parameter error after {J} updates {pr:.3e}")
     assert worst <= GRAD_TOL, worst
-    assert np.allclose(gt["loss"], ot["loss"], rtol=2e-4, atol=1e-6)
-    assert pr <= PARAM_TOL, pr
+    assert np.allclose(gt["loss"], ot["loss"], rtol=FP32_LOSS_RTOL, atol=1e-6)
+    assert pr <= FP32_PARAM_TOL, pr
     ctx.close()
     return worst, pr
 
@@ -224,8 +229,8 @@ def test_replicas_are_independent_runs(ssgd, oracle, torch_cuda):
         tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=6, replica=r)
         tr.run(80)
         assert_trace_equal(ctx.trace(r), tr.trace())
-        assert rel(ctx.params(r), tr.params()) <= PARAM_TOL
-        assert np.allclose(ctx.trace(r)["loss"], tr.trace()["loss"], rtol=2e-4, atol=1e-6)
+        assert rel(ctx.params(r), tr.params()) <= FP32_PARAM_TOL
+        assert np.allclose(ctx.trace(r)["loss"], tr.trace()["loss"], rtol=FP32_LOSS_RTOL, atol=1e-6)
     assert not np.array_equal(ctx.params(0), ctx.params(1))
     ctx.close()
 
@@ -264,7 +269,7 @@ def test_adasync_plateau_mode(ssgd, oracle, torch_cuda):
     # sits within rounding of the threshold, so compare exactly and report the first difference
     assert np.array_equal(g["K"], o["K"]), np.argwhere(g["K"] != o["K"])[:3]
     assert_trace_equal(g, o)
-    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
+    assert rel(ctx.params(), tr.params()) <= FP32_PARAM_TOL
     ctx.close()
 
 
@@ -294,14 +299,42 @@ def mixture_full(torch_cuda):
     return X, y, torch_cuda.from_numpy(X).cuda(), torch_cuda.from_numpy(y).cuda()
 
 
-def test_config1_softmax_kasync_full_size(ssgd, oracle, torch_cuda, mixture_full):
-    """d=3072, N=50000, 10 classes, P=8, m=32, K=2, shifted-Exp(0.5, 1), lr=0.05: the benchmark's launch
-    configuration (many replicas in one launch), J=5000 on the GPU; the oracle follows replicas 0 and 37
-    for the first 600 updates (trace bit-exact over all 5000 via a gradient-free oracle run)."""
+@pytest.fixture(scope="module")
+def config2_oracle_run(oracle, mixture_full):
+    """The oracle's whole run of config 2 (2000 iterations of 16 x 128 rows at d=3072 take it minutes on one core),
+    started in a thread of its own the first time a full-size test asks for the data, collected by the config 2
+    test at the end of the module.  The oracle keeps no state outside a Trainer and its calls release the
+    interpreter lock."""
+    import threading
+    from concurrent.futures import ThreadPoolExecutor
+    X, y, _, _ = mixture_full
+
+    def run():
+        tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 64, 16, 128, "k_batch_sync",
+                            oracle.Dist("pareto", 2.5, 1.0), 0.05, seed=0)
+        for _ in range(20):
+            if stop.is_set():     # the module's tests are over (one of them failed): do not hold up the exit
+                break
+            tr.run(100)
+        return tr
+
+    stop = threading.Event()
+    pool = ThreadPoolExecutor(max_workers=1)
+    fut = pool.submit(run)
+    yield fut
+    stop.set()
+    pool.shutdown(wait=False, cancel_futures=True)
+
+
+def test_config1_softmax_kasync_full_size(ssgd, oracle, torch_cuda, mixture_full, config2_oracle_run):
+    """d=3072, N=50000, 10 classes, P=8, m=32, K=2, shifted-Exp(0.5, 1), lr=0.05, J=5000, in the benchmark's launch
+    configuration (many replicas in one launch).  The oracle follows replica 0 through all 5000 updates (30 of them
+    as single steps with the averaged gradient compared, from update 1 on through the steady-state kernel) and
+    replica 37 for the first 600; schedule, loss trace and the parameters at J against it."""
     torch = torch_cuda
     X, y, Xd, yd = mixture_full
     gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
-    R = 40
+    R, J = 40, 5000
     ctx = ssgd.Context("softmax", Xd, yd, 8, 2, 32, "k_async", gd, 0.05, seed=0, classes=10, replicas=R)
     agg = torch.zeros(ctx.nw, device="cuda")
     tr0 = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=0, replica=0)
@@ -311,52 +344,58 @@ def test_config1_softmax_kasync_full_size(ssgd, oracle, torch_cuda, mixture_full
         worst = max(worst, rel(agg.cpu().numpy(), tr0.step()))
     assert worst <= GRAD_TOL, worst
     ctx.run(570)
-    tr0.run(570)
     tr37 = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=0, replica=37)
     tr37.run(600)
-    for r, tr in ((0, tr0), (37, tr37)):
-        assert_trace_equal(ctx.trace(r), tr.trace())
-        assert rel(ctx.params(r), tr.params()) <= PARAM_TOL
-        assert np.allclose(ctx.trace(r)["loss"], tr.trace()["loss"], rtol=2e-4, atol=1e-6)
-    ctx.run(4400)
-    assert ctx.updates == 5000
-    # schedule of the whole run against an oracle that skips the gradients (tiny stand-in model)
+    assert_trace_equal(ctx.trace(37), tr37.trace())
+    assert rel(ctx.params(37), tr37.params()) <= FP32_PARAM_TOL
+    assert np.allclose(ctx.trace(37)["loss"], tr37.trace()["loss"], rtol=FP32_LOSS_RTOL, atol=1e-6)
+    ctx.run(J - 600)
+    tr0.run(J - 30)
+    assert ctx.updates == J and tr0.updates == J
+    assert_trace_equal(ctx.trace(0), tr0.trace())
+    pr = rel(ctx.params(0), tr0.params())
+    print(f"config 1: worst per-step gradient error {worst:.3e}, parameter error after {J} updates {pr:.3e}")
+    assert pr <= FP32_PARAM_TOL, pr
+    assert np.allclose(ctx.trace(0)["loss"], tr0.trace()["loss"], rtol=FP32_LOSS_RTOL, atol=1e-6)
+    # schedule of the whole run of another replica against an oracle that skips the gradients (tiny stand-in model)
     Xs, ys, _ = synth.lsq_data(16, 2, 0)
     sched = oracle.Trainer(oracle.Model("lsq", Xs, ys), 8, 2, 1, "k_async", od, 0.0, seed=0, replica=37)
-    sched.run(5000)
+    sched.run(J)
     assert_trace_equal(ctx.trace(37), sched.trace())
     w = ctx.params(37)
     assert np.all(np.isfinite(w)) and ctx.trace(37)["loss"][-200:].mean() < ctx.trace(37)["loss"][:50].mean()
     ctx.close()
 
 
-def test_config2_softmax_kbatch_sync_full_size(ssgd, oracle, torch_cuda, mixture_full):
-    """P=64, m=128, K=16, Pareto(2.5, 1), lr=0.05 on the d=3072 data; 25 iterations against the oracle,
-    the schedule of all 2000 against a gradient-free oracle run."""
+@pytest.mark.parametrize("variant", ["k_sync", "k_batch_sync"])
+def test_steady_state_kernel_single_steps_at_the_benchmark_launch_shape(ssgd, oracle, torch_cuda, variant):
+    """Eq. (2) at the launch shape of config 1 (d=3072: twelve column slices, 40 replicas in one launch, P=8, m=32,
+    K=2): every single step of replica 0 goes through the steady-state kernel, teacher-forced from the oracle's
+    iterate, the averaged gradient within 1e-5."""
     torch = torch_cuda
-    X, y, Xd, yd = mixture_full
-    gd, od = dist_pair(ssgd, oracle, ("pareto", 2.5, 1.0))
-    ctx = ssgd.Context("softmax", Xd, yd, 64, 16, 128, "k_batch_sync", gd, 0.05, seed=0, classes=10)
-    tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 64, 16, 128, "k_batch_sync", od, 0.05, seed=0)
+    X, y = synth.mixture_data(3000, 3072, 10, seed=3)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    ctx = ssgd.Context("softmax", Xd, yd, 8, 2, 32, variant, gd, 0.05, seed=4, classes=10, replicas=40)
+    tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, variant, od, 0.05, seed=4)
     agg = torch.zeros(ctx.nw, device="cuda")
     worst = 0.0
-    for j in range(25):
+    for j in range(40):
+        ctx.set_params(tr.params())
         ctx.step(agg)
         worst = max(worst, rel(agg.cpu().numpy(), tr.step()))
+    print(f"{variant}: worst per-step gradient error {worst:.3e}")
     assert worst <= GRAD_TOL, worst
     assert_trace_equal(ctx.trace(), tr.trace())
-    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
-    # the steady-state kernel takes an iteration as 32 tiles of 64 rows: 15 more iterations against the oracle
-    ctx.run(15)
-    tr.run(15)
-    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
-    assert np.allclose(ctx.trace()["loss"], tr.trace()["loss"], rtol=2e-4, atol=1e-6)
-    ctx.run(1960)
-    Xs, ys, _ = synth.lsq_data(16, 2, 0)
-    sched = oracle.Trainer(oracle.Model("lsq", Xs, ys), 64, 16, 1, "k_batch_sync", od, 0.0, seed=0)
-    sched.run(2000)
-    assert_trace_equal(ctx.trace(), sched.trace())
     ctx.close()
+
+
+def test_general_kernel_single_steps(ssgd, oracle, torch_cuda, monkeypatch):
+    """The general kernel, forced for a shape the steady-state kernel would take: same bars."""
+    monkeypatch.setenv("SSGD_KERNEL", "general")
+    X, y = synth.mixture_data(1500, 320, 10, seed=1)
+    _run_pair(ssgd, oracle, torch_cuda, "softmax", X, y, 8, 2, 32, "k_async", ("shifted_exp", 0.5, 1.0), 0.05, 120, seed=3,
+              classes=10)
 
 
 # ------------------------------------------------------------------------------- Monte Carlo
@@ -415,7 +454,7 @@ def test_mc_kbatch_async_closed_form_at_scale(ssgd, torch_cuda):
 # the difference visible are decisions taken on those sums -- a hidden unit whose pre-activation is
 # within that error of zero switches its ReLU mask, and a delta1 value within it of a bf16 rounding
 # boundary moves by one bf16 ulp (2^-8 relative) -- each a rare, isolated change of one entry.
-MLP_GRAD_TOL = 2e-3
+MLP_GRAD_TOL = 3e-4     # observed: 6e-7 ... 9e-5
 MLP_PARAM_TOL = 2e-3
 
 
@@ -447,6 +486,8 @@ def test_mlp_initial_parameters_bit_exact(ssgd, oracle, torch_cuda):
     ("k_batch_async", 3, 5, 64, 128, 4, 128),  # K > P: a worker pushes several times per update
     ("k_batch_async", 40, 70, 4, 128, 3, 128), # 109 records at version 0, split gradient contraction
     ("k_batch_async", 5, 1, 64, 128, 16, 128), # K = 1: fully asynchronous SGD
+    ("k_sync", 80, 64, 4, 256, 5, 512),        # 512 hidden units: four rows of 128 x 128 tiles in the split contraction
+    ("k_async", 130, 128, 2, 384, 10, 512),    # eight shares of 16 slots, four rows and three columns of tiles
 ])
 def test_mlp_gradients_teacher_forced(ssgd, oracle, torch_cuda, variant, P, K, m, d, classes, hidden):
     """Every update's averaged gradient against the oracle's.  K-sync is teacher-forced (the oracle's iterate is
@@ -545,6 +586,34 @@ def test_config4_mlp_full_size_first_updates(ssgd, oracle, torch_cuda, mixture_f
     ctx.close()
 
 
+def test_config4_mlp_full_size_large_K(ssgd, oracle, torch_cuda, mixture_full):
+    """Config 4 at its real shape with K forced to the values AdaSync's doubling ends at (Algorithm 1 raises K up
+    to P): two updates at K=64 and one at K=256, each averaged gradient against the oracle's.  From K=64 on the
+    first-layer gradient runs as the split contraction (128 x 128 tiles over 512 x 3072 outputs, shares of the
+    consumed slots added in order) followed by the separate update kernel."""
+    torch = torch_cuda
+    X, y, Xd, yd = mixture_full
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    ada = dict(mode=1, K0=8, Kmax=256, window=200, rel_tol=0.01)
+    ctx = ssgd.Context("mlp2", Xd, yd, 256, 8, 64, "k_async", gd, 0.05, seed=0, classes=10, hidden=512, bf16=1, adasync=ada)
+    tr = oracle.Trainer(oracle.Model("mlp2", X, y, classes=10, hidden=512, bf16=1), 256, 8, 64, "k_async", od, 0.05,
+                        seed=0, adasync=ada)
+    agg = torch.zeros(ctx.nw, dtype=torch.float32, device="cuda")
+    errs = []
+    for K in (64, 64, 256):
+        ctx.force_K(K)
+        tr.force_K(K)
+        ctx.step(agg)
+        errs.append(rel(agg.cpu().numpy(), tr.step()))
+    assert_trace_equal(ctx.trace(), tr.trace())
+    assert list(ctx.trace()["K"]) == [64, 64, 256]
+    pr = rel(ctx.params(), tr.params())
+    print(f"config 4 full size, K = 64, 64, 256: per-step gradient errors {errs}, parameter error {pr:.3e}")
+    assert max(errs) <= MLP_GRAD_TOL, errs
+    assert pr <= MLP_PARAM_TOL, pr
+    ctx.close()
+
+
 def test_exchange_fallback_without_shared_l2(ssgd, oracle, torch_cuda, monkeypatch):
     """The cluster exchange has two protocols: through the L2 of one XCD (data words polled directly) and, for a
     cluster that is spread over XCDs, released stores with an arrival counter.  The second one is forced here."""
@@ -583,7 +652,7 @@ def test_more_replicas_than_one_launch_holds(ssgd, oracle, torch_cuda):
         tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=2, replica=r)
         tr.run(60)
         assert_trace_equal(ctx.trace(r), tr.trace())
-        assert rel(ctx.params(r), tr.params()) <= PARAM_TOL
+        assert rel(ctx.params(r), tr.params()) <= FP32_PARAM_TOL
     ctx.close()
 
 
@@ -618,8 +687,8 @@ def test_adasync_ksync_rule_with_growing_tile_count(ssgd, oracle, torch_cuda):
     g, o = ctx.trace(), tr.trace()
     assert o["K"][-1] > 8
     assert_trace_equal(g, o)
-    assert np.allclose(g["loss"], o["loss"], rtol=2e-4, atol=1e-6)
-    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
+    assert np.allclose(g["loss"], o["loss"], rtol=FP32_LOSS_RTOL, atol=1e-6)
+    assert rel(ctx.params(), tr.params()) <= FP32_PARAM_TOL
     ctx.close()
 
 
@@ -679,7 +748,7 @@ def test_snapshot_resume_continues_the_same_run(ssgd, oracle, torch_cuda, kind, 
     tr = oracle.Trainer(oracle.Model(kind, X, y, classes=classes), P, K, m, variant, od, 0.03, seed=13, replica=2, adasync=ada)
     tr.run(100)
     assert_trace_equal(b.trace(2), tr.trace())
-    assert rel(b.params(2), tr.params()) <= PARAM_TOL
+    assert rel(b.params(2), tr.params()) <= FP32_PARAM_TOL
     # a snapshot of another configuration is refused and leaves the context as it was
     other = ssgd.Context(kind, Xd, yd, P, K, m, variant, gd, 0.03, seed=14, classes=classes, replicas=3, adasync=ada)
     with pytest.raises(ssgd.SsgdError):
@@ -687,6 +756,42 @@ def test_snapshot_resume_continues_the_same_run(ssgd, oracle, torch_cuda, kind, 
     assert other.updates == 0
     for c in (a, b, other):
         c.close()
+
+
+def test_malformed_snapshots_leave_the_context_unchanged(ssgd, oracle, torch_cuda):
+    """A truncated buffer, a header that claims more updates than the buffer holds, or one whose size does not
+    fit this configuration is refused with SSGD_EINVAL before the context is touched: the run goes on as if
+    nothing had been tried."""
+    torch = torch_cuda
+    X, y = synth.mixture_data(800, 320, 10, seed=3)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    ctx = ssgd.Context("softmax", Xd, yd, 8, 2, 32, "k_async", gd, 0.05, seed=1, classes=10)
+    ctx.run(20)
+    good = ctx.get_state()
+    ctx.run(15)
+    hdr_j = 8 + 8 + 12 * 4 + 2 * 8        # offset of the update count in the header: magic, size, 12 ints, N, nw
+    assert int(np.frombuffer(good, dtype=np.int64, count=1, offset=hdr_j)[0]) == 20
+    def with_j(v):
+        b = good.copy()
+        b[hdr_j:hdr_j + 8] = np.frombuffer(np.int64(v).tobytes(), dtype=np.uint8)
+        return b
+    bad = [good[:-64].copy(),                                     # truncated
+           with_j(2 ** 40), with_j(-3), with_j(19),               # update counts the buffer cannot hold / does not match
+           np.frombuffer(b"SSGDST01" + bytes(40), dtype=np.uint8)]   # shorter than a header
+    for b in bad:
+        with pytest.raises(ssgd.SsgdError) as ei:
+            ctx.set_state(b)
+        assert ei.value.status == ssgd.EINVAL
+        assert ctx.updates == 35
+    ctx.run(10)
+    tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=1)
+    tr.run(45)
+    assert_trace_equal(ctx.trace(), tr.trace())
+    assert rel(ctx.params(), tr.params()) <= FP32_PARAM_TOL
+    ctx.set_state(good)                                           # and a good snapshot is still accepted
+    assert ctx.updates == 20
+    ctx.close()
 
 
 @pytest.mark.parametrize("variant,K", [("k_async", 2), ("k_batch_async", 4)])
@@ -753,7 +858,7 @@ def test_kbatch_async_long_schedule_and_workers(ssgd, oracle, torch_cuda):
     otau, ofinish = tr.workers()
     assert np.array_equal(g["tau"].astype(np.int64), otau)
     assert np.array_equal(g["finish"], ofinish)
-    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
+    assert rel(ctx.params(), tr.params()) <= FP32_PARAM_TOL
     other = mk()
     other.set_state(blob)
     other.run(800)
@@ -853,7 +958,7 @@ def test_full_gradient_against_the_oracle(ssgd, oracle, torch_cuda, kind, N, d, 
 
 
 def test_staleness_gamma_estimate(ssgd, oracle, torch_cuda):
-    """gamma of Sec. 5.1 from the driver: zero for a synchronous variant (every gradient is fresh), positive and
+    """gamma of the staleness bound (fifth assumption of Sec. 4.1) from the driver: zero for a synchronous variant (every gradient is fresh), positive and
     growing with the staleness for K-async (K = 1 against K = P / 2 at P = 8), and equal to the same ratio formed
     from the oracle's fp64 gradients at the iterates of the run."""
     from paper_2003_10579_amd import staleness_gamma
@@ -886,10 +991,11 @@ def test_staleness_gamma_estimate(ssgd, oracle, torch_cuda):
     assert abs(a1["gamma"] - want) <= 1e-4 * want, (a1["gamma"], want)
 
 
-def test_error_runtime_frontier_orders_the_variants(ssgd, torch_cuda):
-    """The four variants at the same K on the same problem (Sec. 3, Table 1): per update K-batch-async is the
-    fastest and K-sync the slowest; the synchronous variants only use fresh gradients, the asynchronous ones do not;
-    and every run ends above the optimum of the least-squares objective."""
+def test_error_runtime_frontier_against_the_oracle(ssgd, oracle, torch_cuda):
+    """The four variants at the same K on the same problem (Sec. 3, Table 1).  Every point of the trade-off against
+    the oracle, replica by replica: the simulated time t_J bit for bit and the sub-optimality F(w_J) - F* (Sec. 2.3)
+    within 1e-3 relative.  Then the orderings: per update K-batch-async is the fastest and K-sync the slowest; the
+    synchronous variants only use fresh gradients, the asynchronous ones do not; every run ends above the optimum."""
     from paper_2003_10579_amd import frontier
     torch = torch_cuda
     X, y, _ = synth.lsq_data(2048, 132, 3)
@@ -899,6 +1005,19 @@ def test_error_runtime_frontier_orders_the_variants(ssgd, torch_cuda):
     f_star = 0.5 * float(np.mean((X64 @ w_opt - y64) ** 2))
     recs = frontier.frontier(ssgd, Xd, yd, f_star, 8, [2, 4], 8, 0.01, 300, 6, ("shifted_exp", 1.0, 1.0), seed=1)
     by = {(r["variant"], r["K"]): r for r in recs}
+    M = oracle.Model("lsq", X, y)
+    od = oracle.Dist("shifted_exp", 1.0, 1.0)
+    worst_gap = 0.0
+    for (variant, K), rec in by.items():
+        for r in range(6):
+            tr = oracle.Trainer(M, 8, K, 8, variant, od, 0.01, seed=1, replica=r)
+            tr.run(300)
+            assert tr.clock == rec["time_by_replica"][r], (variant, K, r)
+            gap = M.full_loss(tr.params()) - f_star
+            assert gap > 0
+            worst_gap = max(worst_gap, abs(rec["gap_by_replica"][r] - gap) / gap)
+    print(f"error-runtime trade-off: worst relative difference of F(w_J) - F* from the oracle's {worst_gap:.2e}")
+    assert worst_gap <= 1e-3, worst_gap
     for K in (2, 4):
         ts = [by[(v, K)]["time_per_update"] for v in ("k_batch_async", "k_async", "k_sync")]
         assert ts[0] < ts[1] < ts[2], ts
@@ -938,8 +1057,8 @@ def test_kbatch_async_with_plateau_doubling(ssgd, oracle, torch_cuda):
     g, o = ctx.trace(), tr.trace()
     assert o["K"][-1] == 8 and o["K"][0] == 1
     assert_trace_equal(g, o)
-    assert np.allclose(g["loss"], o["loss"], rtol=2e-4, atol=1e-6)
-    assert rel(ctx.params(), tr.params()) <= PARAM_TOL
+    assert np.allclose(g["loss"], o["loss"], rtol=FP32_LOSS_RTOL, atol=1e-6)
+    assert rel(ctx.params(), tr.params()) <= FP32_PARAM_TOL
     ctx.close()
 
 
@@ -952,3 +1071,35 @@ def test_stream_read_rate_is_plausible(ssgd, torch_cuda):
     assert 1.0e12 < rate < 8.0e12, rate
     with pytest.raises(ssgd.SsgdError):
         ssgd.stream_read_rate(x[1:], passes=1)          # not 16-byte aligned
+
+
+# ------------------------------------------------------------------------------- config 2 at its full horizon
+
+def test_config2_softmax_kbatch_sync_full_size(ssgd, oracle, torch_cuda, mixture_full, config2_oracle_run):
+    """P=64, m=128, K=16, Pareto(2.5, 1), lr=0.05 on the d=3072 data, J=2000: 25 iterations as single steps with
+    the averaged gradient compared (each iteration is 32 tiles of 64 rows in the steady-state kernel), then the
+    whole run: schedule, loss trace and the parameters at J against the oracle, whose 2000 iterations (about two
+    minutes on one core) run in a thread of their own from the start of this module."""
+    torch = torch_cuda
+    X, y, Xd, yd = mixture_full
+    gd, od = dist_pair(ssgd, oracle, ("pareto", 2.5, 1.0))
+    J = 2000
+    ctx = ssgd.Context("softmax", Xd, yd, 64, 16, 128, "k_batch_sync", gd, 0.05, seed=0, classes=10)
+    tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 64, 16, 128, "k_batch_sync", od, 0.05, seed=0)
+    agg = torch.zeros(ctx.nw, device="cuda")
+    worst = 0.0
+    for j in range(25):
+        ctx.step(agg)
+        worst = max(worst, rel(agg.cpu().numpy(), tr.step()))
+    assert worst <= GRAD_TOL, worst
+    assert_trace_equal(ctx.trace(), tr.trace())
+    assert rel(ctx.params(), tr.params()) <= FP32_PARAM_TOL
+    ctx.run(J - 25)
+    full = config2_oracle_run.result()
+    assert full.updates == J
+    assert_trace_equal(ctx.trace(), full.trace())
+    pr = rel(ctx.params(), full.params())
+    print(f"config 2: worst per-step gradient error {worst:.3e}, parameter error after {J} iterations {pr:.3e}")
+    assert pr <= FP32_PARAM_TOL, pr
+    assert np.allclose(ctx.trace()["loss"], full.trace()["loss"], rtol=FP32_LOSS_RTOL, atol=1e-6)
+    ctx.close()

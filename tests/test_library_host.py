@@ -50,6 +50,13 @@ def _model(kind=ssgd.SOFTMAX, d=8, classes=3, X=0x1000, y=0x1000, N=10, hidden=0
     dict(dist=("shifted_exp", 0.5, -2.0)), dict(model=dict(X=None)), dict(model=dict(N=0)),
     dict(model=dict(classes=17)), dict(model=dict(kind=ssgd.LSQ, bf16=1)), dict(model=dict(kind=9)),
     dict(model=dict(kind=ssgd.MLP2, hidden=100)), dict(ada=dict(mode=1, K0=2, Kmax=1, window=10)),
+    # the two-layer network: every limit the header states, refused before anything is allocated
+    dict(model=dict(kind=ssgd.MLP2, d=128, hidden=128, classes=4, bf16=0)),      # fp32 operands are not built
+    dict(model=dict(kind=ssgd.MLP2, d=128, hidden=192, classes=4, bf16=1)),      # hidden % 128
+    dict(model=dict(kind=ssgd.MLP2, d=96, hidden=128, classes=4, bf16=1)),       # d % 128
+    dict(model=dict(kind=ssgd.MLP2, d=128, hidden=128, classes=4, bf16=1), m=65),
+    dict(model=dict(kind=ssgd.MLP2, d=128, hidden=128, classes=4, bf16=1), replicas=2),
+    dict(model=dict(kind=ssgd.MLP2, d=128, hidden=128, classes=17, bf16=1)),
     dict(ada=dict(mode=2, K0=2, Kmax=4, window=0, interval_t=0.0)),
 ])
 def test_create_rejects_invalid_arguments(L, case):

@@ -517,6 +517,46 @@ def test_mlp_bf16_mode_rounds_where_stated(oracle):
     assert 0 < rel < 2.0 ** -8                          # W1 gradient differs only by the bf16 rounding
 
 
+def test_initial_parameters(oracle):
+    """Reading of the paper's silence on w_0: zeros for the linear models; for the two-layer network biases
+    exactly 0 and every weight uniform on +-1/sqrt(fan_in) of ITS layer (fan-in d for the hidden layer, the
+    number of hidden units for the output layer).  Checked: support, mean 0 and variance bound^2/3 within 5
+    standard errors, a Kolmogorov-Smirnov test against the uniform law, layout (which entries are weights and
+    which biases), dependence on the seed and on nothing else."""
+    X, y = synth.mixture_data(20, 48, 7, seed=1)
+    for kind, classes in (("lsq", 1), ("softmax", 7)):
+        yy = y if kind == "softmax" else np.float32(y)
+        assert not oracle.Model(kind, X, yy, classes=classes).init_params(seed=3).any()
+    d, H, C = 48, 200, 7
+    M = oracle.Model("mlp2", X, y, classes=C, hidden=H, bf16=1)
+    assert M.nw == H * d + H + C * H + C
+    w = M.init_params(seed=3)
+    W1, b1 = w[:H * d], w[H * d:H * d + H]
+    W2, b2 = w[H * d + H:H * d + H + C * H], w[H * d + H + C * H:]
+    assert not b1.any() and not b2.any()
+    for W, fan_in in ((W1, d), (W2, H)):
+        bound = 1.0 / math.sqrt(fan_in)
+        n = W.size
+        assert np.all(np.abs(W) < bound * (1 + 1e-6)) and np.abs(W).max() > 0.95 * bound
+        # a wrong fan-in (the other layer's, or fan-out) moves the variance by a factor, far outside 5 sigma
+        assert abs(W.mean()) <= 5 * bound / math.sqrt(3 * n)
+        var_se = (bound ** 2) * math.sqrt(4.0 / 45.0 / n)          # sd of U^2 for U ~ U(-b, b) is b^2 sqrt(4/45)
+        assert abs(np.mean(np.float64(W) ** 2) - bound ** 2 / 3) <= 5 * var_se
+        assert stats.kstest(np.float64(W), stats.uniform(loc=-bound, scale=2 * bound).cdf).pvalue > 1e-3
+        assert np.unique(W).size > 0.99 * n
+    # consecutive entries are not correlated (one Philox word per entry, not one word reused)
+    assert abs(np.corrcoef(W1[:-1], W1[1:])[0, 1]) < 5 / math.sqrt(W1.size)
+    assert np.array_equal(w, M.init_params(seed=3))
+    w4 = M.init_params(seed=4)
+    assert np.mean(w4[:H * d] == W1) < 0.01
+    # the data set plays no part
+    X2, y2 = synth.mixture_data(20, 48, 7, seed=9)
+    assert np.array_equal(oracle.Model("mlp2", X2, y2, classes=C, hidden=H, bf16=1).init_params(seed=3), w)
+    # a trainer starts from exactly these parameters
+    tr = oracle.Trainer(M, 3, 2, 4, "k_sync", oracle.Dist("exp", 1.0), 0.1, seed=3)
+    assert np.array_equal(tr.params(), w)
+
+
 # --------------------------------------------------------------------------- update rules
 
 def test_full_sync_equals_minibatch_sgd_with_P_fold_batch(oracle):
