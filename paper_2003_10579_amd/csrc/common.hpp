@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <string>
+
 #include "rng.hpp"
 
 namespace ssgd {
@@ -122,10 +124,18 @@ bool full_grad_supports(int kind, int d, int C);
 int64_t full_grad_scratch_floats(int64_t N, int d, int C, int* chunks_out);
 hipError_t launch_full_grad(int kind, const float* X, const void* y, int64_t N, int d, int C, const float* w,
                             float* scratch, float* out, int cus, hipStream_t s);
+// The static scratch array of full_grad.hip (one copy per GPU, held until the process ends): its size, the per-device
+// look-up of its address (call once with the device current), and the address on the current device.
+int64_t full_grad_static_scratch_floats();
+hipError_t full_grad_static_scratch_prepare();
+float* full_grad_static_scratch();
 // Objective over the whole data set for one parameter vector of a linear model (full_loss.hip): partial sums of the
 // per-sample losses, one fp64 per workgroup.
 bool full_loss_supports(int kind, int d, int C);
 hipError_t launch_full_loss(int kind, const float* X, const void* y, int64_t N, int d, int C, const float* w, double* partial,
                             int blocks, hipStream_t s);
+
+// Message behind ssgd_last_error(NULL), for the entry points that take no context (api.hip).
+void set_global_error(const std::string& msg);
 
 }  // namespace ssgd

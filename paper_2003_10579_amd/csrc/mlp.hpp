@@ -23,6 +23,4 @@ hipError_t mlp_get_state(MlpState* s, unsigned char* host);
 hipError_t mlp_set_state(MlpState* s, const unsigned char* host);
 void mlp_destroy(MlpState* s);
 
-void set_global_error(const std::string& msg);
-
 }  // namespace ssgd
