@@ -167,6 +167,21 @@ ssgd_status ssgd_full_loss(ssgd_ctx *ctx, int32_t replica, double *loss_out);
  * SSGD_EINVAL. */
 ssgd_status ssgd_full_gradient(ssgd_ctx *ctx, int32_t replica, float *grad_out);
 
+/* ssgd_full_gradient for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels in the same launch shape,
+ * hence the same values bit for bit, but the intermediate results (16 floats per sample and up to
+ * 64 partial gradients) live in a static device array of the library, 4 Mi floats = 16 MiB that every
+ * GPU the library runs on holds until the process ends, and the gradient is written to
+ * grad_out_device (DEVICE, |w| floats, layout of the parameters).  The call allocates and frees
+ * nothing, copies nothing to the host and does not wait: the work is enqueued on the context's stream
+ * and the result is complete when that stream reaches the end of it.  Data sets that need more than
+ * the array holds (16 N + min(64, ceil(N / 256)) * classes * (d + 1) floats > 4 Mi) give SSGD_EINVAL,
+ * as do the shapes ssgd_full_gradient refuses.  All calls on one GPU, from any context, share that
+ * GPU's array: calls that overlap on one GPU (different streams or threads) race; calls on one stream
+ * are ordered.  Nothing in the array has to be zero at entry: a call writes every word before it
+ * reads it, so the contents left by an earlier, larger call do not matter. */
+ssgd_status ssgd_full_gradient_static(ssgd_ctx *ctx, int32_t replica, float *grad_out_device);
+
 /* The mini-batch each worker of a K-async run has in flight (Sec. 2.2: a worker that is not
  * among the K selected keeps computing on the parameters it read): version read tau_i, ordinal,
  * absolute finish time f_i.  HOST arrays of P entries, each nullable.  SSGD_EINVAL for the

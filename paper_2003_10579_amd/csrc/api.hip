@@ -504,6 +504,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         }
         HIP_C(c->arrive.alloc(sizeof(unsigned int) * kArriveStride * R));
         HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * R, c->stream));
+        // set-up for ssgd_full_gradient_static: this device's address of the library's static scratch array
+        HIP_C(full_grad_static_scratch_prepare());
     }
     HIP_C(hipStreamSynchronize(c->stream));
 #undef HIP_C
@@ -644,6 +646,27 @@ ssgd_status ssgd_full_gradient(ssgd_ctx* c, int32_t replica, float* grad_out) {
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     scratch.release(); out.release();
     if (e != hipSuccess) return fail(c, SSGD_EDEVICE, std::string("full gradient: ") + hipGetErrorString(e));
+    return SSGD_OK;
+}
+
+ssgd_status ssgd_full_gradient_static(ssgd_ctx* c, int32_t replica, float* grad_out_device) {
+    if (!c || !grad_out_device) return fail(c, SSGD_EINVAL, "null argument");
+    if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
+    if (c->broken) return fail(c, SSGD_ESTATE, "context is unusable after a device error");
+    const int C = c->model.kind == SSGD_LSQ ? 1 : c->model.classes;
+    if (c->model.kind == SSGD_MLP2 || !full_grad_supports(c->model.kind, c->model.d, C))
+        return fail(c, SSGD_EINVAL, "the full gradient is built for the linear models with d % 4 == 0");
+    const int64_t need = full_grad_scratch_floats(c->model.N, c->model.d, C, nullptr);
+    if (need > full_grad_static_scratch_floats())
+        return fail(c, SSGD_EINVAL, "the data set needs " + std::to_string(need) + " floats of scratch memory, the static array holds " +
+                                        std::to_string(full_grad_static_scratch_floats()) + " (16 N + min(64, ceil(N / 256)) classes (d + 1))");
+    HIP_OK(c, hipSetDevice(c->device));
+    float* work = full_grad_static_scratch();
+    if (!work) return fail(c, SSGD_ESTATE, "the static scratch array was not set up on this device");
+    // every word of the scratch memory that the kernels read has been written by this call before (the per-sample
+    // deltas of rows 0 .. N-1, the partial sums of all chunks, classes and columns), so nothing has to be cleared
+    HIP_OK(c, launch_full_grad(c->model.kind, c->model.X, c->model.y, c->model.N, c->model.d, C,
+                               c->params.as<float>() + (int64_t)replica * c->nw, work, grad_out_device, c->cu_count, c->stream));
     return SSGD_OK;
 }
 

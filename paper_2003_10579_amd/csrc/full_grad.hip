@@ -5,12 +5,24 @@
 //   2. G[c][col] = sum_n delta[n][c] X[n][col], a thread per column (the bias is one more column of ones), the
 //      samples split into chunks whose partial sums (fp32 within a chunk) are added in chunk order in fp64.
 // A statistic for drivers, not part of an update: plain FMA code, bound by the two reads of X.
+#include <mutex>
+
 #include "common.hpp"
 
 namespace ssgd {
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Scratch memory of the entry point that allocates nothing: every GPU the library runs on holds one copy of this
+// array for the life of the process (16 MiB).  In host code the name stands for the symbol, not for a device
+// address: the address on the current device comes from hipGetSymbolAddress, once per device, and only that pointer
+// is handed to kernels.
+constexpr int64_t kStaticScratchFloats = 4ll << 20;
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
 
 struct FullGradArgs {
     const float* X;
@@ -134,14 +146,41 @@ int64_t full_grad_scratch_floats(int64_t N, int d, int C, int* chunks_out) {
     return N * 16 + (int64_t)chunks * C * (d + 1);
 }
 
-// `scratch`: full_grad_scratch_floats floats of device memory; `out`: |w| floats of device memory
+int64_t full_grad_static_scratch_floats() { return kStaticScratchFloats; }
+
+// Looks up, once per device, where that device keeps its copy of the static scratch array.  Called with the device
+// current (ssgd_create does, for every context of a linear model), so that the entry point itself only reads the table.
+hipError_t full_grad_static_scratch_prepare() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] != nullptr) return hipSuccess;
+    float* p = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+    return hipSuccess;
+}
+
+// The current device's copy of the static scratch array, nullptr before full_grad_static_scratch_prepare ran there.
+float* full_grad_static_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    return g_scratch_ptr[dev];
+}
+
+// `work`: full_grad_scratch_floats floats of device memory; `out`: |w| floats of device memory
 hipError_t launch_full_grad(int kind, const float* X, const void* y, int64_t N, int d, int C, const float* w,
-                            float* scratch, float* out, int cus, hipStream_t s) {
+                            float* work, float* out, int cus, hipStream_t s) {
     FullGradArgs a{};
     a.X = X; a.y = y; a.w = w; a.N = N; a.d = d; a.C = C; a.kind = kind;
     (void)full_grad_scratch_floats(N, d, C, &a.chunks);
     a.chunk_rows = ((N + a.chunks - 1) / a.chunks + 63) / 64 * 64;
-    a.delta = scratch; a.partial = scratch + N * 16; a.out = out;
+    a.delta = work; a.partial = work + N * 16; a.out = out;
     const int blocks = (int)std::min<int64_t>((N + 15) / 16, (int64_t)std::max(1, cus) * 8);
     if (kind == kLsq) hipLaunchKernelGGL(full_grad_delta_kernel<kLsq>, dim3(blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(full_grad_delta_kernel<kSoftmax>, dim3(blocks), dim3(256), 0, s, a);

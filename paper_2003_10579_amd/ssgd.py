@@ -21,7 +21,7 @@ EXPORTS = [
     "ssgd_create", "ssgd_run", "ssgd_reserve_trace", "ssgd_step", "ssgd_param_count", "ssgd_updates_done", "ssgd_current_K",
     "ssgd_trace_width", "ssgd_get_trace", "ssgd_get_params", "ssgd_set_params", "ssgd_force_K",
     "ssgd_get_workers", "ssgd_state_bytes", "ssgd_get_state", "ssgd_set_state", "ssgd_full_loss",
-    "ssgd_full_gradient",
+    "ssgd_full_gradient", "ssgd_full_gradient_static",
     "ssgd_runtime_mc", "ssgd_debug_delays", "ssgd_debug_batch", "ssgd_stream_read_rate", "ssgd_last_error",
     "ssgd_last_kernel_ms",
     "ssgd_destroy",
@@ -89,6 +89,7 @@ def lib():
         L.ssgd_force_K.argtypes = [C.c_void_p, C.c_int32]
         L.ssgd_full_loss.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]
         L.ssgd_full_gradient.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        L.ssgd_full_gradient_static.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.ssgd_get_workers.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ssgd_state_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         L.ssgd_get_state.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
@@ -204,6 +205,12 @@ class Context:
         g = np.zeros(self.nw, dtype=np.float32)
         _check(lib().ssgd_full_gradient(self.h, replica, g.ctypes.data), self.h)
         return g
+
+    def full_gradient_static(self, out, replica=0):
+        """Same gradient into `out` (a device tensor of |w| floats), through the library's static scratch array:
+        nothing is allocated, nothing is awaited (the work is enqueued on the context's stream)."""
+        assert out.is_cuda and out.is_contiguous() and out.numel() >= self.nw and out.element_size() == 4
+        _check(lib().ssgd_full_gradient_static(self.h, replica, out.data_ptr()), self.h)
 
     def workers(self, replica=0):
         tau = np.zeros(self.P, dtype=np.int32)
