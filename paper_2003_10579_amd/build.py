@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssgd.so")
-SOURCES = ["api.hip", "schedule.hip", "linear.hip", "linear_tile.hip", "full_loss.hip", "full_grad.hip", "mlp.hip", "mc.hip"]
+SOURCES = ["api.hip", "schedule.hip", "linear.hip", "linear_tile.hip", "linear_defer.hip", "full_loss.hip", "full_grad.hip", "mlp.hip", "mc.hip"]
 HEADERS = ["common.hpp", "rng.hpp", "mlp.hpp", os.path.join("..", "..", "include", "ssgd.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

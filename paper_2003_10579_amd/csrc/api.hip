@@ -44,7 +44,7 @@ struct ssgd_ctx {
     int device = 0;
     int64_t nw = 0;
     int32_t Kcap = 0, S = 0, G = 0, nbw = 0, maxrows = 0, table_ord = 1;
-    int tile_resident_groups = 0, cu_count = 0;
+    int tile_resident_groups = 0, defer_per_launch = 0, cu_count = 0;
     LinArgs lin{};
     int64_t j = 0;
     int32_t win_cnt = 0;
@@ -54,7 +54,7 @@ struct ssgd_ctx {
     DevBuf tr_t, tr_loss, tr_K, tr_sel, tr_tau, tr_ord;
     WorkerState ws{};
     DevBuf ws_finish, ws_tau, ws_ord, ws_clock, ws_curK, ws_winprev, ws_winidx, ws_F0, ws_intstart, ws_crossed, ws_ndone;
-    DevBuf params, park, park_small, zpart, zx, arrive, abort_flag, xcc_ids, prof;
+    DevBuf params, park, park_small, zpart, zx, dx, fallback, arrive, abort_flag, xcc_ids, prof;
     int resident_groups = 0;
     size_t lds_bytes = 0;
     MlpState* mlp = nullptr;
@@ -189,14 +189,20 @@ int chunks_for(int n_rec, int mp) {
     return n_rec * ((mp + 63) / 64);
 }
 
-// One launch per group of co-resident replicas; `tile` selects the single-tile steady-state kernel.
-ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, bool tile,
+// One launch per group of co-resident replicas; `mode` selects the kernel.
+enum LinearKernel { kGeneralKernel = 0, kTileKernel = 1, kDeferKernel = 2 };
+ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, int mode,
                          std::vector<std::pair<hipEvent_t, hipEvent_t>>* events) {
+    const bool tile = mode != kGeneralKernel;
     // a cluster stays on one XCD (block ids congruent modulo 8), so the resident slots count per XCD
     const int resident = tile ? c->tile_resident_groups : c->resident_groups;
-    const int per_launch = std::max(1, 8 * ((resident / 8) / c->G));
+    const int per_launch = mode == kDeferKernel ? c->defer_per_launch : std::max(1, 8 * ((resident / 8) / c->G));
     HIP_OK(c, hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * c->R, c->stream));
     if (tile) HIP_OK(c, hipMemsetAsync(c->zx.p, 0xFF, sizeof(uint32_t) * 3 * 1024 * (size_t)c->R * c->G, c->stream));
+    if (mode == kDeferKernel) {
+        HIP_OK(c, hipMemsetAsync(c->dx.p, 0xFF, sizeof(uint32_t) * 3 * 1024 * (size_t)c->R, c->stream));
+        HIP_OK(c, hipMemsetAsync(c->fallback.p, 0, sizeof(int32_t) * (size_t)c->R, c->stream));
+    }
     if (getenv("SSGD_DEBUG"))
         fprintf(stderr, "ssgd launch: v0=%lld n=%lld tile=%d resident=%d per_launch=%d R=%d\n", (long long)v0, (long long)n,
                 (int)tile, resident, per_launch, c->R);
@@ -208,9 +214,11 @@ ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, boo
         a.agg_out = agg_out;
         a.pair_cus = 0; a.pair_layers = 0;
         a.shared_cus = (a.replicas * c->G > c->cu_count) ? 1 : 0;
-        a.prof_wave = 0; a.prof_a = -1; a.prof_b = -1; a.prof_base = (int64_t)c->R * c->G * 20;
+        a.prof_wave = 0; a.prof_a = -1; a.prof_b = -1; a.prof_base = (int64_t)c->R * c->G * 20; a.prof_helper = (int64_t)c->R * c->G * 2;
         if (const char* e = getenv("SSGD_PHASE_PROFILE")) (void)sscanf(e, "%d,%d,%d", &a.prof_a, &a.prof_b, &a.prof_wave);
-        if (tile && a.replicas == per_launch && c->cu_count % 8 == 0 && resident % c->cu_count == 0 && !getenv("SSGD_NO_PAIRING")) {
+        a.debug_flags = 0;
+        if (const char* e = getenv("SSGD_DEBUG_FLAGS")) a.debug_flags = atoi(e);
+        if (mode == kTileKernel && a.replicas == per_launch && c->cu_count % 8 == 0 && resident % c->cu_count == 0 && !getenv("SSGD_NO_PAIRING")) {
             a.pair_cus = c->cu_count / 8;
             a.pair_layers = resident / c->cu_count;
             // the dealt-out layout must hold as many clusters per XCD as the consecutive one
@@ -222,8 +230,35 @@ ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, boo
             HIP_OK(c, hipEventCreate(&e0)); HIP_OK(c, hipEventCreate(&e1));
             HIP_OK(c, hipEventRecord(e0, c->stream));
         }
-        HIP_OK(c, tile ? launch_linear_tile(a, c->stream) : launch_linear(a, c->nbw, c->stream));
+        HIP_OK(c, mode == kDeferKernel ? launch_linear_defer(a, c->stream)
+                                       : (tile ? launch_linear_tile(a, c->stream) : launch_linear(a, c->nbw, c->stream)));
         if (events) { HIP_OK(c, hipEventRecord(e1, c->stream)); events->push_back({e0, e1}); }
+    }
+    if (mode == kDeferKernel) {
+        // A cluster that found itself spread over XCDs has left its replica untouched: those replicas take the same
+        // updates through the kernel that can exchange across XCDs.
+        std::vector<int32_t> fb((size_t)c->R);
+        HIP_OK(c, hipMemcpyAsync(fb.data(), c->fallback.p, sizeof(int32_t) * fb.size(), hipMemcpyDeviceToHost, c->stream));
+        HIP_OK(c, hipStreamSynchronize(c->stream));
+        bool any = false;
+        for (int r = 0; r < c->R; ++r) any = any || fb[r] != 0;
+        if (any) {
+            HIP_OK(c, hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * c->R, c->stream));
+            HIP_OK(c, hipMemsetAsync(c->zx.p, 0xFF, sizeof(uint32_t) * 3 * 1024 * (size_t)c->R * c->G, c->stream));
+            for (int r = 0; r < c->R; ++r) {
+                if (!fb[r]) continue;
+                LinArgs a = c->lin;
+                a.replica0 = r; a.replicas = 1;
+                a.tr = c->tr;
+                a.v0 = v0; a.nsteps = n;
+                a.agg_out = agg_out;
+                a.pair_cus = 0; a.pair_layers = 0; a.shared_cus = 0;
+                a.prof_wave = 0; a.prof_a = -1; a.prof_b = -1; a.prof_base = (int64_t)c->R * c->G * 20; a.prof_helper = (int64_t)c->R * c->G * 2;
+                a.debug_flags = 0;
+                if (!linear_tile_supports(a, c->Kcap)) return fail(c, SSGD_EDEVICE, "a cluster was spread over XCDs and no other kernel takes its shape");
+                HIP_OK(c, launch_linear_tile(a, c->stream));
+            }
+        }
     }
     return SSGD_OK;
 }
@@ -240,6 +275,8 @@ ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_ou
     a.params = c->params.as<float>(); a.park = c->park.as<float>(); a.park_small = c->park_small.as<float>();
     a.zpart = c->zpart.as<float>(); a.maxrows = c->maxrows;
     a.zx = c->zx.as<uint32_t>();
+    a.dx = c->dx.as<uint32_t>();
+    a.fallback = c->fallback.as<int32_t>();
     a.arrive = c->arrive.as<unsigned int>();
     a.abort_flag = c->abort_flag.as<int32_t>();
     a.spin_limit = 4000000u;
@@ -253,21 +290,27 @@ ssgd_status run_segment_linear(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_ou
     // The steady-state kernel runs the steps whose mini-batches fit one tile; step 0 of K-async
     // (all P workers start) and every other shape go through the general kernel.
     bool tile = c->nbw == 4 && c->tile_resident_groups >= c->G;
-    if (const char* e = getenv("SSGD_KERNEL")) tile = tile && strcmp(e, "general") != 0;
+    bool defer = c->nbw == 4 && c->defer_per_launch >= 1 && c->tile_resident_groups >= c->G;
+    if (const char* e = getenv("SSGD_KERNEL")) {          // diagnostics: "general" or "tile" keep the later kernels out
+        tile = tile && strcmp(e, "general") != 0;
+        defer = defer && strcmp(e, "general") != 0 && strcmp(e, "tile") != 0;
+    }
     int64_t head = 0;
-    if (tile) {
-        a.v0 = v0;
+    a.v0 = v0;
+    a.chunked = 0;
+    if (tile || defer) {
         if (c->variant == SSGD_K_ASYNC && v0 == 0) { head = 1; a.v0 = 1; }
         a.chunked = ((c->variant == SSGD_K_SYNC || c->variant == SSGD_K_BATCH_SYNC) && a.mp * c->Kcap > 64) ? 1 : 0;
-        tile = linear_tile_supports(a, c->Kcap);
+        tile = tile && linear_tile_supports(a, c->Kcap);
+        defer = defer && linear_defer_supports(a);
     }
-    if (!tile && c->variant == SSGD_K_BATCH_ASYNC) return fail(c, SSGD_EINVAL, "K-batch-async: the cluster of this shape does not fit the device");
-    if (!tile) return launch_steps(c, v0, n, agg_out, false, events);
+    if (!tile && !defer && c->variant == SSGD_K_BATCH_ASYNC) return fail(c, SSGD_EINVAL, "K-batch-async: the cluster of this shape does not fit the device");
+    if (!tile && !defer) return launch_steps(c, v0, n, agg_out, kGeneralKernel, events);
     if (head > 0) {
-        ssgd_status st = launch_steps(c, v0, std::min(head, n), agg_out, false, events);
+        ssgd_status st = launch_steps(c, v0, std::min(head, n), agg_out, kGeneralKernel, events);
         if (st != SSGD_OK) return st;
     }
-    if (n > head) return launch_steps(c, v0 + head, n - head, agg_out, true, events);
+    if (n > head) return launch_steps(c, v0 + head, n - head, agg_out, defer ? kDeferKernel : kTileKernel, events);
     return SSGD_OK;
 }
 
@@ -487,6 +530,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         { hipDeviceProp_t prop; HIP_C(hipGetDeviceProperties(&prop, c->device)); c->cu_count = prop.multiProcessorCount; }
         if (c->nbw == 4 && C <= 15 && linear_tile_lds_bytes(C, c->S) <= 160 * 1024)
             c->tile_resident_groups = linear_tile_resident_groups(linear_tile_lds_bytes(C, c->S));
+        if (c->nbw == 4 && C <= 15 && variant == SSGD_K_ASYNC && c->S <= 8 && linear_defer_lds_bytes(C, c->S) <= 160 * 1024)
+            c->defer_per_launch = linear_defer_replicas_per_launch(c->G, c->cu_count);
         HIP_C(c->params.alloc(sizeof(float) * R * c->nw));
         HIP_C(hipMemsetAsync(c->params.p, 0, sizeof(float) * R * c->nw, c->stream));
         const size_t park_n = (size_t)R * c->G * c->S * 16 * SL;
@@ -496,11 +541,13 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         HIP_C(hipMemsetAsync(c->park_small.p, 0, sizeof(float) * R * c->G * c->S * 17, c->stream));
         HIP_C(c->zpart.alloc(sizeof(float) * R * 2 * c->G * c->maxrows * 16));
         HIP_C(c->zx.alloc(sizeof(uint32_t) * 3 * 1024 * (size_t)R * c->G));
-        HIP_C(c->xcc_ids.alloc(sizeof(int32_t) * R * c->G));
-        HIP_C(hipMemsetAsync(c->xcc_ids.p, 0xFF, sizeof(int32_t) * R * c->G, c->stream));
+        HIP_C(c->dx.alloc(sizeof(uint32_t) * 3 * 1024 * (size_t)R));
+        HIP_C(c->fallback.alloc(sizeof(int32_t) * (size_t)R));
+        HIP_C(c->xcc_ids.alloc(sizeof(int32_t) * R * (c->G + 1)));
+        HIP_C(hipMemsetAsync(c->xcc_ids.p, 0xFF, sizeof(int32_t) * R * (c->G + 1), c->stream));
         if (getenv("SSGD_PHASE_PROFILE")) {
-            HIP_C(c->prof.alloc(sizeof(unsigned long long) * R * c->G * 22));
-            HIP_C(hipMemsetAsync(c->prof.p, 0, sizeof(unsigned long long) * R * c->G * 22, c->stream));
+            HIP_C(c->prof.alloc(sizeof(unsigned long long) * (R * c->G * 22 + R)));
+            HIP_C(hipMemsetAsync(c->prof.p, 0, sizeof(unsigned long long) * (R * c->G * 22 + R), c->stream));
         }
         HIP_C(c->arrive.alloc(sizeof(unsigned int) * kArriveStride * R));
         HIP_C(hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * R, c->stream));
@@ -889,12 +936,15 @@ void ssgd_destroy(ssgd_ctx* c) {
     if (c->prof.p) {
         // diagnostics requested through SSGD_PHASE_PROFILE=a,b[,wave]: mean cycles per update between mark a and the
         // next mark b of one wave per workgroup (marks below 16: compute waves, from 16: loader waves)
-        std::vector<unsigned long long> h((size_t)c->R * c->G * 2);
+        std::vector<unsigned long long> h((size_t)c->R * c->G * 2 + (size_t)c->R);
         if (hipMemcpy(h.data(), c->prof.as<unsigned long long>() + (size_t)c->R * c->G * 20, h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost) == hipSuccess && c->j > 0) {
-            double tot[2] = {0, 0};
-            for (size_t q = 0; q < h.size(); ++q) tot[q % 2] += (double)h[q];
-            fprintf(stderr, "ssgd phase profile %s: %.0f cycles per update and workgroup\n", getenv("SSGD_PHASE_PROFILE"),
-                    (tot[0] + tot[1]) / ((double)c->R * c->G * (double)c->j));
+            double tot[2] = {0, 0}, helper = 0;
+            const size_t nslice = (size_t)c->R * c->G * 2;
+            for (size_t q = 0; q < nslice; ++q) tot[q % 2] += (double)h[q];
+            for (size_t q = nslice; q < h.size(); ++q) helper += (double)h[q];
+            // marks from 32 on belong to the helper workgroups (one per replica) of the kernel that has them
+            const double per = helper > 0 ? helper / ((double)c->R * (double)c->j) : (tot[0] + tot[1]) / ((double)c->R * c->G * (double)c->j);
+            fprintf(stderr, "ssgd phase profile %s: %.0f cycles per update and workgroup\n", getenv("SSGD_PHASE_PROFILE"), per);
         }
     }
     if (c->xcc_ids.p && getenv("SSGD_DEBUG")) {
@@ -914,7 +964,7 @@ void ssgd_destroy(ssgd_ctx* c) {
     if (c->side) (void)hipStreamDestroy(c->side);
     DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,
                       &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx, &c->ws_F0,
-                      &c->ws_intstart, &c->ws_crossed, &c->ws_ndone, &c->params, &c->park, &c->park_small, &c->zpart, &c->zx,
+                      &c->ws_intstart, &c->ws_crossed, &c->ws_ndone, &c->params, &c->park, &c->park_small, &c->zpart, &c->zx, &c->dx, &c->fallback,
                       &c->arrive, &c->abort_flag, &c->xcc_ids, &c->prof};
     for (DevBuf* b : bufs) b->release();
     delete c;

@@ -86,12 +86,14 @@ struct LinArgs {
     float* zpart;            // [R][2][G][maxrows][16] partial logits exchanged inside a cluster
     int32_t maxrows;
     uint32_t* zx;            // [R][3][G][64][16] exchange of the steady-state kernel: every word 0xFFFFFFFF until written
+    uint32_t* dx;            // [R][3][64][16] delta on its way from a cluster's helper workgroup to its slices, same convention
+    int32_t* fallback;       // [R] set by a cluster that does not sit on one XCD: the replica was left untouched
     unsigned int* arrive;    // [R][kArriveStride] arrival counters of the cluster exchange, zero at launch:
                              // word 0 fenced exchanges, word kArriveFast shared-L2 exchanges (a cache line each)
     int32_t* abort_flag;
     uint32_t spin_limit;
     float* agg_out;          // nullable: averaged gradient of the last update of replica 0
-    int32_t* xcc_ids;        // [R][G] XCD each workgroup of a cluster runs on (checked on the device)
+    int32_t* xcc_ids;        // [R][G + 1] XCD each workgroup of a cluster runs on (checked on the device); kernels without a helper use [R][G]
     int32_t allow_fast;      // 1: exchange through the shared L2 once a cluster is known to sit on one XCD
     // Steady-state kernel, full launches only: CUs per XCD and resident workgroups per CU.  When set, the
     // workgroup slots of an XCD are dealt out so that the clusters that share CUs share all of them in pairs
@@ -102,7 +104,9 @@ struct LinArgs {
     // with the memory operations of the one it shares the CU with.
     int32_t shared_cus;
     int32_t prof_wave, prof_a, prof_b;   // diagnostics: wave and the pair of marks of the phase profile
+    int32_t debug_flags;                 // diagnostics (timing experiments; results are wrong): bit 0 skips the row gathers
     int64_t prof_base;                   // first word of the steady-state kernel's part of prof
+    int64_t prof_helper;                 // offset, from prof_base, of the helper workgroups' words (one per replica)
     // Steady-state kernel: 1 for a synchronous variant whose iteration does not fit one 64-row tile.  The rows of the
     // K mini-batches are then taken 64 at a time, each tile through the whole forward / exchange / backward schedule,
     // the gradient summed over the tiles and the update applied after the last one.
@@ -118,6 +122,12 @@ bool linear_tile_supports(const LinArgs& a, int max_records);
 size_t linear_tile_lds_bytes(int C, int S);
 int linear_tile_resident_groups(size_t lds_bytes);
 hipError_t launch_linear_tile(const LinArgs& a, hipStream_t s);
+// Steady-state kernel of K-async with at most 8 workers (linear_defer.hip): one workgroup per CU, the gradients in
+// flight in LDS, the gradient contraction of a tile one version behind its forward pass.  Same state layout.
+bool linear_defer_supports(const LinArgs& a);
+size_t linear_defer_lds_bytes(int C, int S);
+int linear_defer_replicas_per_launch(int G, int cus);
+hipError_t launch_linear_defer(const LinArgs& a, hipStream_t s);
 
 // Gradient of that objective (full_grad.hip): `scratch` holds full_grad_scratch_floats floats, `out` |w| floats (device).
 bool full_grad_supports(int kind, int d, int C);
