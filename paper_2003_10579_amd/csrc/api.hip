@@ -200,7 +200,7 @@ ssgd_status launch_steps(ssgd_ctx* c, int64_t v0, int64_t n, float* agg_out, int
     HIP_OK(c, hipMemsetAsync(c->arrive.p, 0, sizeof(unsigned int) * kArriveStride * c->R, c->stream));
     if (tile) HIP_OK(c, hipMemsetAsync(c->zx.p, 0xFF, sizeof(uint32_t) * 3 * 1024 * (size_t)c->R * c->G, c->stream));
     if (mode == kDeferKernel) {
-        HIP_OK(c, hipMemsetAsync(c->dx.p, 0xFF, sizeof(uint32_t) * 3 * 1024 * (size_t)c->R, c->stream));
+        HIP_OK(c, hipMemsetAsync(c->dx.p, 0xFF, sizeof(uint32_t) * 4 * 1024 * (size_t)c->R, c->stream));
         HIP_OK(c, hipMemsetAsync(c->fallback.p, 0, sizeof(int32_t) * (size_t)c->R, c->stream));
     }
     if (getenv("SSGD_DEBUG"))
@@ -541,7 +541,7 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         HIP_C(hipMemsetAsync(c->park_small.p, 0, sizeof(float) * R * c->G * c->S * 17, c->stream));
         HIP_C(c->zpart.alloc(sizeof(float) * R * 2 * c->G * c->maxrows * 16));
         HIP_C(c->zx.alloc(sizeof(uint32_t) * 3 * 1024 * (size_t)R * c->G));
-        HIP_C(c->dx.alloc(sizeof(uint32_t) * 3 * 1024 * (size_t)R));
+        HIP_C(c->dx.alloc(sizeof(uint32_t) * 4 * 1024 * (size_t)R));
         HIP_C(c->fallback.alloc(sizeof(int32_t) * (size_t)R));
         HIP_C(c->xcc_ids.alloc(sizeof(int32_t) * R * (c->G + 1)));
         HIP_C(hipMemsetAsync(c->xcc_ids.p, 0xFF, sizeof(int32_t) * R * (c->G + 1), c->stream));

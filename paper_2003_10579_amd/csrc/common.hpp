@@ -86,7 +86,7 @@ struct LinArgs {
     float* zpart;            // [R][2][G][maxrows][16] partial logits exchanged inside a cluster
     int32_t maxrows;
     uint32_t* zx;            // [R][3][G][64][16] exchange of the steady-state kernel: every word 0xFFFFFFFF until written
-    uint32_t* dx;            // [R][3][64][16] delta on its way from a cluster's helper workgroup to its slices, same convention
+    uint32_t* dx;            // [R][4][64][16] delta on its way from a cluster's helper workgroup to its slices, same convention
     int32_t* fallback;       // [R] set by a cluster that does not sit on one XCD: the replica was left untouched
     unsigned int* arrive;    // [R][kArriveStride] arrival counters of the cluster exchange, zero at launch:
                              // word 0 fenced exchanges, word kArriveFast shared-L2 exchanges (a cache line each)

@@ -65,13 +65,6 @@ __device__ __forceinline__ float quad_lane0(float x) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x00, 0xF, 0xF, false));   // quad_perm [0,0,0,0]
 }
 
-__device__ __forceinline__ void lds_barrier() {
-    // orders LDS traffic only: outstanding global loads and stores stay in flight
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 // a wave gives up its wait: the launch is aborted (every workgroup of every cluster sees the flag in its own waits)
 __device__ __forceinline__ bool give_up(const LinArgs& a, uint32_t spins) {
     return spins > a.spin_limit ||
@@ -128,9 +121,39 @@ struct ListReader {
     }
 };
 
+// Spins until the LDS counter has reached `target`; false if the launch was given up meanwhile.
+__device__ __forceinline__ bool wait_count(const LinArgs& a, int* ctl, int which, int target) {
+    uint32_t spins = 0;
+    while (__builtin_amdgcn_readfirstlane(__hip_atomic_load(ctl + which, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP)) < target) {
+        __builtin_amdgcn_s_sleep(1);
+        ++spins;
+        if ((spins & 255u) == 0) {
+            if (__builtin_amdgcn_readfirstlane(__hip_atomic_load(ctl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) != 0) return false;
+            if ((spins >> 8) > a.spin_limit || __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                if ((threadIdx.x & 63) == 0) {
+                    __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(ctl, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                return false;
+            }
+        }
+    }
+    return true;
+}
+__device__ __forceinline__ void bump(int* ctl, int which) {
+    if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_add(ctl + which, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // ============================================================================================================
-// Helper workgroup (256 threads): thread -> row tid / 4 of the tile, classes 4 (tid % 4) .. + 3.
-// LDS: colsum[2][4][16], bias[16], small[S][17].
+// Helper workgroup: four softmax waves (thread -> row tid / 4 of the tile, classes 4 (tid % 4) .. + 3) and one
+// clerk wave.  The softmax waves do nothing but what the slices wait for: poll the partial logits, add them, take
+// residual / softmax with the bias and the labels that the clerk has put into LDS, store delta, and leave the column
+// sums of delta (bias gradient, loss) in LDS for the clerk.  The clerk wave (lane -> row of the tile for the labels,
+// lane -> class for the sums) reads the schedule, draws the sample ids and fetches the labels of the next version,
+// keeps the bias and the bias gradients in flight, and writes the loss record.  They meet through two LDS counters:
+//   sums   += 1 by every softmax wave once its column sums of version s are in LDS    (complete at 4 (s + 1))
+//   meta    = s + 1 by the clerk once bias and labels of version s are in LDS
+// LDS: colsum[2][4][16], biasbuf[2][16], labbuf[2][64], small[S][17], counters.
 // ============================================================================================================
 template <int KIND, bool PROF>
 __device__ __forceinline__ void helper_role(const LinArgs& a, int rep, unsigned char* smem) {
@@ -139,38 +162,19 @@ __device__ __forceinline__ void helper_role(const LinArgs& a, int rep, unsigned 
     const int d = a.d, C = a.C, m = a.m, mp = a.mp, S = a.S, G = a.G;
     const int64_t cap = a.tr.cap;
     float* colsum = reinterpret_cast<float*>(smem);          // [2][4][16], per step parity
-    float* bias = colsum + 128;                              // [16]
-    float* small = bias + 16;                                // [S][17]
+    float* biasbuf = colsum + 128;                           // [2][16]
+    uint32_t* labbuf = reinterpret_cast<uint32_t*>(biasbuf + 32);   // [2][64] label (or target) bits; kNoRow: no sample in this row
+    int* cnt = reinterpret_cast<int*>(labbuf + 128);         // [4]: 0 stop, 1 sums, 2 meta
+    float* small = reinterpret_cast<float*>(cnt + 4);        // [S][17]
+    constexpr int kSums = 1, kMeta = 2;
     const int64_t nw = (KIND == kLsq) ? d : (int64_t)C * d + C;
     float* params = a.params + (int64_t)rep * nw;
     float* small_g = a.park_small + (int64_t)rep * G * S * 17;      // slice 0's copy is read; every slice's is written back
-    if (tid < 16) bias[tid] = (KIND == kSoftmax && tid < C) ? params[(int64_t)C * d + tid] : 0.0f;
-    for (int q = tid; q < S * 17; q += NTC) small[q] = small_g[q];
+    for (int q = tid; q < S * 17; q += 5 * 64) small[q] = small_g[q];
+    if (tid < 4) cnt[tid] = 0;
     __syncthreads();
 
-    const int nquad = (C + 3) / 4;
-    const int z_row = tid >> 2, z_qd = tid & 3;
-    const int z_load_off = (z_qd < nquad) ? (z_row * 16 + 4 * z_qd) * 4 : kOutOfRange;
-    // delta goes out as [row % 4][class][row / 4]: the slices read it as the first operand of their MFMAs, where a lane
-    // takes one class of rows 4 kk + lane / 16 for all sixteen kk
-    const int dT_off = (((z_row & 3) * 16 + 4 * z_qd) * 16 + (z_row >> 2)) * 4;      // class 4 z_qd; + 64 bytes per class
-    const float inv_m = 1.0f / (float)m;
-    const __amdgpu_buffer_rsrc_t ersrc = make_rsrc(a.zx + (int64_t)rep * 3 * G * 1024, (uint32_t)(3u * G * 4096u));
-    const __amdgpu_buffer_rsrc_t drsrc = make_rsrc(a.dx + (int64_t)rep * 3 * 1024, 3u * 4096u);
-    const int rec_of = z_row / mp, smp_of = z_row % mp;
-
-    ListReader lists{a.tr.sel + (int64_t)rep * cap * a.tr.Kcap, a.tr.tau + (int64_t)rep * cap * a.tr.Kcap, a.tr.Kcap, lane};
-    TileMeta cur, nxt;
-    // label (or target) of this thread's row of the tile of version `ver`
-    auto row_label = [&](const TileMeta& t, int64_t ver, bool& ok) -> float {
-        const int worker = __shfl(t.worker, min(rec_of, 63), 64);
-        ok = smp_of < m && rec_of < t.nrec;
-        if (!ok) return 0.0f;
-        const uint32_t row_id = batch_index(a.seed, (uint32_t)rep, (uint32_t)worker, 0u, (uint32_t)ver, (uint32_t)smp_of, a.N);
-        return (KIND == kLsq) ? reinterpret_cast<const float*>(a.y)[row_id]
-                              : __int_as_float(reinterpret_cast<const int32_t*>(a.y)[row_id]);
-    };
-    uint32_t h_acc = 0, h_t0 = 0;            // diagnostics: cycles between two marks (numbered from 32) of wave 0
+    uint32_t h_acc = 0, h_t0 = 0;            // diagnostics: cycles between two marks (numbered from 32) of one wave
     auto hmark = [&](int q) {
         if constexpr (PROF) {
             if (wave == a.prof_wave) {
@@ -179,15 +183,100 @@ __device__ __forceinline__ void helper_role(const LinArgs& a, int rep, unsigned 
             }
         }
     };
-    lists.start(a.v0);
-    lists.take(cur, a.v0, a.nsteps > 1);
-    bool ok_cur = false, ok_nxt = false;
-    float lab_cur = row_label(cur, a.v0, ok_cur), lab_nxt = 0.0f;
-    // this thread's four bias values live in registers; every thread of a class quad applies the same updates to them
-    f32x4 b4 = {bias[4 * z_qd], bias[4 * z_qd + 1], bias[4 * z_qd + 2], bias[4 * z_qd + 3]};
+    auto hprof_out = [&]() {
+        if constexpr (PROF) {
+            if (wave == a.prof_wave && lane == 0) a.prof[(int64_t)a.prof_base + (int64_t)a.prof_helper + rep] += h_acc;
+        }
+    };
 
-    // The partial logits of this thread's row from the slices of one batch (up to 12), 16 bytes each.  They are asked
-    // for as early as possible: the loads travel while the bookkeeping of the step before is done.
+    if (wave == 4) {
+        // ===================================== clerk =====================================
+        ListReader lists{a.tr.sel + (int64_t)rep * cap * a.tr.Kcap, a.tr.tau + (int64_t)rep * cap * a.tr.Kcap, a.tr.Kcap, lane};
+        TileMeta cur, nxt;
+        const int rec_of = lane / mp, smp_of = lane % mp;          // tile row `lane` is sample smp_of of record rec_of
+        // label (or target) bits of tile row `lane` of version `ver`; leaves the load in flight
+        auto row_label = [&](const TileMeta& t, int64_t ver) -> uint32_t {
+            const int worker = __shfl(t.worker, min(rec_of, 63), 64);
+            if (!(smp_of < m && rec_of < t.nrec)) return kNoRow;
+            const uint32_t row_id = batch_index(a.seed, (uint32_t)rep, (uint32_t)worker, 0u, (uint32_t)ver, (uint32_t)smp_of, a.N);
+            return reinterpret_cast<const uint32_t*>(a.y)[row_id];
+        };
+        float bias_c = (KIND == kSoftmax && lane < C) ? params[(int64_t)C * d + lane] : 0.0f;     // lane c: bias of class c
+        lists.start(a.v0);
+        lists.take(cur, a.v0, a.nsteps > 1);
+        labbuf[lane] = row_label(cur, a.v0);
+        if (lane < 16) biasbuf[lane] = bias_c;
+        if (lane == 0) __hip_atomic_store(cnt + kMeta, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int gpr = mp >> 4;                       // groups of 16 rows per mini-batch
+        for (int64_t step = 0; step < a.nsteps; ++step) {
+            const int64_t v = a.v0 + step;
+            const int par = (int)(step & 1);
+            hmark(0);
+            // the next version's lists and labels: asked for before the wait, stored after it
+            uint32_t lab_nxt = kNoRow;
+            if (step + 1 < a.nsteps) {
+                lists.take(nxt, v + 1, step + 2 < a.nsteps);
+                lab_nxt = row_label(nxt, v + 1);
+            }
+            hmark(1);
+            if (!wait_count(a, cnt, kSums, (int)(4 * (step + 1)))) return;      // the column sums of version v are complete
+            hmark(2);
+            // Bias gradient (classes 0..C-1) and mean loss (class 15) of every mini-batch of the tile: summed over the
+            // consume list of update v like the weight gradients, or parked in the worker's slot.  Lane c takes class c.
+            {
+                const int c = lane & 15;
+                const int sidx = (c == 15) ? 16 : c;          // the slot record keeps the loss in word 16
+                float tot = 0.0f;
+                for (int i = 0; i < cur.nstale; ++i) {
+                    // entry i of the compact list of parked gradients: the lane whose stale_pos is i holds its slot
+                    const unsigned long long who = __ballot(cur.stale_pos == i);
+                    const int slot = __builtin_amdgcn_readlane(cur.stale, (int)__builtin_ctzll(who | (1ull << 63)));
+                    tot += small[slot * 17 + sidx];
+                }
+                for (int r = 0; r < cur.nrec; ++r) {
+                    float prt = 0.0f;
+                    for (int g = 0; g < gpr; ++g) prt += colsum[par * 64 + (r * gpr + g) * 16 + c];
+                    const int word = __builtin_amdgcn_readlane(cur.rec_word, r);
+                    if ((word >> 16) != 0) tot += prt;
+                    else if (lane < 16) small[(word & 0xFFFF) * 17 + sidx] = prt;
+                }
+                const float invK = 1.0f / (float)cur.K;
+                if (KIND == kSoftmax && lane < C) bias_c -= (a.lr * invK) * tot;
+                if (lane == 15) a.tr.loss[(int64_t)rep * cap + v] = tot * invK;
+                // the averaged gradient of replica 0, when the caller asked for it: bias part
+                if (KIND == kSoftmax && a.agg_out != nullptr && rep == 0 && lane < C) a.agg_out[(int64_t)C * d + lane] = tot * invK;
+            }
+            hmark(3);
+            if (step + 1 < a.nsteps) {
+                // (the softmax waves are done with the buffers of version v - 1, which version v + 1 takes over: they
+                // read them before they left their column sums of version v - 1, let alone v)
+                labbuf[(1 - par) * 64 + lane] = lab_nxt;
+                if (lane < 16) biasbuf[(1 - par) * 16 + lane] = bias_c;
+                if (lane == 0) __hip_atomic_store(cnt + kMeta, (int)(step + 2), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            cur = nxt;
+            hmark(4);
+        }
+        hprof_out();
+        // ---- leave the state in HBM for the next launch (every slice's copy of the bias gradients in flight)
+        if (KIND == kSoftmax && lane < C) params[(int64_t)C * d + lane] = bias_c;
+        for (int g = 0; g < G; ++g)
+            for (int q = lane; q < S * 17; q += 64) small_g[(int64_t)g * S * 17 + q] = small[q];
+        return;
+    }
+
+    // ===================================== softmax waves =====================================
+    const int nquad = (C + 3) / 4;
+    const int z_row = tid >> 2, z_qd = tid & 3;
+    const int z_load_off = (z_qd < nquad) ? (z_row * 16 + 4 * z_qd) * 4 : kOutOfRange;
+    // delta goes out as [row % 4][class][row / 4]: the slices read it as the first operand of their MFMAs, where a lane
+    // takes one class of rows 4 kk + lane / 16 for all sixteen kk
+    const int dT_off = (((z_row & 3) * 16 + 4 * z_qd) * 16 + (z_row >> 2)) * 4;      // class 4 z_qd; + 64 bytes per class
+    const float inv_m = 1.0f / (float)m;
+    const __amdgpu_buffer_rsrc_t ersrc = make_rsrc(a.zx + (int64_t)rep * 3 * G * 1024, (uint32_t)(3u * G * 4096u));
+    const __amdgpu_buffer_rsrc_t drsrc = make_rsrc(a.dx + (int64_t)rep * 4 * 1024, 4u * 4096u);
+
+    // The partial logits of this thread's row from the slices of one batch (up to 12), 16 bytes each.
     u32x4v part[12];
     auto ask = [&](int buf, int g0) {
         const int xbase = buf * G * 4096;
@@ -196,22 +285,13 @@ __device__ __forceinline__ void helper_role(const LinArgs& a, int rep, unsigned 
             part[i] = __builtin_amdgcn_raw_buffer_load_b128(ersrc, z_load_off, xbase + min(g0 + i, G - 1) * 4096, kAgentLoad);
     };
     ask(0, 0);
-
     for (int64_t step = 0; step < a.nsteps; ++step) {
-        const int64_t v = a.v0 + step;
         const int buf = (int)(step % 3);
         const int par = (int)(step & 1);
         hmark(0);
-        // ---- what the next step needs, while the first look at this step's partial logits is on its way
-        if (step + 1 < a.nsteps) {
-            lists.take(nxt, v + 1, step + 2 < a.nsteps);
-            lab_nxt = row_label(nxt, v + 1, ok_nxt);
-        }
-        hmark(1);
         // ---- full logits of row z_row: the partial logits of the G slices, polled until none of the words is the
         //      sentinel, added in slice order
         f32x4 zz = {0.f, 0.f, 0.f, 0.f};
-        bool lost = false;
         {
             uint32_t spins = 0;
             for (int g0 = 0; g0 < G; g0 += 12) {
@@ -224,81 +304,92 @@ __device__ __forceinline__ void helper_role(const LinArgs& a, int rep, unsigned 
                     if (__ballot(top == kSentinel) == 0ull) break;
                     ++spins;
                     if (give_up(a, spins)) {
-                        if (lane == 0) __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        lost = true;
-                        break;
+                        if (lane == 0) {
+                            __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __hip_atomic_store(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        }
+                        return;
                     }
                     ask(buf, g0);
                 }
-                if (lost) break;
 #pragma unroll
                 for (int i = 0; i < 12; ++i)
                     if (g0 + i < G) zz += __builtin_bit_cast(f32x4, part[i]);
             }
         }
-        hmark(2);
-        // ---- The buffer that the next version's delta will use is re-armed now.  It holds the delta of two versions
-        //      ago; every slice has stored its partial logits of this version, which it does after it has taken the
-        //      delta of the version before into registers, so neither of the two older buffers is read any more.
-        //      The stores travel while the softmax is computed and are waited for before this version's delta goes out.
-        if (!lost) {
+        // everything this wave has stored so far (the re-arming stores of the version before among it) is in the L2;
+        // those stores are a whole version old, so this costs nothing
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        hmark(1);
+        // ---- The delta buffer of two versions on is re-armed.  It holds the delta of two versions ago; every slice
+        //      has stored its partial logits of this version, which it does after it has taken the delta of the
+        //      version before into registers, so that buffer is read no more.  No wait is needed here: this wave's
+        //      next data store to these words is two versions away, and before the slices look at them they have seen
+        //      the delta of the next version, which goes out after a wait for this wave's loads that covers the
+        //      stores issued now (loads and stores share the wave's counter).
+        {
             uint32_t sv = kSentinel;
             asm volatile("" : "+v"(sv));
 #pragma unroll
-            for (int e = 0; e < 4; ++e) __builtin_amdgcn_raw_buffer_store_b32(sv, drsrc, dT_off + 64 * e, (int)((step + 1) % 3) * 4096, 0);
+            for (int e = 0; e < 4; ++e) __builtin_amdgcn_raw_buffer_store_b32(sv, drsrc, dT_off + 64 * e, (int)((step + 2) % 4) * 4096, 0);
         }
+        // ---- bias and labels of this version (the clerk has had a whole version's time for them)
+        if (!wait_count(a, cnt, kMeta, (int)(step + 1))) return;
+        const uint32_t lab_bits = labbuf[par * 64 + z_row];
+        const f32x4 b4 = *reinterpret_cast<const f32x4*>(biasbuf + par * 16 + 4 * z_qd);
+        const bool ok = lab_bits != kNoRow;
         // ---- residual / softmax.  The slices wait for delta: it is stored as soon as it is known, the row loss (which
         //      needs a logarithm) follows.
         f32x4 dl = {0.f, 0.f, 0.f, 0.f};
         float loss = 0.0f;
         float s_den = 1.0f, s_lt = 0.0f;
-        {
-            const bool ok = ok_cur;
-            if constexpr (KIND == kLsq) {
-                const float z0 = quad_lane0(zz.x);
-                const float r = z0 - lab_cur;
-                if (ok) loss = 0.5f * r * r;
-                if (z_qd == 0 && ok) dl.x = r * inv_m;
-            } else {
-                const int lab = __float_as_int(lab_cur);
-                float zmax = -3.0e38f;
+        if constexpr (KIND == kLsq) {
+            const float z0 = quad_lane0(zz.x);
+            const float r = z0 - __uint_as_float(lab_bits);
+            if (ok) loss = 0.5f * r * r;
+            if (z_qd == 0 && ok) dl.x = r * inv_m;
+        } else {
+            const int lab = (int)lab_bits;
+            float zmax = -3.0e38f;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    zz[e] += b4[e];
-                    if (4 * z_qd + e < C) zmax = fmaxf(zmax, zz[e]);
-                }
-                zmax = fmaxf(zmax, quad_xor1(zmax));
-                zmax = fmaxf(zmax, quad_xor2(zmax));
-                float den = 0.0f, lt_ = 0.0f;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float ex = (4 * z_qd + e < C) ? expf(zz[e] - zmax) : 0.0f;
-                    den += ex;
-                    if (4 * z_qd + e == lab) lt_ = -(zz[e] - zmax);
-                    dl[e] = ex;
-                }
-                den += quad_xor1(den);
-                den += quad_xor2(den);
-                const float inv = 1.0f / den;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float pr = dl[e] * inv - ((4 * z_qd + e == lab) ? 1.0f : 0.0f);
-                    dl[e] = (ok && 4 * z_qd + e < C) ? pr * inv_m : 0.0f;
-                }
-                s_den = den; s_lt = lt_;
+            for (int e = 0; e < 4; ++e) {
+                zz[e] += b4[e];
+                if (4 * z_qd + e < C) zmax = fmaxf(zmax, zz[e]);
             }
+            zmax = fmaxf(zmax, quad_xor1(zmax));
+            zmax = fmaxf(zmax, quad_xor2(zmax));
+            float den = 0.0f, lt_ = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float ex = (4 * z_qd + e < C) ? expf(zz[e] - zmax) : 0.0f;
+                den += ex;
+                if (4 * z_qd + e == lab) lt_ = -(zz[e] - zmax);
+                dl[e] = ex;
+            }
+            den += quad_xor1(den);
+            den += quad_xor2(den);
+            const float inv = 1.0f / den;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float pr = dl[e] * inv - ((4 * z_qd + e == lab) ? 1.0f : 0.0f);
+                dl[e] = (ok && 4 * z_qd + e < C) ? pr * inv_m : 0.0f;
+            }
+            s_den = den; s_lt = lt_;
         }
         // ---- delta goes out.  (Class 15 of a row, which does not exist, will carry the row loss in this workgroup's
         //      column sums; the slices get a zero there.)
-        if (!lost) {
+        {
             u32x4v ob = __builtin_bit_cast(u32x4v, dl);
 #pragma unroll
             for (int c = 0; c < 4; ++c) ob[c] = (ob[c] == kSentinel) ? 0x7FC00000u : ob[c];   // a NaN that is not the sentinel
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the re-arming stores are in the L2
 #pragma unroll
-            for (int e = 0; e < 4; ++e) __builtin_amdgcn_raw_buffer_store_b32(ob[e], drsrc, dT_off + 64 * e, buf * 4096, 0);
+            for (int e = 0; e < 4; ++e) __builtin_amdgcn_raw_buffer_store_b32(ob[e], drsrc, dT_off + 64 * e, (int)(step % 4) * 4096, 0);
+        }
+        hmark(2);
+        {
             // this thread's words of the partial logits are re-armed for the exchange three versions on (a slice writes
-            // them again only after it has seen the delta of the next version, which goes out after the wait above)
+            // them again only after it has seen the delta of the next version, which goes out after a wait that covers
+            // these stores)
             uint32_t sv = kSentinel;
             asm volatile("" : "+v"(sv));
             const u32x4v arm = {sv, sv, sv, sv};
@@ -306,18 +397,17 @@ __device__ __forceinline__ void helper_role(const LinArgs& a, int rep, unsigned 
             // and the first look at the next version's partial logits is asked for
             if (step + 1 < a.nsteps) ask((int)((step + 1) % 3), 0);
         }
-        hmark(3);
-        // ---- the rest of this version, while those loads travel: row loss, column sums, bias, loss record
+        // ---- row loss and column sums for the clerk
         if constexpr (KIND == kSoftmax) {
             float lt_ = s_lt;
             lt_ += quad_xor1(lt_);
             lt_ += quad_xor2(lt_);
-            loss = ok_cur ? lt_ + logf(s_den) : 0.0f;
+            loss = ok ? lt_ + logf(s_den) : 0.0f;
         }
         // the unused class 15 carries the row loss: the column sums of delta then hold the bias gradient and the loss
         if (z_qd == 3) dl.w = loss * inv_m;
-        // column sums of delta over this wave's 16 rows (one group of 16 rows never straddles two mini-batches)
         {
+            // over this wave's 16 rows (one group of 16 rows never straddles two mini-batches)
             f32x4 cs = dl;
 #pragma unroll
             for (int o = 4; o < 64; o <<= 1) {
@@ -326,67 +416,10 @@ __device__ __forceinline__ void helper_role(const LinArgs& a, int rep, unsigned 
             }
             if (lane < 4) *reinterpret_cast<f32x4*>(colsum + par * 64 + wave * 16 + 4 * lane) = cs;
         }
-        hmark(4);
-        lds_barrier();
-        hmark(5);
-        // The launch was given up (by a wave of this workgroup, before the barrier above, or anywhere else): leave.
-        // A wave that has ended no longer counts at the barriers of the waves that go on for a moment.
-        if (__hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
-        // ---- Bias gradient (classes 0..C-1) and mean loss (class 15) of every mini-batch of the tile: summed over the
-        //      consume list of update v like the weight gradients, or parked in the worker's slot.  Every thread takes
-        //      the sums of its own four classes and steps its copy of the bias; wave 0 also writes the slots and the
-        //      loss record (a slot written now is read at the earliest after the next barrier).
-        {
-            const int gpr = mp >> 4;                       // groups of 16 rows per mini-batch
-            const float invK = 1.0f / (float)cur.K;
-            f32x4 tot = {0.f, 0.f, 0.f, 0.f};
-            for (int i = 0; i < cur.nstale; ++i) {
-                // entry i of the compact list of parked gradients: the lane whose stale_pos is i holds its slot
-                const unsigned long long who = __ballot(cur.stale_pos == i);
-                const int slot = __builtin_amdgcn_readlane(cur.stale, (int)__builtin_ctzll(who | (1ull << 63)));
-#pragma unroll
-                for (int e = 0; e < 4; ++e) tot[e] += small[slot * 17 + ((4 * z_qd + e == 15) ? 16 : 4 * z_qd + e)];
-            }
-            for (int r = 0; r < cur.nrec; ++r) {
-                f32x4 prt = {0.f, 0.f, 0.f, 0.f};
-                for (int g = 0; g < gpr; ++g) prt += *reinterpret_cast<const f32x4*>(colsum + par * 64 + (r * gpr + g) * 16 + 4 * z_qd);
-                const int word = __builtin_amdgcn_readlane(cur.rec_word, r);
-                if ((word >> 16) != 0) tot += prt;
-                else if (wave == 0 && lane < 4) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) small[(word & 0xFFFF) * 17 + ((4 * z_qd + e == 15) ? 16 : 4 * z_qd + e)] = prt[e];
-                }
-            }
-            if constexpr (KIND == kSoftmax) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) b4[e] -= (a.lr * invK) * tot[e];
-            }
-            if (wave == 0 && lane < 4) {
-                if (lane == 3) a.tr.loss[(int64_t)rep * cap + v] = tot.w * invK;      // class 15: the loss
-                // the averaged gradient of replica 0, when the caller asked for it: bias part
-                if (KIND == kSoftmax && a.agg_out != nullptr && rep == 0) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (4 * lane + e < C) a.agg_out[(int64_t)C * d + 4 * lane + e] = tot[e] * invK;
-                }
-            }
-        }
-        cur = nxt; ok_cur = ok_nxt; lab_cur = lab_nxt;
-        hmark(6);
+        bump(cnt, kSums);
+        hmark(3);
     }
-    if constexpr (PROF) {
-        if (wave == a.prof_wave && lane == 0) a.prof[(int64_t)a.prof_base + (int64_t)a.prof_helper + rep] += h_acc;
-    }
-    lds_barrier();
-    if (wave == 0 && lane < 4) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) bias[4 * lane + e] = b4[e];
-    }
-    lds_barrier();
-    // ---- leave the state in HBM for the next launch (every slice's copy of the bias gradients in flight)
-    if (KIND == kSoftmax && tid < C) params[(int64_t)C * d + tid] = bias[tid];
-    for (int g = 0; g < G; ++g)
-        for (int q = tid; q < S * 17; q += NTC) small_g[(int64_t)g * S * 17 + q] = small[q];
+    hprof_out();
 }
 
 // ============================================================================================================
@@ -419,29 +452,6 @@ __device__ __forceinline__ Lds carve(unsigned char* smem, int C, int S) {
     l.s_stale = l.stp + 8;
     l.s_rec = l.s_stale + 2 * SMAX;
     return l;
-}
-
-// Spins until the LDS counter has reached `target`; false if the launch was given up meanwhile.
-__device__ __forceinline__ bool wait_count(const LinArgs& a, int* ctl, int which, int target) {
-    uint32_t spins = 0;
-    while (__builtin_amdgcn_readfirstlane(__hip_atomic_load(ctl + which, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP)) < target) {
-        __builtin_amdgcn_s_sleep(1);
-        ++spins;
-        if ((spins & 255u) == 0) {
-            if (__builtin_amdgcn_readfirstlane(__hip_atomic_load(ctl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) != 0) return false;
-            if ((spins >> 8) > a.spin_limit || __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                if ((threadIdx.x & 63) == 0) {
-                    __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(ctl, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                }
-                return false;
-            }
-        }
-    }
-    return true;
-}
-__device__ __forceinline__ void bump(int* ctl, int which) {
-    if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_add(ctl + which, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 template <int KIND, bool PROF, int MPK>
@@ -606,9 +616,9 @@ __device__ __forceinline__ void slice_role(const LinArgs& a, int rep, int slice,
     if (L.ctl[0] != 0) return;
 
     // exchange: three buffers of G x 64 x 16 words (partial logits, written here) and three of 64 x 16 words (delta,
-    // written by the helper), used in turn; a word is the sentinel until it has been written
+    // written by the helper; four of those), used in turn; a word is the sentinel until it has been written
     const __amdgpu_buffer_rsrc_t ersrc = make_rsrc(a.zx + (int64_t)rep * 3 * G * 1024, (uint32_t)(3u * G * 4096u));
-    const __amdgpu_buffer_rsrc_t drsrc = make_rsrc(a.dx + (int64_t)rep * 3 * 1024, 3u * 4096u);
+    const __amdgpu_buffer_rsrc_t drsrc = make_rsrc(a.dx + (int64_t)rep * 4 * 1024, 4u * 4096u);
     // forward: rows 16 wave .. 16 wave + 15; row / class index of this lane in the MFMA operands
     const int f_row = 16 * wave + (lane & 15);
     const int f_key = min(lane & 15, C - 1);     // lanes of classes that do not exist read the last class
@@ -722,7 +732,7 @@ __device__ __forceinline__ void slice_role(const LinArgs& a, int rep, int slice,
         if (!wait_count(a, L.ctl, kStepped, (int)(4 * step))) return false;          // w_v is complete
         if (!wait_count(a, L.ctl, kReady, (int)(4 * (step + 1)))) return false;      // tile v is complete
         mark(0);
-        const int buf = (int)(step % 3);
+        const int buf = (int)(step % 3), dbuf = (int)(step % 4);
         const int4 stp4 = *reinterpret_cast<const int4*>(L.stp + Q * 4);
         const int Kv = __builtin_amdgcn_readfirstlane(stp4.x);
         const int n_rec = __builtin_amdgcn_readfirstlane(stp4.y);
@@ -806,15 +816,15 @@ __device__ __forceinline__ void slice_role(const LinArgs& a, int rep, int slice,
         if (fresh) {
             // update v consumes a mini-batch that started at w_v: its gradient cannot wait
             mark(12);
-            ask_delta(buf);
-            if (!await_delta(buf)) return false;
+            ask_delta(dbuf);
+            if (!await_delta(dbuf)) return false;
             mark(13);
             backward(xb[Q], rec_lane, n_rec, true);
         } else {
             pend = true;
             pend_words = rec_lane;
             pend_nrec = n_rec;
-            pend_buf = buf;
+            pend_buf = dbuf;
         }
         mark(5);
         // ---- update v: each compute thread owns its weights and keeps them in registers; the forward passes read the LDS copy
@@ -892,7 +902,7 @@ __global__ __launch_bounds__(512, 2) void linear_defer_kernel(LinArgs a) {
     if (cluster >= a.replicas) return;
     const int rep = a.replica0 + cluster;
     const bool helper = role == a.G;
-    if (helper && threadIdx.x >= NTC) return;      // the helper has four waves
+    if (helper && threadIdx.x >= 5 * 64) return;   // the helper has five waves
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int same_xcd;
@@ -960,7 +970,7 @@ hipError_t launch_d(const LinArgs& a, size_t lds, hipStream_t s) {
 
 size_t linear_defer_lds_bytes(int C, int S) {
     const size_t slice_words = (size_t)ROWS * SL + (size_t)C * SL + (size_t)S * C * SL + 4 + 8 + 4 * SMAX;
-    const size_t helper_words = 128 + 16 + (size_t)S * 17;
+    const size_t helper_words = 128 + 32 + 128 + 4 + (size_t)S * 17;
     return sizeof(float) * std::max(slice_words, helper_words);
 }
 
