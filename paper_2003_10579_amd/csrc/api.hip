@@ -332,11 +332,14 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
         sa.tr = c->tr; sa.ws = c->ws; sa.dist = c->dist; sa.seed = c->seed; sa.P = c->P; sa.variant = c->variant;
         sa.table_ord = c->table_ord; sa.replica0 = 0; sa.j0 = c->j; sa.count = seg;
         sa.interval_t = (c->ada.mode >= 2) ? c->ada.interval_t : 0.0;
-        // The schedule does not depend on the numerics (K changes only between segments here), so for the network, whose
-        // updates are separate launches, it is written piece by piece on a second stream while the gradient kernels of
-        // the piece before run: a single wavefront beside kernels that fill the chip.
-        constexpr int64_t kPiece = 64;
-        const bool pipelined = c->model.kind == SSGD_MLP2 && c->ada.mode < 2 && seg > kPiece;
+        // The schedule does not depend on the numerics (K changes only between segments here), so it is written piece by
+        // piece on a second stream while the gradient kernels of the piece before run: one wavefront per replica beside
+        // kernels that leave it room (the network's updates are separate launches; the steady-state kernel of K-async
+        // on the linear models leaves CUs free).  The pieces of the linear models are long: every piece is a launch of
+        // its own, which reads the gradients in flight from HBM and writes them back.
+        const bool linear_pipe = c->model.kind != SSGD_MLP2 && c->variant == SSGD_K_ASYNC && c->defer_per_launch >= 1 && agg_out == nullptr;
+        const int64_t kPiece = c->model.kind == SSGD_MLP2 ? 64 : 1024;
+        const bool pipelined = (c->model.kind == SSGD_MLP2 || linear_pipe) && c->ada.mode < 2 && seg > kPiece;
         if (pipelined) {
             if (!c->side) HIP_OK(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
             hipEvent_t before = nullptr;
@@ -353,16 +356,27 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
             }
             std::string msg;
             size_t k = 0;
-            for (int64_t off = 0; off < seg && e == hipSuccess; off += kPiece, ++k) {
+            ssgd_status lin_st = SSGD_OK;
+            for (int64_t off = 0; off < seg && e == hipSuccess && lin_st == SSGD_OK; off += kPiece, ++k) {
                 e = hipStreamWaitEvent(c->stream, written[k], 0);
-                if (e == hipSuccess)
+                if (e != hipSuccess) break;
+                if (c->model.kind == SSGD_MLP2)
                     e = mlp_run_segment(c->mlp, c->tr, c->ws, c->j + off, std::min(kPiece, seg - off), agg_out, c->stream,
                                         &c->last_ms, &c->last_launches, &msg);
+                else
+                    lin_st = run_segment_linear(c, c->j + off, std::min(kPiece, seg - off), agg_out, &events);
+            }
+            if (lin_st != SSGD_OK) {
+                (void)hipStreamSynchronize(c->side);
+                (void)hipEventDestroy(before);
+                for (hipEvent_t ev : written) (void)hipEventDestroy(ev);
+                c->broken = true;
+                return lin_st;
             }
             if (e != hipSuccess) (void)hipStreamSynchronize(c->side);
             (void)hipEventDestroy(before);
             for (hipEvent_t ev : written) (void)hipEventDestroy(ev);
-            if (e != hipSuccess) { c->broken = true; return fail(c, SSGD_EDEVICE, "mlp segment: " + (msg.empty() ? std::string(hipGetErrorString(e)) : msg)); }
+            if (e != hipSuccess) { c->broken = true; return fail(c, SSGD_EDEVICE, "pipelined segment: " + (msg.empty() ? std::string(hipGetErrorString(e)) : msg)); }
         } else {
             launch_schedule(sa, c->R, c->stream);
             HIP_OK(c, hipGetLastError());
