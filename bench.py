@@ -2,7 +2,7 @@
 
 Workload: the K-async softmax-regression configuration the metric is quoted on (d=3072, 10 classes,
 N=50000 Gaussian-mixture samples, P=8 virtual workers, m=32, K=2, shifted-exponential delays (0.5, 1),
-lr=0.05, J=5000 updates), run as R independent replicas in one launch.  A step is one pass of the whole
+lr=0.05, J=5000 updates), run as R independent replicas, 16 to a launch.  A step is one pass of the whole
 hot path: the schedule (delays, K-of-P selection, staleness) and all J updates (gather, gradients at
 stale parameters, aggregate, update) of every replica, with the data resident in HBM.
 """
@@ -40,22 +40,56 @@ def cpu_baseline(X, y, spec, budget_s=12.0):
             "mc_trials_per_s": 200 / dt_mc, "mc_sample": f"200 trials (P=128, K=1..128, chains of 8, Exp(1)), {dt_mc:.1f} s"}
 
 
-def measured_traffic(replicas, updates):
+KERNEL_SOURCES = ("linear_defer.hip", "linear_tile.hip", "common.hpp")
+
+
+def kernel_source_hash():
+    """sha256 over the sources of the kernels that the timed launches run."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2003_10579_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(replicas, updates, grads_per_launch):
     """HBM bytes per launch of the dominant kernel, from the committed counter summary (two rocprofv3 --pmc
-    runs of this script, scaled by a copy kernel); None when the summary was taken in another launch shape."""
-    path = os.path.join(ROOT, "profiles", "linear_tile_kernel_config1_hbm_traffic.txt")
+    runs of this script, scaled by a copy kernel).  None unless the summary was taken with the same replicas and
+    updates and from the kernel sources as they are now (the summary records their hash)."""
+    path = os.path.join(ROOT, "profiles", "linear_defer_kernel_config1_hbm_traffic.txt")
     try:
         rec = {}
         with open(path) as f:
             for line in f:
                 if line.startswith("bench:"):
                     k, v = line[len("bench:"):].split("=")
-                    rec[k.strip()] = float(v)
-        if int(rec["replicas"]) == replicas and int(rec["updates_per_launch"]) == updates:
-            return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+                    rec[k.strip()] = v.strip()
+        if (int(rec["replicas"]) == replicas and int(rec["updates"]) == updates
+                and rec["kernel_source_sha256"] == kernel_source_hash()):
+            return (float(rec["fetch_bytes_per_worker_gradient"]) + float(rec["write_bytes_per_worker_gradient"])) * grads_per_launch
     except (OSError, KeyError, ValueError):
         pass
     return None
+
+
+def config2_rate(ssgd, Xd, yd, replicas=40, updates=200):
+    """Config 2 (softmax K-batch-sync, P=64, m=128, K=16, Pareto(2.5, 1) delays) through the same library: worker-gradients
+    per second and the fraction of the HBM peak in algorithmic bytes."""
+    import torch
+    ctx = ssgd.Context("softmax", Xd, yd, 64, 16, 128, "k_batch_sync", ssgd.delay_dist("pareto", 2.5, 1.0), 0.05, seed=0,
+                       classes=10, replicas=replicas)
+    ctx.reserve_trace(2 * updates)
+    ctx.run(updates)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.run(updates)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.close()
+    rate = replicas * updates * 16 / dt
+    return {"workload": f"config 2: softmax K-batch-sync d=3072 P=64 m=128 K=16 Pareto(2.5,1), {updates} updates, {replicas} replicas",
+            "worker_gradients_per_s": rate, "frac_of_hbm_peak": rate * 128 * (3072 + 1) * 4 / 1e9 / HBM_PEAK_GBS}
 
 
 def mc_rate(ssgd):
@@ -73,7 +107,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--replicas", type=int, default=int(os.environ.get("SSGD_BENCH_REPLICAS", "40")))
+    ap.add_argument("--replicas", type=int, default=int(os.environ.get("SSGD_BENCH_REPLICAS", "48")))
     ap.add_argument("--updates", type=int, default=5000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -126,15 +160,15 @@ def main():
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config 1: softmax regression K-async, d=3072, 10 classes, N=50000, P=8, m=32, K=2, "
-                               f"shifted-exp(0.5,1), lr=0.05, J={J}, {R} independent replicas per launch",
+                               f"shifted-exp(0.5,1), lr=0.05, J={J}, {R} independent replicas (16 per launch)",
                    "replicas": R, "updates_per_step": J, "final_loss_replica0": loss,
                    "value_replicas_1": 1 * J * K / dt1},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "linear_tile_kernel<softmax>", "launches": kn, "avg_launch_ms": kms / kn,
+                     "kernel": "linear_defer_kernel<softmax>", "launches": kn, "avg_launch_ms": kms / kn,
                      "algorithmic_bytes_per_launch": per_launch_bytes},
     }
-    out["roofline"]["traffic"] = measured_traffic(R, J)
+    out["roofline"]["traffic"] = measured_traffic(R, J, grads / kn)
     # what a plain streaming read of the same data set reaches on this device, beside the published peak
     stream_gbs = ssgd.stream_read_rate(Xd, passes=10) / 1e9
     out["roofline"]["stream_read_GBps"] = stream_gbs
@@ -143,6 +177,7 @@ def main():
         # the counted HBM-side bytes (sample rows plus the round trip of the parked gradients) against the same ceiling
         out["roofline"]["traffic_GBps"] = out["roofline"]["traffic"] / (kms / kn * 1e-3) / 1e9
         out["roofline"]["traffic_frac_of_stream_read"] = out["roofline"]["traffic_GBps"] / stream_gbs
+    out["config"]["config2"] = config2_rate(ssgd, Xd, yd)
     out["config"]["mc_trials_per_s"] = mc_rate(ssgd)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(X, y, spec)
