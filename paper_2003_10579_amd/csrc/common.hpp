@@ -104,7 +104,7 @@ struct LinArgs {
     // with the memory operations of the one it shares the CU with.
     int32_t shared_cus;
     int32_t prof_wave, prof_a, prof_b;   // diagnostics: wave and the pair of marks of the phase profile
-    int32_t debug_flags;                 // diagnostics (timing experiments; results are wrong): bit 0 skips the row gathers
+    int32_t debug_flags;                 // test switches set by the host (SSGD_DEBUG_FLAGS): bit 1 makes the odd replicas take the path of a cluster spread over XCDs
     int64_t prof_base;                   // first word of the steady-state kernel's part of prof
     int64_t prof_helper;                 // offset, from prof_base, of the helper workgroups' words (one per replica)
     // Steady-state kernel: 1 for a synchronous variant whose iteration does not fit one 64-row tile.  The rows of the

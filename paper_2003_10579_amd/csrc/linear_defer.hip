@@ -502,14 +502,12 @@ __device__ __forceinline__ void slice_role(const LinArgs& a, int rep, int slice,
         };
         // Sample ids of the tile of version `ver`; leaves the gathers in flight.
         auto make_tile = [&](const TileMeta& t, f32x4 (&pf)[LLOADS], int64_t ver) {
-            if (a.debug_flags & 16) return;
             const int worker = __shfl(t.worker, min(r_of, 63), 64);
             uint32_t row_id = kNoRow;
             if (s_of < m && r_of < t.nrec)
                 row_id = batch_index(a.seed, (uint32_t)rep, (uint32_t)worker, 0u, (uint32_t)ver, (uint32_t)s_of, a.N);
             asm volatile("" : "+v"(row_id) : : "memory");
             __builtin_amdgcn_sched_barrier(0);
-            if (a.debug_flags & 1) return;
 #pragma unroll
             for (int i = 0; i < LLOADS; ++i) {
                 // rows without a sample read row 0; their delta is zero
@@ -519,10 +517,8 @@ __device__ __forceinline__ void slice_role(const LinArgs& a, int rep, int slice,
             }
         };
         auto publish = [&](const TileMeta& t, const f32x4 (&pf)[LLOADS], int par) {
-            if (!(a.debug_flags & 8)) {
 #pragma unroll
             for (int i = 0; i < LLOADS; ++i) *reinterpret_cast<f32x4*>(my_tile + 4 * i * SL) = pf[i];
-            }
             if (lw == 0) {
                 if (lane == 0) {
                     L.stp[par * 4 + 0] = t.K; L.stp[par * 4 + 1] = t.nrec; L.stp[par * 4 + 2] = t.nstale; L.stp[par * 4 + 3] = t.fresh;
@@ -931,7 +927,7 @@ __global__ __launch_bounds__(512, 2) void linear_defer_kernel(LinArgs a) {
         if (ok > 0) {
             for (int g = 0; g <= a.G; ++g)
                 if ((__hip_atomic_load(ids + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xFF) != my_xcc) ok = 0;
-            if ((a.debug_flags & 2) != 0 && (rep & 1) != 0) ok = 0;      // diagnostics: odd replicas pretend to be spread out
+            if ((a.debug_flags & 2) != 0 && (rep & 1) != 0) ok = 0;      // test switch of the host: odd replicas take the path of a spread cluster
         }
         same_xcd = ok;
     }

@@ -639,7 +639,7 @@ def test_single_tile_kernel_shapes(ssgd, oracle, torch_cuda, kind, variant, P, K
 
 
 def test_more_replicas_than_one_launch_holds(ssgd, oracle, torch_cuda):
-    """45 replicas of a 12-slice cluster need two launches (40 + 5); zero updates are a no-op."""
+    """45 replicas of a 12-slice cluster need several launches (16 + 16 + 13); zero updates are a no-op."""
     torch = torch_cuda
     X, y = synth.mixture_data(3000, 3072, 10, seed=7)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
@@ -651,6 +651,46 @@ def test_more_replicas_than_one_launch_holds(ssgd, oracle, torch_cuda):
     for r in (0, 39, 40, 44):
         tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=2, replica=r)
         tr.run(60)
+        assert_trace_equal(ctx.trace(r), tr.trace())
+        assert rel(ctx.params(r), tr.params()) <= FP32_PARAM_TOL
+    ctx.close()
+
+
+def test_k_async_kernel_hands_spread_clusters_to_the_fenced_exchange(ssgd, oracle, torch_cuda, monkeypatch):
+    """The K-async steady-state kernel exchanges through the L2 of one XCD.  A cluster that finds its workgroups on
+    several XCDs leaves its replica untouched and flags it, and the host runs those replicas through the kernel that
+    can exchange across XCDs.  Here the odd replicas are told that they are spread out (a host-side switch; every
+    kernel exits normally): all replicas must still follow the oracle."""
+    torch = torch_cuda
+    monkeypatch.setenv("SSGD_DEBUG_FLAGS", "2")
+    X, y = synth.mixture_data(2000, 1280, 10, seed=11)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    ctx = ssgd.Context("softmax", Xd, yd, 8, 2, 32, "k_async", gd, 0.05, seed=5, classes=10, replicas=5)
+    ctx.run(50)
+    ctx.run(40)
+    for r in (0, 1, 3, 4):
+        tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=5, replica=r)
+        tr.run(90)
+        assert_trace_equal(ctx.trace(r), tr.trace())
+        assert rel(ctx.params(r), tr.params()) <= FP32_PARAM_TOL
+    ctx.close()
+
+
+def test_parked_gradients_with_two_workgroups_per_cu(ssgd, oracle, torch_cuda, monkeypatch):
+    """K-async through the kernel that parks gradients in HBM, 40 replicas of twelve slices in one launch (two
+    workgroups per CU): replicas from both halves of the launch follow the oracle through updates that consume parked
+    gradients.  (A 16-byte store that lost its data in the second workgroup of a CU once showed up exactly here.)"""
+    torch = torch_cuda
+    monkeypatch.setenv("SSGD_KERNEL", "tile")
+    X, y = synth.mixture_data(3000, 3072, 10, seed=7)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    ctx = ssgd.Context("softmax", Xd, yd, 8, 2, 32, "k_async", gd, 0.05, seed=2, classes=10, replicas=40)
+    ctx.run(40)
+    for r in (0, 8, 20, 37, 39):
+        tr = oracle.Trainer(oracle.Model("softmax", X, y, classes=10), 8, 2, 32, "k_async", od, 0.05, seed=2, replica=r)
+        tr.run(40)
         assert_trace_equal(ctx.trace(r), tr.trace())
         assert rel(ctx.params(r), tr.params()) <= FP32_PARAM_TOL
     ctx.close()
