@@ -20,6 +20,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <type_traits>
 #include <vector>
 
 namespace ssgd {
@@ -33,6 +34,7 @@ typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 constexpr int MP = 64;         // rows kept per worker (m <= 64; the rest is zero)
 constexpr int KT = 64;         // contraction depth per stage
 constexpr int LDT = KT + 8;    // padded LDS row (bf16 elements): 144 bytes, keeps 16-byte reads conflict-poor
+constexpr int kSmallRec = 16;  // most records per update that take the few-record path
 
 // round to nearest even, as a 16-bit pattern; infinities and NaNs are truncated
 __device__ __forceinline__ unsigned short bf16_bits(float x) {
@@ -59,11 +61,16 @@ struct MlpArgs {
     unsigned short* xbt;       // [S][d][MP]   the same, transposed
     float* hbuf;               // [S][MP][H]   hidden activations
     unsigned short* d1t;       // [S][H][MP]   delta1 / m in bf16, transposed
-    float* gb1;                // [S][H]       sum over the mini-batch of delta1
-    float* gw2;                // [S][C][H]    sum of delta2 (x) h
-    float* gb2;                // [S][16]      sum of delta2
+    // The second-layer gradients and the loss have room for one record per quarter of the mini-batch (rows 16 q ..
+    // 16 q + 15).  The few-record path fills all four (its workgroups take a quarter each and need not meet) and sets the
+    // slot's flag; the other path adds the quarters itself, fills the first and clears the flag.  Whoever consumes a slot
+    // adds what the flag says, in order.
+    float* gb1;                // [S][4][H]    sum over the quarter of delta1
+    float* gw2;                // [S][4][C][H] sum of delta2 (x) h
+    float* gb2;                // [S][4][16]   sum of delta2
     float* d2;                 // [S][MP][16]  delta2 of every row
-    float* loss;               // [S]          sum of the sample losses
+    float* loss;               // [S][4]       sum of the sample losses
+    int32_t* quartered;        // [S]          1: four quarter records, 0: one record in the first quarter
     int32_t* ylab;             // [S][MP]      labels (-1: no sample)
     float* agg_out;            // nullable
     float* dw_part;            // [nsplit][H][d] partial first-layer gradient sums when the slots are split over workgroups;
@@ -198,6 +205,9 @@ __global__ __launch_bounds__(256) void mlp_gather_kernel(MlpArgs a) {
     }
 }
 
+template <int G>
+__device__ __forceinline__ void small_update_body(const MlpArgs& a, int block, int nblocks);
+
 // ---- contraction: C[M x N] = sum over stages of A_stage[M x 64] B_stage[N x 64]^T, bf16 MFMA ----
 // FWD: rows = (record, sample) of the compute list, columns = hidden units, depth = d.
 // BWD: rows = hidden units, columns = input features, depth = 64 samples of every consumed slot.
@@ -218,6 +228,11 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bm = blockIdx.x, bn = blockIdx.y;
     const int d = a.d, H = a.H;
+    if constexpr (!FWD && !SPLIT) {
+        // a launch with one more row of workgroups than there are column tiles: that row takes the small parameters of
+        // the update (they do not depend on the contraction), which saves a launch per update
+        if ((int)blockIdx.y == d / BT) { small_update_body<1>(a, blockIdx.x, gridDim.x); return; }
+    }
     // gradient contraction: the slots of the consumed gradients are read once, not once per stage in front of the
     // operand loads that depend on them
     __shared__ int slot_list[FWD ? 1 : 256];
@@ -254,21 +269,27 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
         if (FWD) return a.w1r + (int64_t)(bn * BT + row) * d + stage * KT;
         return a.xbt + ((int64_t)slot_list[FWD ? 0 : stage] * d + bn * BT + row) * MP;
     };
-    u16x8 ra[LP], rb[LP];
-    auto fetch = [&](int stage) {
+    // Operand stages travel global -> registers -> LDS.  A ring of PF register sets holds the stages that have been
+    // asked for and not yet stored to LDS, so that PF stages (PF x BT x 256 bytes) are in flight per workgroup: with one
+    // stage in flight a workgroup is bound by the latency of its loads, whatever the tile size.
+    constexpr int PF = 3;
+    u16x8 ra[PF][LP], rb[PF][LP];
+    auto fetch = [&](auto slot, int stage) {
+        constexpr int Q = decltype(slot)::value;
 #pragma unroll
         for (int i = 0; i < LP; ++i) {
             const int row = lrow + 32 * i;
-            ra[i] = *reinterpret_cast<const u16x8*>(a_ptr(row, stage) + 8 * lchunk);
-            rb[i] = *reinterpret_cast<const u16x8*>(b_ptr(row, stage) + 8 * lchunk);
+            ra[Q][i] = *reinterpret_cast<const u16x8*>(a_ptr(row, stage) + 8 * lchunk);
+            rb[Q][i] = *reinterpret_cast<const u16x8*>(b_ptr(row, stage) + 8 * lchunk);
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](auto slot, int buf) {
+        constexpr int Q = decltype(slot)::value;
 #pragma unroll
         for (int i = 0; i < LP; ++i) {
             const int row = lrow + 32 * i;
-            *reinterpret_cast<u16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = ra[i];
-            *reinterpret_cast<u16x8*>(Bs + (buf * BT + row) * LDT + 8 * lchunk) = rb[i];
+            *reinterpret_cast<u16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = ra[Q][i];
+            *reinterpret_cast<u16x8*>(Bs + (buf * BT + row) * LDT + 8 * lchunk) = rb[Q][i];
         }
     };
 
@@ -281,14 +302,18 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    if (stages > 0) {
-        fetch(stage0);
-        stash(0);
-    }
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    if (stages > 0) fetch(I0{}, stage0);
+    if (stages > 1) fetch(I1{}, stage0 + 1);
+    if (stages > 2) fetch(I2{}, stage0 + 2);
+    if (stages > 0) stash(I0{}, 0);
     __syncthreads();
-    for (int st = 0; st < stages; ++st) {
+    // stage st is in LDS buffer st & 1 and came from ring slot st % PF, which is free again
+    auto one_stage = [&](auto cur, auto nxt, int st) {
         const int buf = st & 1;
-        if (st + 1 < stages) fetch(stage0 + st + 1);
+        if (st + PF < stages) fetch(cur, stage0 + st + PF);
 #pragma unroll
         for (int kk = 0; kk < KT / 16; ++kk) {
             bf16x8 fa[NF], fb[NF];
@@ -305,8 +330,13 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
                 for (int j = 0; j < NF; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
-        if (st + 1 < stages) stash(buf ^ 1);
+        if (st + 1 < stages) stash(nxt, buf ^ 1);
         __syncthreads();
+    };
+    for (int st = 0; st < stages; st += PF) {
+        one_stage(I0{}, I1{}, st);
+        if (st + 1 < stages) one_stage(I1{}, I2{}, st + 1);
+        if (st + 2 < stages) one_stage(I2{}, I0{}, st + 2);
     }
 
     // The result goes through LDS so that the global accesses of the epilogue run along rows.
@@ -357,6 +387,276 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
             if (a.agg_out) *reinterpret_cast<f32x4*>(a.agg_out + p) = v * invK;
         }
     }
+}
+
+// ---- Few records (small K): the forward pass straight from the sample matrix --------------------------------
+// One launch does what the gather kernel, the split forward contraction and its finishing kernel do otherwise:
+// workgroup (record r, 64 hidden units bn, share z of the depth d) draws the sample ids of the record, reads its rows
+// from X in fp32, rounds them to bf16 on the way to LDS and leaves its partial sums of Z1 in dw_part; the workgroups
+// with bn = 0 also write the rows' transposed bf16 copy, which the first-layer gradient contraction of a later update
+// reads.  (Workgroups of one launch do not hand results to each other: making one workgroup's stores visible to
+// another on a different XCD costs a write-back of the L2, far more than the launch it would save.)  A launch of this
+// kind is a chain of load latencies, so three stages per operand are in flight in registers.
+__global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
+    constexpr int BT = 64, LP = 2, PF = 3;
+    __shared__ __attribute__((aligned(16))) unsigned short As[2 * BT * LDT];
+    __shared__ __attribute__((aligned(16))) unsigned short Bs[2 * BT * LDT];
+    __shared__ uint32_t ids[MP];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = blockIdx.x, bn = blockIdx.y;
+    const int d = a.d, H = a.H;
+    int worker, ordinal, slot;
+    record_of(a, r, worker, ordinal, slot);
+    if (tid < MP) {
+        uint32_t id = 0xFFFFFFFFu;
+        if (tid < a.m) id = batch_index(a.seed, 0u, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)tid, a.N);
+        ids[tid] = id;
+        if (bn == 0 && blockIdx.z == 0) a.ylab[slot * MP + tid] = (id == 0xFFFFFFFFu) ? -1 : a.y[id];
+    }
+    __syncthreads();
+    const int total = d / KT, per = (total + a.fsplit - 1) / a.fsplit;
+    const int stage0 = blockIdx.z * per, stages = max(0, min(per, total - stage0));
+    const int lchunk = tid & 7, lrow = tid >> 3;
+    const float* xrow[LP];
+    bool has[LP];
+#pragma unroll
+    for (int i = 0; i < LP; ++i) {
+        const uint32_t id = ids[lrow + 32 * i];
+        has[i] = id != 0xFFFFFFFFu;
+        xrow[i] = a.X + (int64_t)(has[i] ? id : 0u) * d + 8 * lchunk;
+    }
+    const unsigned short* wrow = a.w1r + (int64_t)(bn * BT + lrow) * d + 8 * lchunk;
+    f32x4 ra[PF][LP][2];
+    u16x8 rb[PF][LP];
+    auto fetch = [&](auto ring, int stage) {
+        constexpr int Q = decltype(ring)::value;
+#pragma unroll
+        for (int i = 0; i < LP; ++i) {
+            ra[Q][i][0] = *reinterpret_cast<const f32x4*>(xrow[i] + stage * KT);
+            ra[Q][i][1] = *reinterpret_cast<const f32x4*>(xrow[i] + stage * KT + 4);
+            rb[Q][i] = *reinterpret_cast<const u16x8*>(wrow + (int64_t)32 * i * d + stage * KT);
+        }
+    };
+    auto stash = [&](auto ring, int buf) {
+        constexpr int Q = decltype(ring)::value;
+#pragma unroll
+        for (int i = 0; i < LP; ++i) {
+            const int row = lrow + 32 * i;
+            u16x8 v;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = has[i] ? bf16_bits(ra[Q][i][e >> 2][e & 3]) : (unsigned short)0;
+            *reinterpret_cast<u16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = v;
+            *reinterpret_cast<u16x8*>(Bs + (buf * BT + row) * LDT + 8 * lchunk) = rb[Q][i];
+        }
+    };
+    const int wm = wave >> 1, wn = wave & 1;
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    if (stages > 0) fetch(I0{}, stage0);
+    if (stages > 1) fetch(I1{}, stage0 + 1);
+    if (stages > 2) fetch(I2{}, stage0 + 2);
+    if (stages > 0) stash(I0{}, 0);
+    __syncthreads();
+    auto one_stage = [&](auto cur, auto nxt, int st) {
+        const int buf = st & 1;
+        if (st + PF < stages) fetch(cur, stage0 + st + PF);
+#pragma unroll
+        for (int kk = 0; kk < KT / 16; ++kk) {
+            const bf16x8 fa = *reinterpret_cast<const bf16x8*>(As + (buf * BT + wm * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
+            const bf16x8 fb = *reinterpret_cast<const bf16x8*>(Bs + (buf * BT + wn * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+        }
+        if (bn == 0) {
+            // transposed copy of this stage's 64 x 64 block: thread -> feature tid / 4, samples 16 (tid % 4) .. + 15
+            const int k = tid >> 2, part = tid & 3;
+            u16x8 v0, v1;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                v0[e] = As[(buf * BT + 16 * part + e) * LDT + k];
+                v1[e] = As[(buf * BT + 16 * part + 8 + e) * LDT + k];
+            }
+            unsigned short* dst = a.xbt + ((int64_t)slot * d + (int64_t)(stage0 + st) * KT + k) * MP + 16 * part;
+            *reinterpret_cast<u16x8*>(dst) = v0;
+            *reinterpret_cast<u16x8*>(dst + 8) = v1;
+        }
+        if (st + 1 < stages) stash(nxt, buf ^ 1);
+        __syncthreads();
+    };
+    for (int st = 0; st < stages; st += PF) {
+        one_stage(I0{}, I1{}, st);
+        if (st + 1 < stages) one_stage(I1{}, I2{}, st + 1);
+        if (st + 2 < stages) one_stage(I2{}, I0{}, st + 2);
+    }
+    // partial sums of Z1: element e of lane -> row 8 (e / 4) + 4 (lane / 32) + e % 4, column lane % 32 of the wave's 32 x 32 block
+    {
+        float* out = a.dw_part + (((int64_t)blockIdx.z * a.nrec + r) * MP) * H + bn * BT + wn * 32 + (lane & 31);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = wm * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            out[(int64_t)row * H] = acc[e];
+        }
+    }
+}
+
+// ---- Few records: everything between the two contractions in one launch ---------------------------------------
+// Workgroup (record r, quarter q) takes rows 16 q .. 16 q + 15 of the record: hidden activations from the partial sums
+// of the split forward pass (shares added in order, bias, ReLU; kept in LDS), layer 2 on the fp32 MFMA units (wave w
+// takes a quarter of the hidden units, the four partial results are added in order), softmax, delta2, loss,
+// delta1 = (W2^T delta2) * [h > 0] (bf16, transposed, for the gradient contraction) and the quarter's second-layer
+// gradients.
+__global__ __launch_bounds__(256) void mlp_mid_kernel(MlpArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float mid_lds[];
+    const int H = a.H, C = a.C, m = a.m;
+    const int HS = H + 4;
+    float* hs = mid_lds;                       // [16][H + 4]
+    float* zp = hs + 16 * HS;                  // [4][16][16] partial logits
+    float* d2s = zp + 4 * 256;                 // [16][16]
+    float* red = d2s + 256;                    // [4] loss of the waves
+    const int r = blockIdx.x >> 2, q = blockIdx.x & 3, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int worker, ordinal, slot;
+    record_of(a, r, worker, ordinal, slot);
+    // ---- hidden activations of the 16 rows: every share of every position is asked for before the first is used
+    {
+        const int h4 = H / 4;                  // 16-byte groups per row; 16 rows = 16 h4 groups, 16 h4 / 256 per thread
+        const float* src = a.dw_part + ((int64_t)r * MP + 16 * q) * H;
+        const int64_t zs = (int64_t)a.nrec * MP * H;
+        const float* b1 = a.params + (int64_t)H * a.d;
+        for (int p0 = tid; p0 < 16 * h4; p0 += 4 * 256) {
+            f32x4 v[4][8];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int p = min(p0 + 256 * u, 16 * h4 - 1);
+#pragma unroll
+                for (int z = 0; z < 8; ++z)
+                    if (z < a.fsplit) v[u][z] = *reinterpret_cast<const f32x4*>(src + z * zs + (int64_t)4 * p);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int p = p0 + 256 * u;
+                if (p < 16 * h4) {
+                    f32x4 t = v[u][0];
+#pragma unroll
+                    for (int z = 1; z < 8; ++z)
+                        if (z < a.fsplit) t += v[u][z];
+                    const int n = 4 * (p % h4);
+                    const f32x4 bb = *reinterpret_cast<const f32x4*>(b1 + n);
+                    f32x4 h;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) { const float zc = t[c] + bb[c]; h[c] = zc > 0.0f ? zc : 0.0f; }
+                    *reinterpret_cast<f32x4*>(hs + (p / h4) * HS + n) = h;
+                }
+            }
+        }
+    }
+    const int cls = lane & 15, kq = lane >> 4;
+    const float b2 = a.params[(int64_t)H * a.d + H + (int64_t)C * H + min(cls, C - 1)];
+    __syncthreads();
+    // ---- layer 2: wave w sums over its quarter of the hidden units
+    {
+        const int kw = H / 4;                  // hidden units per wave, a multiple of 32
+        const float* hp = hs + (lane & 15) * HS + wave * kw + 4 * kq;
+        const float* wp = a.w2r + (int64_t)min(cls, C - 1) * H + wave * kw + 4 * kq;
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        for (int k0 = 0; k0 < kw / 16; k0 += 8) {
+            f32x4 hv[8], wv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int kb = min(k0 + u, kw / 16 - 1);
+                hv[u] = *reinterpret_cast<const f32x4*>(hp + 16 * kb);
+                wv[u] = *reinterpret_cast<const f32x4*>(wp + 16 * kb);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (k0 + u < kw / 16) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[u].x, wv[u].x, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[u].y, wv[u].y, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[u].z, wv[u].z, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[u].w, wv[u].w, acc1, 0, 0, 0);
+                }
+            }
+        }
+        const f32x4 acc = acc0 + acc1;         // class lane % 16 of rows 4 (lane / 16) + e
+#pragma unroll
+        for (int e = 0; e < 4; ++e) zp[wave * 256 + (4 * kq + e) * 16 + cls] = acc[e];
+    }
+    // second-layer weights of this thread's hidden units (delta1 below), asked for before the softmax
+    float w2c[2][16];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int c = 0; c < 16; ++c) w2c[u][c] = (c < C && tid + 256 * u < H) ? a.w2r[c * H + tid + 256 * u] : 0.0f;
+    __syncthreads();
+    // ---- softmax, delta2, loss: thread -> (row tid / 16, class tid % 16)
+    {
+        const int row = tid >> 4, c = tid & 15;   // c == lane % 16: b2 is this lane's own class
+        const int s = 16 * q + row;
+        const int lab = a.ylab[slot * MP + s];
+        const bool ok = s < m && lab >= 0;
+        const float z = ((zp[row * 16 + c] + zp[256 + row * 16 + c]) + zp[512 + row * 16 + c]) + zp[768 + row * 16 + c] + b2;
+        float zmax = c < C ? z : -3.0e38f;
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 64));
+        const float ex = c < C ? expf(z - zmax) : 0.0f;
+        float den = ex;
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) den += __shfl_xor(den, o, 64);
+        float dv = 0.0f, ls = 0.0f;
+        if (c < C && ok) {
+            dv = ex / den - (c == lab ? 1.0f : 0.0f);
+            if (c == lab) ls = -(z - zmax - logf(den));
+        }
+        d2s[row * 16 + c] = dv;
+        a.d2[(slot * MP + s) * 16 + c] = dv;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) ls += __shfl_xor(ls, o, 64);
+        if (lane == 0) red[wave] = ls;
+    }
+    __syncthreads();
+    // ---- delta1 and the quarter's sums: thread -> hidden units tid and tid + 256
+    const float inv_m = 1.0f / (float)m;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int j = tid + 256 * u;
+        if (j < H) {
+            float gw[16];
+#pragma unroll
+            for (int c = 0; c < 16; ++c) gw[c] = 0.0f;
+            float g1 = 0.0f;
+            u16x8 pack[2];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float h = hs[e * HS + j];
+                float d1 = 0.0f;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) {
+                    const float dv = d2s[e * 16 + c];
+                    d1 += w2c[u][c] * dv;
+                    gw[c] += dv * h;
+                }
+                if (!(h > 0.0f)) d1 = 0.0f;
+                g1 += d1;
+                pack[e >> 3][e & 7] = bf16_bits(d1 * inv_m);
+            }
+            unsigned short* dst = a.d1t + ((int64_t)slot * H + j) * MP + 16 * q;
+            *reinterpret_cast<u16x8*>(dst) = pack[0];
+            *reinterpret_cast<u16x8*>(dst + 8) = pack[1];
+            a.gb1[(slot * 4 + q) * H + j] = g1;
+#pragma unroll
+            for (int c = 0; c < 16; ++c)
+                if (c < C) a.gw2[((int64_t)(slot * 4 + q) * C + c) * H + j] = gw[c];
+        }
+    }
+    if (tid < 16) {
+        float sum = 0.0f;
+        for (int e = 0; e < 16; ++e) sum += d2s[e * 16 + tid];
+        a.gb2[(slot * 4 + q) * 16 + tid] = sum;
+    }
+    if (tid == 16) a.loss[slot * 4 + q] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (tid == 17 && q == 0) a.quartered[slot] = 1;
 }
 
 // ---- hidden activations from the partial sums of a split forward pass: shares added in order, bias, ReLU --------
@@ -459,7 +759,7 @@ __global__ __launch_bounds__(256) void mlp_output_kernel(MlpArgs a) {
     for (int o = 32; o >= 1; o >>= 1) lsum += __shfl_xor(lsum, o, 64);
     if (lane == 0) wsum[wave] = lsum;
     __syncthreads();
-    if (tid == 0) a.loss[slot] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    if (tid == 0) a.loss[slot * 4] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
 }
 
 // ---- delta1 = (W2^T delta2) * [H > 0], second-layer gradient: workgroup = (record, 64 hidden units) ----
@@ -501,7 +801,7 @@ __global__ __launch_bounds__(256) void mlp_delta1_kernel(MlpArgs a) {
     unsigned short* dst = a.d1t + ((int64_t)slot * H + j) * MP + 16 * rq;
     *reinterpret_cast<u16x8*>(dst) = pack[0];
     *reinterpret_cast<u16x8*>(dst + 8) = pack[1];
-    // the four row quarters are added in a fixed order
+    // the four row quarters are added in a fixed order; the sum is the slot's only record
     if (rq > 0) {
         part[rq - 1][jl][16] = g1;
 #pragma unroll
@@ -509,20 +809,25 @@ __global__ __launch_bounds__(256) void mlp_delta1_kernel(MlpArgs a) {
     }
     __syncthreads();
     if (rq == 0) {
-        a.gb1[slot * H + j] = ((g1 + part[0][jl][16]) + part[1][jl][16]) + part[2][jl][16];
+        a.gb1[slot * 4 * H + j] = ((g1 + part[0][jl][16]) + part[1][jl][16]) + part[2][jl][16];
 #pragma unroll
         for (int c = 0; c < 16; ++c)
-            if (c < C) a.gw2[((int64_t)slot * C + c) * H + j] = ((gw[c] + part[0][jl][c]) + part[1][jl][c]) + part[2][jl][c];
+            if (c < C) a.gw2[((int64_t)slot * 4 * C + c) * H + j] = ((gw[c] + part[0][jl][c]) + part[1][jl][c]) + part[2][jl][c];
     }
     if (jb == 0 && tid < 16) {
         float sum = 0.0f;
         for (int s = 0; s < MP; ++s) sum += d2s[s][tid];
-        a.gb2[slot * 16 + tid] = sum;
+        a.gb2[slot * 4 * 16 + tid] = sum;
     }
+    if (jb == 0 && tid == 16) a.quartered[slot] = 0;
 }
 
 // ---- the small parameters of update v, and its loss record ------------------------------------
-__global__ __launch_bounds__(256) void mlp_small_update_kernel(MlpArgs a) {
+// Element q of the per-slot record [gb1 | gw2 | gb2 | loss] is summed over the consumed slots by a group of G lanes
+// (G a power of two, at most 16): lane g of the group takes the slots g, g + G, ... in list order, the G partial sums are
+// added in a fixed butterfly order.  (block `block` of `nblocks` blocks of 256 threads)
+template <int G>
+__device__ __forceinline__ void small_update_body(const MlpArgs& a, int block, int nblocks) {
     const int H = a.H, C = a.C, d = a.d;
     const float invKm = 1.0f / ((float)a.Kv * (float)a.m);
     float* b1 = a.params + (int64_t)H * d;
@@ -530,37 +835,63 @@ __global__ __launch_bounds__(256) void mlp_small_update_kernel(MlpArgs a) {
     float* b2 = W2 + (int64_t)C * H;
     const int total = H + C * H + C + 1;
     __shared__ int slots[256];
-    for (int l = threadIdx.x; l < a.Kv; l += blockDim.x) slots[l] = consumed_slot(a, l);
+    __shared__ int nquart[256];
+    for (int l = threadIdx.x; l < a.Kv; l += blockDim.x) {
+        const int sl = consumed_slot(a, l);
+        slots[l] = sl;
+        nquart[l] = a.quartered[sl] != 0 ? 4 : 1;
+    }
     __syncthreads();
-    for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < total; q += gridDim.x * blockDim.x) {
-        // element q of the per-slot record [gb1 | gw2 | gb2 | loss]; slots are summed in list order, eight loads in flight
-        const float* base;
-        int stride;
-        if (q < H) { base = a.gb1 + q; stride = H; }
-        else if (q < H + C * H) { base = a.gw2 + (q - H); stride = C * H; }
-        else if (q < H + C * H + C) { base = a.gb2 + (q - H - C * H); stride = 16; }
-        else { base = a.loss; stride = 1; }
-        float sum = 0.0f;
-        int l = 0;
-        for (; l + 8 <= a.Kv; l += 8) {
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = base[(int64_t)slots[l + u] * stride];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) sum += v[u];
+    const int g = threadIdx.x % G;
+    const int per_block = blockDim.x / G;
+    const int rounds = (total + nblocks * per_block - 1) / (nblocks * per_block);
+    for (int it = 0; it < rounds; ++it) {
+        const int q = (it * nblocks + block) * per_block + threadIdx.x / G;
+        const bool live = q < total;
+        const float* base = a.loss;
+        int stride = 1;             // between the quarters of a slot; four times that between slots
+        if (live) {
+            if (q < H) { base = a.gb1 + q; stride = H; }
+            else if (q < H + C * H) { base = a.gw2 + (q - H); stride = C * H; }
+            else if (q < H + C * H + C) { base = a.gb2 + (q - H - C * H); stride = 16; }
         }
-        for (; l < a.Kv; ++l) sum += base[(int64_t)slots[l] * stride];
-        const float g = sum * invKm;
-        if (q < H) { b1[q] -= a.lr * g; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = g; }
-        else if (q < H + C * H) {
-            const float w = W2[q - H] - a.lr * g;
-            W2[q - H] = w;
-            a.w2r[q - H] = bf16_round(w);
-            if (a.agg_out) a.agg_out[(int64_t)H * d + q] = g;
-        } else if (q < H + C * H + C) { b2[q - H - C * H] -= a.lr * g; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = g; }
-        else a.tr.loss[a.v] = g;
+        float sum = 0.0f;
+        if (live) {
+            int l = g;
+            for (; l + 3 * G < a.Kv; l += 4 * G) {
+                float v[4][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq)
+                        v[u][qq] = qq < nquart[l + u * G] ? base[((int64_t)slots[l + u * G] * 4 + qq) * stride] : 0.0f;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) sum += ((v[u][0] + v[u][1]) + v[u][2]) + v[u][3];
+            }
+            for (; l < a.Kv; l += G) {
+                float v[4];
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) v[qq] = qq < nquart[l] ? base[((int64_t)slots[l] * 4 + qq) * stride] : 0.0f;
+                sum += ((v[0] + v[1]) + v[2]) + v[3];
+            }
+        }
+#pragma unroll
+        for (int o = 1; o < G; o <<= 1) sum += __shfl_xor(sum, o, 64);
+        if (live && g == 0) {
+            const float gr = sum * invKm;
+            if (q < H) { b1[q] -= a.lr * gr; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr; }
+            else if (q < H + C * H) {
+                const float w = W2[q - H] - a.lr * gr;
+                W2[q - H] = w;
+                a.w2r[q - H] = bf16_round(w);
+                if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr;
+            } else if (q < H + C * H + C) { b2[q - H - C * H] -= a.lr * gr; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr; }
+            else a.tr.loss[a.v] = gr;
+        }
     }
 }
+template <int G>
+__global__ __launch_bounds__(256) void mlp_small_update_kernel(MlpArgs a) { small_update_body<G>(a, blockIdx.x, gridDim.x); }
 
 __global__ void mlp_refresh_kernel(const float* params, unsigned short* w1r, float* w2r, int64_t n1, int64_t off2, int64_t n2) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -590,6 +921,7 @@ __global__ void mlp_init_kernel(float* params, uint64_t seed, int64_t nw, int64_
 // operand double buffer; the epilogue's fp32 tile [BT][BT + 4] fits inside it
 size_t contract_lds(int bt) { return (size_t)4 * bt * LDT * 2; }
 constexpr int kMaxSplit = 8;     // shares of the consumed slots in the split gradient contraction
+size_t mid_lds_bytes(int H) { return sizeof(float) * (16 * (size_t)(H + 4) + 4 * 256 + 256 + 4); }
 
 struct DevMem {
     void* p = nullptr;
@@ -605,7 +937,7 @@ struct MlpState {
     int S = 0;
     int64_t nw = 0;
     int prevK = 0;          // size of the consume list of the last update run (records of the next K-async step)
-    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, dw_part, plan;
+    DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, dw_part, plan, quartered;
     hipStream_t stream = nullptr;
 };
 
@@ -635,12 +967,14 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(s->xbt.alloc(2 * S * MP * a.d));
     TRY(s->hbuf.alloc(sizeof(float) * S * MP * a.H));
     TRY(s->d1t.alloc(2 * S * MP * a.H));
-    TRY(s->gb1.alloc(sizeof(float) * S * a.H));
-    TRY(s->gw2.alloc(sizeof(float) * S * a.C * a.H));
-    TRY(s->gb2.alloc(sizeof(float) * S * 16));
+    TRY(s->gb1.alloc(sizeof(float) * S * 4 * a.H));
+    TRY(s->gw2.alloc(sizeof(float) * S * 4 * a.C * a.H));
+    TRY(s->gb2.alloc(sizeof(float) * S * 4 * 16));
     TRY(s->d2.alloc(sizeof(float) * S * MP * 16));
-    TRY(s->loss.alloc(sizeof(float) * S));
+    TRY(s->loss.alloc(sizeof(float) * S * 4));
     TRY(s->ylab.alloc(sizeof(int32_t) * S * MP));
+    TRY(s->quartered.alloc(sizeof(int32_t) * S));
+    TRY(hipMemsetAsync(s->quartered.p, 0, sizeof(int32_t) * S, stream));
     TRY(s->dw_part.alloc(sizeof(float) * kMaxSplit * (size_t)n1));
     {
         // every slot free (popped in the order 0, 1, ...), no worker has a mini-batch yet
@@ -657,16 +991,17 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(hipMemsetAsync(s->xbt.p, 0, 2 * S * MP * a.d, stream));
     TRY(hipMemsetAsync(s->hbuf.p, 0, sizeof(float) * S * MP * a.H, stream));
     TRY(hipMemsetAsync(s->d1t.p, 0, 2 * S * MP * a.H, stream));
-    TRY(hipMemsetAsync(s->gb1.p, 0, sizeof(float) * S * a.H, stream));
-    TRY(hipMemsetAsync(s->gw2.p, 0, sizeof(float) * S * a.C * a.H, stream));
-    TRY(hipMemsetAsync(s->gb2.p, 0, sizeof(float) * S * 16, stream));
-    TRY(hipMemsetAsync(s->loss.p, 0, sizeof(float) * S, stream));
+    TRY(hipMemsetAsync(s->gb1.p, 0, sizeof(float) * S * 4 * a.H, stream));
+    TRY(hipMemsetAsync(s->gw2.p, 0, sizeof(float) * S * 4 * a.C * a.H, stream));
+    TRY(hipMemsetAsync(s->gb2.p, 0, sizeof(float) * S * 4 * 16, stream));
+    TRY(hipMemsetAsync(s->loss.p, 0, sizeof(float) * S * 4, stream));
     TRY(hipMemsetAsync(s->ylab.p, 0xFF, sizeof(int32_t) * S * MP, stream));
     a.params = (float*)s->params.p; a.w1r = (unsigned short*)s->w1r.p; a.w2r = (float*)s->w2r.p;
     a.xb = (unsigned short*)s->xb.p; a.xbt = (unsigned short*)s->xbt.p; a.hbuf = (float*)s->hbuf.p;
     a.d1t = (unsigned short*)s->d1t.p; a.gb1 = (float*)s->gb1.p; a.gw2 = (float*)s->gw2.p; a.gb2 = (float*)s->gb2.p;
-    a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p; a.d2 = (float*)s->d2.p;
+    a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p; a.d2 = (float*)s->d2.p; a.quartered = (int32_t*)s->quartered.p;
     a.dw_part = (float*)s->dw_part.p; a.nsplit = 1; a.fsplit = 1; a.eval_base = -1;
+
     const float bound1 = (float)(1.0 / sqrt((double)a.d)), bound2 = (float)(1.0 / sqrt((double)a.H));
     hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
     TRY(hipGetLastError());
@@ -675,6 +1010,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 128, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 64, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_mid_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)mid_lds_bytes(1024)));
 #undef TRY
     *out = s;
     return hipSuccess;
@@ -710,10 +1046,16 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
         if (a.variant == kBatchAsync) a.nrec = (a.v == 0 ? a.P : 1) + a.Kv - 1;
         if (a.Kv < 1 || a.Kv > a.Kcap || a.nrec < 0 || a.nrec > s->S) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return fail(hipErrorInvalidValue, "inconsistent K in the trace"); }
         if (a.variant == kBatchAsync) hipLaunchKernelGGL(mlp_batch_plan_kernel, dim3(1), dim3(64), 0, stream, a);
-        if (a.nrec > 0) {
+        const int wgs64 = a.nrec * (a.H / 64);
+        if (a.nrec > 0 && a.nrec <= kSmallRec && wgs64 <= 128 && a.H <= 1024 &&
+            (int64_t)a.nrec * MP * a.H * 8 <= (int64_t)kMaxSplit * a.H * a.d) {
+            // few records: two launches; the depth is split so that two workgroups share every CU and none walks all of d
+            a.fsplit = std::max(2, std::min(getenv("SSGD_FS") ? atoi(getenv("SSGD_FS")) : 8, 512 / wgs64));
+            hipLaunchKernelGGL(mlp_fwd_gather_kernel, dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(mlp_mid_kernel, dim3(a.nrec * 4), dim3(256), mid_lds_bytes(a.H), stream, a);
+        } else if (a.nrec > 0) {
             hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
             // small tiles while the large ones would not fill the chip
-            const int wgs64 = a.nrec * (a.H / 64);
             if (((a.nrec + 1) / 2) * (a.H / 128) >= 192) {
                 hipLaunchKernelGGL((mlp_contract_kernel<true, 128>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
             } else if (wgs64 <= 128 && (int64_t)a.nrec * MP * a.H * 4 <= (int64_t)kMaxSplit * a.H * a.d) {
@@ -727,18 +1069,18 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
             hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
             hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
         }
-        // the gradient contraction always uses the small tiles: 384 workgroups instead of 96 matter more than the
-        // reuse inside a larger tile
         if (a.Kv >= 64) {
             // many slots: 128 x 128 tiles (half the operand traffic of the small ones), the slots split into shares so
             // that the chip is still full; the shares are added, in order, by the update kernel
             a.nsplit = std::min(kMaxSplit, a.Kv / 16);
             hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3(a.H / 128, a.d / 128, a.nsplit), dim3(256), contract_lds(128), stream, a);
             hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
         } else {
-            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64), dim3(256), contract_lds(64), stream, a);
+            // small tiles: 384 workgroups instead of 96 matter more than the reuse inside a larger tile; one more row of
+            // workgroups takes the small parameters
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64 + 1), dim3(256), contract_lds(64), stream, a);
         }
-        hipLaunchKernelGGL(mlp_small_update_kernel, dim3(24), dim3(256), 0, stream, a);
         if (launches) *launches += 1;
     }
     (void)hipEventRecord(e1, stream);
@@ -774,7 +1116,7 @@ hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::stri
     if (e == hipSuccess) e = xb.alloc(2 * (size_t)E * MP * a.d);
     if (e == hipSuccess) e = hbuf.alloc(sizeof(float) * (size_t)E * MP * a.H);
     if (e == hipSuccess) e = d2.alloc(sizeof(float) * (size_t)E * MP * 16);
-    if (e == hipSuccess) e = loss.alloc(sizeof(float) * (size_t)E);
+    if (e == hipSuccess) e = loss.alloc(sizeof(float) * (size_t)E * 4);
     if (e == hipSuccess) e = ylab.alloc(sizeof(int32_t) * (size_t)E * MP);
     if (e != hipSuccess) { release(); return fail(e, "allocating the evaluation buffers"); }
     a.xb = (unsigned short*)xb.p; a.xbt = nullptr; a.hbuf = (float*)hbuf.p; a.d2 = (float*)d2.p;
@@ -783,7 +1125,7 @@ hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::stri
     a.m = MP; a.v = 0; a.Kv = 1;
     const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
     hipLaunchKernelGGL(mlp_refresh_kernel, dim3(1024), dim3(256), 0, stream, a.params, a.w1r, a.w2r, n1, off2, n2);
-    std::vector<float> h((size_t)E);
+    std::vector<float> h((size_t)E * 4);
     double total = 0.0;
     for (int64_t s0 = 0; s0 < nslot && e == hipSuccess; s0 += E) {
         a.eval_base = s0 * MP;
@@ -795,9 +1137,9 @@ hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::stri
             hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
         hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
         e = hipGetLastError();
-        if (e == hipSuccess) e = hipMemcpyAsync(h.data(), a.loss, sizeof(float) * a.nrec, hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(h.data(), a.loss, sizeof(float) * a.nrec * 4, hipMemcpyDeviceToHost, stream);
         if (e == hipSuccess) e = hipStreamSynchronize(stream);
-        if (e == hipSuccess) for (int q = 0; q < a.nrec; ++q) total += (double)h[(size_t)q];
+        if (e == hipSuccess) for (int q = 0; q < a.nrec; ++q) total += (double)h[(size_t)q * 4];
     }
     release();
     if (e != hipSuccess) return fail(e, "evaluating the objective");
@@ -810,7 +1152,7 @@ hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::stri
 // mini-batches in flight, slot by slot.
 static std::vector<DevMem*> mlp_state_buffers(MlpState* s) {
     return {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss,
-            &s->ylab, &s->plan};
+            &s->ylab, &s->plan, &s->quartered};
 }
 
 int64_t mlp_state_bytes(MlpState* s) {
@@ -849,7 +1191,7 @@ float* mlp_params(MlpState* s) { return s ? (float*)s->params.p : nullptr; }
 void mlp_destroy(MlpState* s) {
     if (!s) return;
     DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss, &s->ylab,
-                      &s->dw_part, &s->plan};
+                      &s->dw_part, &s->plan, &s->quartered};
     for (DevMem* b : bufs) b->release();
     delete s;
 }
