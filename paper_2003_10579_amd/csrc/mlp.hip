@@ -30,6 +30,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
 
 constexpr int MP = 64;         // rows kept per worker (m <= 64; the rest is zero)
 constexpr int KT = 64;         // contraction depth per stage
@@ -74,7 +75,7 @@ struct MlpArgs {
     int32_t* ylab;             // [S][MP]      labels (-1: no sample)
     float* agg_out;            // nullable
     float* dw_part;            // [nsplit][H][d] partial first-layer gradient sums when the slots are split over workgroups;
-                               // also [fsplit][nrec][MP][H] partial hidden-layer sums when the depth of the forward pass is split
+                               // also [fsplit][nrec][MP][H] partial hidden-layer sums of the few-record forward pass
     int32_t nsplit;
     int32_t fsplit;            // shares of the depth d in the forward contraction of few records
     int64_t eval_base;         // >= 0: objective evaluation; record r holds data rows eval_base + 64 r .. + 63 in slot r
@@ -213,10 +214,8 @@ __device__ __forceinline__ void small_update_body(const MlpArgs& a, int block, i
 // BWD: rows = hidden units, columns = input features, depth = 64 samples of every consumed slot.
 // BT x BT output tile per workgroup (128: four waves of 64 x 64; 64: four waves of 32 x 32, for launches
 // that would otherwise leave most CUs idle).
-// SPLIT: blockIdx.z takes a share of the depth and leaves its partial sum in dw_part.  Gradient contraction: shares of
-// the consumed slots, mlp_w1_update_kernel adds them in order and applies the update.  Forward pass of few records
-// (a launch of a few dozen workgroups that each walk the whole depth d is bound by the latency of its loads): shares
-// of d, mlp_fwd_finish_kernel adds them in order, then bias and ReLU.
+// SPLIT (gradient contraction only): blockIdx.z takes a share of the consumed slots and leaves its partial sum in
+// dw_part; mlp_w1_update_kernel adds the shares in order and applies the update.
 template <bool FWD, int BT, bool SPLIT = false>
 __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     constexpr int WT = BT / 2;          // rows and columns per wave
@@ -242,7 +241,8 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     }
     int stage0 = 0, stages = FWD ? d / KT : a.Kv;
     if constexpr (SPLIT) {
-        const int total = FWD ? d / KT : a.Kv, shares = FWD ? a.fsplit : a.nsplit;
+        static_assert(!FWD, "only the gradient contraction is split here");
+        const int total = a.Kv, shares = a.nsplit;
         const int per = (total + shares - 1) / shares;
         stage0 = blockIdx.z * per;
         stages = max(0, min(per, total - stage0));
@@ -359,11 +359,7 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     for (int q = tid; q < BT * C4; q += 256) {
         const int row = q / C4, c4 = q % C4;
         const f32x4 v = *reinterpret_cast<const f32x4*>(Cs + row * LDC + 4 * c4);
-        if (FWD && SPLIT) {
-            const int r = RPT * bm + row / MP;
-            if (r < a.nrec)
-                *reinterpret_cast<f32x4*>(a.dw_part + (((int64_t)blockIdx.z * a.nrec + r) * MP + (row % MP)) * H + bn * BT + 4 * c4) = v;
-        } else if (FWD) {
+        if (FWD) {
             const int r = RPT * bm + row / MP;
             if (r < a.nrec) {
                 const int n = bn * BT + 4 * c4;
@@ -397,25 +393,39 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
 // reads.  (Workgroups of one launch do not hand results to each other: making one workgroup's stores visible to
 // another on a different XCD costs a write-back of the L2, far more than the launch it would save.)  A launch of this
 // kind is a chain of load latencies, so three stages per operand are in flight in registers.
+template <int BT, bool SPLIT>
 __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
-    constexpr int BT = 64, LP = 2, PF = 3;
-    __shared__ __attribute__((aligned(16))) unsigned short As[2 * BT * LDT];
-    __shared__ __attribute__((aligned(16))) unsigned short Bs[2 * BT * LDT];
-    __shared__ uint32_t ids[MP];
+    constexpr int LP = BT / 32;         // row chunks per thread, operand and stage
+    constexpr int PF = BT == 64 ? 3 : 2;
+    constexpr int RPT = BT / MP;        // records per workgroup
+    constexpr int WT = BT / 2, NF = WT / 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+    unsigned short* As = lds;                       // [2][BT][LDT]
+    unsigned short* Bs = lds + 2 * BT * LDT;        // [2][BT][LDT]
+    __shared__ uint32_t ids[BT];
+    __shared__ int slot_s[RPT];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = blockIdx.x, bn = blockIdx.y;
+    const int bm = blockIdx.x, bn = blockIdx.y;
     const int d = a.d, H = a.H;
-    int worker, ordinal, slot;
-    record_of(a, r, worker, ordinal, slot);
-    if (tid < MP) {
+    if (tid < BT) {
+        const int r = RPT * bm + tid / MP, row = tid % MP;
         uint32_t id = 0xFFFFFFFFu;
-        if (tid < a.m) id = batch_index(a.seed, 0u, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)tid, a.N);
+        if (r < a.nrec) {
+            int worker, ordinal, slot;
+            record_of(a, r, worker, ordinal, slot);
+            if (row < a.m) id = batch_index(a.seed, 0u, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)row, a.N);
+            if (bn == 0 && blockIdx.z == 0) a.ylab[slot * MP + row] = (id == 0xFFFFFFFFu) ? -1 : a.y[id];
+            if (row == 0) slot_s[tid / MP] = slot;
+        } else if (row == 0) slot_s[tid / MP] = -1;
         ids[tid] = id;
-        if (bn == 0 && blockIdx.z == 0) a.ylab[slot * MP + tid] = (id == 0xFFFFFFFFu) ? -1 : a.y[id];
     }
     __syncthreads();
-    const int total = d / KT, per = (total + a.fsplit - 1) / a.fsplit;
-    const int stage0 = blockIdx.z * per, stages = max(0, min(per, total - stage0));
+    int stage0 = 0, stages = d / KT;
+    if constexpr (SPLIT) {
+        const int total = d / KT, per = (total + a.fsplit - 1) / a.fsplit;
+        stage0 = blockIdx.z * per;
+        stages = max(0, min(per, total - stage0));
+    }
     const int lchunk = tid & 7, lrow = tid >> 3;
     const float* xrow[LP];
     bool has[LP];
@@ -442,23 +452,32 @@ __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
 #pragma unroll
         for (int i = 0; i < LP; ++i) {
             const int row = lrow + 32 * i;
-            u16x8 v;
+            // eight floats -> bf16, round to nearest even, on the packed conversion unit
+            f32x8 w;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = has[i] ? bf16_bits(ra[Q][i][e >> 2][e & 3]) : (unsigned short)0;
-            *reinterpret_cast<u16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = v;
+            for (int e = 0; e < 8; ++e) w[e] = has[i] ? ra[Q][i][e >> 2][e & 3] : 0.0f;
+            *reinterpret_cast<bf16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = __builtin_convertvector(w, bf16x8);
             *reinterpret_cast<u16x8*>(Bs + (buf * BT + row) * LDT + 8 * lchunk) = rb[Q][i];
         }
     };
     const int wm = wave >> 1, wn = wave & 1;
-    f32x16 acc;
+    f32x16 acc[NF][NF];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+    for (int i = 0; i < NF; ++i)
+#pragma unroll
+        for (int j = 0; j < NF; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    // The transposed bf16 copy of the rows (read by the gradient contraction of a later update) is written by the
+    // workgroups with bn = 0.  (Sharing it out between the workgroups that read the same rows was measured slower: the
+    // 2-byte LDS reads of the transposition then delay the operand reads of every workgroup, not of a quarter of them.
+    // Likewise the thread mapping below: eight samples per thread instead of sixteen was slower by a third.)
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    using I2 = std::integral_constant<int, 2>;
+    using I2 = std::integral_constant<int, PF == 3 ? 2 : 0>;
     if (stages > 0) fetch(I0{}, stage0);
     if (stages > 1) fetch(I1{}, stage0 + 1);
-    if (stages > 2) fetch(I2{}, stage0 + 2);
+    if (PF == 3 && stages > 2) fetch(I2{}, stage0 + 2);
     if (stages > 0) stash(I0{}, 0);
     __syncthreads();
     auto one_stage = [&](auto cur, auto nxt, int st) {
@@ -466,40 +485,74 @@ __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
         if (st + PF < stages) fetch(cur, stage0 + st + PF);
 #pragma unroll
         for (int kk = 0; kk < KT / 16; ++kk) {
-            const bf16x8 fa = *reinterpret_cast<const bf16x8*>(As + (buf * BT + wm * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
-            const bf16x8 fb = *reinterpret_cast<const bf16x8*>(Bs + (buf * BT + wn * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+            bf16x8 fa[NF], fb[NF];
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8*>(As + (buf * BT + wm * WT + i * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8*>(Bs + (buf * BT + wn * WT + j * 32 + (lane & 31)) * LDT + kk * 16 + 8 * (lane >> 5));
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+#pragma unroll
+                for (int j = 0; j < NF; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
         if (bn == 0) {
-            // transposed copy of this stage's 64 x 64 block: thread -> feature tid / 4, samples 16 (tid % 4) .. + 15
+            // transposed copy of this stage's rows: thread -> feature tid / 4, samples 16 (tid % 4) .. + 15 of every record
             const int k = tid >> 2, part = tid & 3;
-            u16x8 v0, v1;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                v0[e] = As[(buf * BT + 16 * part + e) * LDT + k];
-                v1[e] = As[(buf * BT + 16 * part + 8 + e) * LDT + k];
+            for (int q = 0; q < RPT; ++q) {
+                const int slot = slot_s[q];
+                if (slot >= 0) {
+                    u16x8 v0, v1;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        v0[e] = As[(buf * BT + q * MP + 16 * part + e) * LDT + k];
+                        v1[e] = As[(buf * BT + q * MP + 16 * part + 8 + e) * LDT + k];
+                    }
+                    unsigned short* dst = a.xbt + ((int64_t)slot * d + (int64_t)(stage0 + st) * KT + k) * MP + 16 * part;
+                    *reinterpret_cast<u16x8*>(dst) = v0;
+                    *reinterpret_cast<u16x8*>(dst + 8) = v1;
+                }
             }
-            unsigned short* dst = a.xbt + ((int64_t)slot * d + (int64_t)(stage0 + st) * KT + k) * MP + 16 * part;
-            *reinterpret_cast<u16x8*>(dst) = v0;
-            *reinterpret_cast<u16x8*>(dst + 8) = v1;
         }
         if (st + 1 < stages) stash(nxt, buf ^ 1);
         __syncthreads();
     };
-    for (int st = 0; st < stages; st += PF) {
-        one_stage(I0{}, I1{}, st);
-        if (st + 1 < stages) one_stage(I1{}, I2{}, st + 1);
-        if (st + 2 < stages) one_stage(I2{}, I0{}, st + 2);
-    }
-    // partial sums of Z1: element e of lane -> row 8 (e / 4) + 4 (lane / 32) + e % 4, column lane % 32 of the wave's 32 x 32 block
-    {
-        float* out = a.dw_part + (((int64_t)blockIdx.z * a.nrec + r) * MP) * H + bn * BT + wn * 32 + (lane & 31);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int row = wm * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            out[(int64_t)row * H] = acc[e];
+    if constexpr (PF == 3) {
+        for (int st = 0; st < stages; st += 3) {
+            one_stage(I0{}, I1{}, st);
+            if (st + 1 < stages) one_stage(I1{}, I2{}, st + 1);
+            if (st + 2 < stages) one_stage(I2{}, I0{}, st + 2);
+        }
+    } else {
+        for (int st = 0; st < stages; st += 2) {
+            one_stage(I0{}, I1{}, st);
+            if (st + 1 < stages) one_stage(I1{}, I0{}, st + 1);
         }
     }
+    // result: element e of lane -> row 8 (e / 4) + 4 (lane / 32) + e % 4, column lane % 32 of a 32 x 32 block
+#pragma unroll
+    for (int i = 0; i < NF; ++i)
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            const int col = bn * BT + wn * WT + j * 32 + (lane & 31);
+            const float b1 = SPLIT ? 0.0f : a.params[(int64_t)H * d + col];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = wm * WT + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const int q = row / MP, r = RPT * bm + q;
+                if (r < a.nrec) {
+                    if constexpr (SPLIT) {
+                        a.dw_part[(((int64_t)blockIdx.z * a.nrec + r) * MP + (row % MP)) * H + col] = acc[i][j][e];
+                    } else {
+                        const float z = acc[i][j][e] + b1;
+                        a.hbuf[((int64_t)slot_s[q] * MP + (row % MP)) * H + col] = z > 0.0f ? z : 0.0f;
+                    }
+                }
+            }
+        }
 }
 
 // ---- Few records: everything between the two contractions in one launch ---------------------------------------
@@ -657,26 +710,6 @@ __global__ __launch_bounds__(256) void mlp_mid_kernel(MlpArgs a) {
     }
     if (tid == 16) a.loss[slot * 4 + q] = (red[0] + red[1]) + (red[2] + red[3]);
     if (tid == 17 && q == 0) a.quartered[slot] = 1;
-}
-
-// ---- hidden activations from the partial sums of a split forward pass: shares added in order, bias, ReLU --------
-__global__ __launch_bounds__(256) void mlp_fwd_finish_kernel(MlpArgs a) {
-    const int H = a.H, h4 = H / 4;
-    const int64_t total = (int64_t)a.nrec * MP * h4;
-    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (int64_t)gridDim.x * blockDim.x) {
-        const int n = 4 * (int)(q % h4);
-        const int64_t rr = q / h4;                      // record * MP + row
-        const int r = (int)(rr / MP), row = (int)(rr % MP);
-        int worker, ordinal, slot;
-        record_of(a, r, worker, ordinal, slot);
-        f32x4 v = *reinterpret_cast<const f32x4*>(a.dw_part + rr * H + n);
-        for (int z = 1; z < a.fsplit; ++z) v += *reinterpret_cast<const f32x4*>(a.dw_part + ((int64_t)z * a.nrec * MP + rr) * H + n);
-        const f32x4 b1 = *reinterpret_cast<const f32x4*>(a.params + (int64_t)H * a.d + n);
-        f32x4 h;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) { const float zc = v[c] + b1[c]; h[c] = zc > 0.0f ? zc : 0.0f; }
-        *reinterpret_cast<f32x4*>(a.hbuf + ((int64_t)slot * MP + row) * H + n) = h;
-    }
 }
 
 // ---- first-layer update from the partial sums of a split gradient contraction: shares added in order --------
@@ -1009,8 +1042,9 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<false, 128, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
-    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_contract_kernel<true, 64, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_mid_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)mid_lds_bytes(1024)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fwd_gather_kernel<128, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fwd_gather_kernel<64, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
 #undef TRY
     *out = s;
     return hipSuccess;
@@ -1051,21 +1085,17 @@ hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, 
             (int64_t)a.nrec * MP * a.H * 8 <= (int64_t)kMaxSplit * a.H * a.d) {
             // few records: two launches; the depth is split so that two workgroups share every CU and none walks all of d
             a.fsplit = std::max(2, std::min(getenv("SSGD_FS") ? atoi(getenv("SSGD_FS")) : 8, 512 / wgs64));
-            hipLaunchKernelGGL(mlp_fwd_gather_kernel, dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, true>), dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), contract_lds(64), stream, a);
             hipLaunchKernelGGL(mlp_mid_kernel, dim3(a.nrec * 4), dim3(256), mid_lds_bytes(a.H), stream, a);
+        } else if (a.nrec > 0 && ((a.nrec + 1) / 2) * (a.H / 128) >= 192) {
+            // many records: large tiles, the rows again straight from the sample matrix
+            hipLaunchKernelGGL((mlp_fwd_gather_kernel<128, false>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
+            hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
         } else if (a.nrec > 0) {
+            // in between: rows to bf16 first, then small tiles (the large ones would not fill the chip)
             hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
-            // small tiles while the large ones would not fill the chip
-            if (((a.nrec + 1) / 2) * (a.H / 128) >= 192) {
-                hipLaunchKernelGGL((mlp_contract_kernel<true, 128>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
-            } else if (wgs64 <= 128 && (int64_t)a.nrec * MP * a.H * 4 <= (int64_t)kMaxSplit * a.H * a.d) {
-                // few records: the depth is split so that the chip is full and no workgroup walks all of d
-                a.fsplit = std::max(2, std::min(4, 512 / wgs64));
-                hipLaunchKernelGGL((mlp_contract_kernel<true, 64, true>), dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), contract_lds(64), stream, a);
-                hipLaunchKernelGGL(mlp_fwd_finish_kernel, dim3(std::min(1024, (a.nrec * MP * (a.H / 4) + 255) / 256)), dim3(256), 0, stream, a);
-            } else {
-                hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
-            }
+            hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
             hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
             hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
         }
