@@ -30,8 +30,8 @@ struct McArgs {
 __device__ __forceinline__ double inf64() { return __longlong_as_double(0x7FF0000000000000LL); }
 
 // Ascending bitonic sort of 64*NQ keys; position p = q*64 + lane.
-template <int NQ>
-__device__ __forceinline__ void sort_keys(double (&key)[NQ], int lane) {
+template <int NQ, typename T>
+__device__ __forceinline__ void sort_keys(T (&key)[NQ], int lane) {
     constexpr int N = 64 * NQ;
 #pragma unroll
     for (int k = 2; k <= N; k <<= 1) {
@@ -41,7 +41,7 @@ __device__ __forceinline__ void sort_keys(double (&key)[NQ], int lane) {
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     const int p = q * 64 + lane;
-                    const double other = __shfl_xor(key[q], j, 64);
+                    const T other = __shfl_xor(key[q], j, 64);
                     const bool up = (p & k) == 0, lower = (p & j) == 0;
                     key[q] = (up == lower) ? fmin(key[q], other) : fmax(key[q], other);
                 }
@@ -52,7 +52,7 @@ __device__ __forceinline__ void sort_keys(double (&key)[NQ], int lane) {
                     if ((q & dq) == 0) {
                         const int p = q * 64 + lane;
                         const bool up = (p & k) == 0;
-                        const double a = key[q], b = key[q | dq];
+                        const T a = key[q], b = key[q | dq];
                         key[q] = up ? fmin(a, b) : fmax(a, b);
                         key[q | dq] = up ? fmax(a, b) : fmin(a, b);
                     }
@@ -103,7 +103,7 @@ __device__ __forceinline__ void sort_prefix_descending(double (&key)[NQ], int la
 template <int NQ>
 __device__ __forceinline__ void resort_prefix(double (&key)[NQ], int lane, int K) {
     constexpr int N = 64 * NQ;
-    if (2 * K > N) { sort_keys<NQ>(key, lane); return; }
+    if (2 * K > N) { sort_keys<NQ, double>(key, lane); return; }
     if (K > 64) { if constexpr (NQ > 2) sort_prefix_descending<NQ, 128>(key, lane); }
     else if (K > 32) sort_prefix_descending<NQ, 64>(key, lane);
     else if (K > 16) sort_prefix_descending<NQ, 32>(key, lane);
@@ -216,10 +216,16 @@ __global__ __launch_bounds__(64) void mc_kernel(McArgs a) {
             __syncthreads();
             continue;
         }
+        // the fresh draws are fp32 values: sorted as such (half the register traffic of the network), then widened
         double sorted0[NQ];
+        {
+            float fresh[NQ];
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) sorted0[q] = base[q];
-        sort_keys<NQ>(sorted0, lane);
+            for (int q = 0; q < NQ; ++q) fresh[q] = (float)base[q];
+            sort_keys<NQ, float>(fresh, lane);
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) sorted0[q] = (double)fresh[q];
+        }
 
         for (int K = a.Kmin + slice; K <= a.Kmax; K += a.nslices) {
             double key[NQ];
@@ -245,7 +251,7 @@ __global__ __launch_bounds__(64) void mc_kernel(McArgs a) {
                             const int w = q * 64 + lane;
                             key[q] = (w < P) ? (double)delay(a.dist, a.seed, kMonteCarlo, (uint32_t)K, trial, P, 1, w, 0, l) : inf64();
                         }
-                        if (a.variant == kSync) sort_keys<NQ>(key, lane);
+                        if (a.variant == kSync) sort_keys<NQ, double>(key, lane);
                     }
                     if (a.variant == kSync) {
                         t_new = t + key_at<NQ>(key, K - 1);

@@ -420,6 +420,17 @@ def test_mc_trials_bit_exact(ssgd, oracle, torch_cuda, variant, P, Kmax, spec):
     assert np.allclose(g["mean"], o["mean"], rtol=1e-12) and np.allclose(g["var"], o["var"], rtol=1e-9)
 
 
+@pytest.mark.parametrize("variant", ["k_async", "k_sync", "k_batch_async"])
+def test_mc_ten_thousand_trials_bit_exact(ssgd, oracle, torch_cuda, variant):
+    """The first 10^4 trials of one shape (P=16, every K, chains of 4 updates, shifted-exponential delays), trial by
+    trial and in the sums."""
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.2, 1.0))
+    g = ssgd.runtime_mc(variant, 16, 1, 16, gd, 10000, 4, seed=3, per_trial=True)
+    o = oracle.runtime_mc(variant, 16, 1, 16, od, 10000, 4, seed=3, per_trial=True)
+    assert np.array_equal(g["per_trial"], o["per_trial"])
+    assert np.allclose(g["sum"], o["sum"], rtol=1e-12) and np.allclose(g["sumsq"], o["sumsq"], rtol=1e-12)
+
+
 def test_mc_closed_forms_at_scale(ssgd, torch_cuda):
     """2e5 trials, P=128, all K: Exp(1) order statistics (App. B.1) for every update of the K-async chain
     (App. B.3); shifted exponential first update = shift + harmonic form; K-async <= K-sync afterwards."""
