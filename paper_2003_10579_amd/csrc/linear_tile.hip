@@ -127,7 +127,10 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     // (read from the arguments where it is possible at all: as a compile-time constant it led the compiler to keep
     // two tiles of gathered rows alive and spill them)
     const bool chunked = CHUNKED && a.chunked != 0;
-    const int mpt = chunked ? ROWS : mp;
+    // K-batch-async with mini-batches of more than 64 rows: a tile is one block of 64 rows of one record; the record's
+    // gradient is summed over its tiles in the slot of its worker
+    const int spr = (BATCH && mp > ROWS) ? (mp + ROWS - 1) / ROWS : 1;      // tiles per record
+    const int mpt = (chunked || spr > 1) ? ROWS : mp;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const Lds L = carve(smem, C, S);
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
         int h_first = 0, h_trig = 0, h_trig_fresh = 0, h_nstale = 0;
         int h_rw = 0, h_ro = 0, h_rf = 0;        // lane j: worker, ordinal, consumed-by-this-update flag of restart j
         int h_csel = -1, h_ctau = -1, h_cord = 0;   // lane l: entry l of the consume list of the version
-        const int rpt = ROWS / mp;               // K-batch-async: whole records per tile
+        const int rpt = spr > 1 ? 1 : ROWS / mp; // K-batch-async: whole records per tile (or one block of a record)
         auto take_lists = [&](int64_t ver, bool more) {
             const int l_sel = q_sel, l_tau = q_tau, l_ord = q_ord;
             const int K = __popcll(__ballot(l_sel >= 0));
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             h_tiles = chunked ? max(1, (nrec * mp + ROWS - 1) / ROWS) : 1;
             if constexpr (BATCH) {
                 h_nstale = n_nstale;
-                h_tiles = max(1, (nrec + rpt - 1) / rpt);
+                h_tiles = spr > 1 ? max(1, nrec * spr) : max(1, (nrec + rpt - 1) / rpt);
             }
             cur_sel = l_sel;
             asm volatile("" : "+v"(n_stale), "+v"(n_stale_pos), "+v"(n_rec_word), "+v"(cur_sel), "+v"(h_worker), "+v"(h_ord) : : "memory");
@@ -255,8 +258,11 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             int worker, ordinal;
             if constexpr (BATCH) {
                 // records t * rpt .. of the version; the parked part of the update comes with the first tile
-                rec = (r_of < rpt) ? t * rpt + r_of : 0x7FFFFFF;
-                n_nrec = min(rpt, h_nrec - t * rpt);
+                const int tr0 = spr > 1 ? t / spr : t * rpt;       // first record of the tile
+                const int blk = spr > 1 ? t % spr : 0;             // which block of 64 rows of its record
+                rec = (r_of < rpt) ? tr0 + r_of : 0x7FFFFFF;
+                if (spr > 1) { rec = tr0; smp = ROWS * blk + lane; }
+                n_nrec = spr > 1 ? 1 : min(rpt, h_nrec - t * rpt);
                 n_nstale = (t == 0) ? h_nstale : 0;
                 // worker, ordinal and consumed-by-this-update flag of record q
                 auto describe = [&](int q, int& w, int& o, int& f) {
@@ -269,7 +275,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 int fr;
                 describe(rec, worker, ordinal, fr);
                 int qw, qo, qf;
-                describe(t * rpt + lane, qw, qo, qf);
+                describe(tr0 + lane, qw, qo, qf);
                 if (ver == 0) {
                     // every worker's first mini-batch: consumed by update 0 if the list holds (worker, version 0, ordinal 0)
                     const int Kv = n_K;
@@ -279,7 +285,9 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                             __builtin_amdgcn_readlane(h_cord, e) == 0) hit = 1;
                     if (qf < 0) qf = hit;
                 }
-                n_rec_word = (lane < n_nrec) ? (qw | (qf << 16)) : 0;
+                // bit 16: consumed by the update of its own version; bit 17: the record goes on in the next tile; bit 18: it
+                // began in an earlier tile
+                n_rec_word = (lane < n_nrec) ? (qw | (qf << 16) | ((blk + 1 < spr ? 1 : 0) << 17) | ((blk > 0 ? 1 : 0) << 18)) : 0;
             } else {
                 worker = __shfl(h_worker, min(rec, 63), 64);
                 ordinal = __shfl(h_ord, min(rec, 63), 64);
@@ -355,7 +363,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 const float part = p0 + p1;
                 const int word = have ? L.s_rec[r] : 0;
                 if (have) {
-                    if ((word >> 16) != 0) tot += part;
+                    if (((word >> 16) & 1) != 0) tot += part;
+                    else if (((word >> 18) & 1) != 0) L.small[(word & 0xFFFF) * 17 + sidx] += part;    // a later block of its record
                     else L.small[(word & 0xFFFF) * 17 + sidx] = part;
                 }
             }
@@ -767,7 +776,23 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             auto finish = [&](int r) {
                 if constexpr (PROF) { asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])); mark(11); }
                 const int word = __builtin_amdgcn_readfirstlane(r == 0 ? rec01.x : (r == 1 ? rec01.y : L.s_rec[r]));
-                if ((word >> 16) != 0) {
+                bool to_sum = ((word >> 16) & 1) != 0;
+                if constexpr (BATCH) {
+                    // A record of several tiles is summed in its worker's slot (free by now: what it held was consumed
+                    // by an earlier update or with the first tile of this one): later blocks add what is there, and
+                    // only the last one goes to the aggregate if the update consumes the record itself.
+                    if (((word >> 18) & 1) != 0) {
+                        const int soff = (word & 0xFFFF) * 16 * NTC * 4;
+#pragma unroll
+                        for (int vv = 0; vv < 4; ++vv) {
+                            const f32x4 pv = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(prsrc, pk_off[vv], soff, 0));
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) acc[c][vv] += pv[c];
+                        }
+                    }
+                    if (((word >> 17) & 1) != 0) to_sum = false;
+                }
+                if (to_sum) {
 #pragma unroll
                     for (int vv = 0; vv < 4; ++vv)
 #pragma unroll
@@ -815,7 +840,7 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
                 auto done = [&](int r) {
                     if constexpr (PROF) { asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])); mark(11); }
                     const int word = __builtin_amdgcn_readfirstlane(r == 0 ? rec01.x : rec01.y);
-                    if ((word >> 16) != 0) {
+                    if (((word >> 16) & 1) != 0) {
 #pragma unroll
                         for (int vv = 0; vv < 4; ++vv)
 #pragma unroll
@@ -979,8 +1004,7 @@ bool linear_tile_supports(const LinArgs& a, int max_records) {
     if (a.chunked && a.variant == kAsync) return false;
     if ((uint64_t)a.N * (uint64_t)a.d * 4u >= (1ull << 32)) return false;   // one buffer descriptor spans the sample matrix
     if (a.variant == kBatchAsync) {
-        // whole records per tile; the consume list and the restarts of an update sit in one lane each
-        if (a.mp > ROWS) return false;
+        // whole records per tile, or tiles of one record; the consume list and the restarts of an update sit in one lane each
         return linear_tile_lds_bytes(a.C, a.S) <= 160 * 1024;
     }
     if (a.variant == kAsync && a.v0 < 1) return false;    // step 0 of K-async starts all P workers

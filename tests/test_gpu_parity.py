@@ -878,6 +878,10 @@ def test_mlp_snapshot_resume(ssgd, oracle, torch_cuda, variant, K):
     ("softmax", 64, 16, 32, 320, 10, ("pareto", 2.5, 1.0)),       # config 2's workers and K: 79 records at version 0
     ("lsq", 200, 3, 8, 64, 1, ("exp", 1.0)),                      # 202 records at version 0, 8 per tile
     ("softmax", 130, 32, 64, 260, 3, ("exp", 1.0)),               # one record per tile, 161 tiles at version 0, K = 32
+    ("softmax", 6, 4, 128, 260, 10, ("shifted_exp", 0.5, 1.0)),   # mini-batches of two tiles
+    ("lsq", 5, 3, 72, 132, 1, ("exp", 1.0)),                      # 72 rows: a full tile and one of 8 rows per record
+    ("softmax", 4, 6, 200, 516, 7, ("pareto", 2.5, 1.0)),         # four tiles per record (the last of 8 rows), K > P
+    ("softmax", 64, 16, 128, 320, 10, ("pareto", 2.5, 1.0)),      # config 2's P, K and m: 158 tiles at version 0
 ])
 def test_kbatch_async_parity(ssgd, oracle, torch_cuda, kind, P, K, m, d, classes, spec):
     """K-batch-async (Sec. 2.2): delays, selections, ordinals and staleness bit for bit, per-update averaged gradients
@@ -921,8 +925,8 @@ def test_kbatch_async_unsupported_shapes_are_refused(ssgd, torch_cuda):
     torch = torch_cuda
     X, y, _ = synth.lsq_data(64, 66, 1)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
-    for P, K, m, cols in ((4, 2, 8, 66), (4, 2, 100, 64), (8, 33, 8, 64)):
-        # d % 4 != 0; m > 64; K > 32
+    for P, K, m, cols in ((4, 2, 8, 66), (8, 33, 8, 64)):
+        # d % 4 != 0; K > 32
         Xc = Xd[:, :cols].contiguous()
         with pytest.raises(ssgd.SsgdError):
             ssgd.Context("lsq", Xc, yd, P, K, m, "k_batch_async", ssgd.delay_dist("exp", 1.0), 0.01)
