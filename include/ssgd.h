@@ -105,8 +105,8 @@ typedef struct {
  * the MLP).  `hip_stream` is a hipStream_t (NULL = default stream); all work
  * is enqueued there.  `adasync` may be NULL (mode 0).
  * Limits: 1 <= K <= P <= 256 for K-sync / K-async, 1 <= K <= 256 for the batch
- * variants, m >= 1, d >= 1, classes <= 16 for SOFTMAX; MLP2 needs replicas == 1,
- * bf16 = 1, m <= 64, d % 128 == 0, hidden % 128 == 0;
+ * variants, m >= 1, d >= 1, classes <= 16 for SOFTMAX; MLP2 needs bf16 = 1, m <= 64,
+ * d % 128 == 0, hidden % 128 == 0, and with several replicas a fixed K or AdaSync mode 1;
  * SSGD_K_BATCH_ASYNC has the limits given with the enumeration.  Invalid arguments give
  * SSGD_EINVAL and leave *out untouched. */
 ssgd_status ssgd_create(const ssgd_model *model, int32_t P, int32_t K, int32_t m, int32_t variant,

@@ -57,7 +57,7 @@ struct ssgd_ctx {
     DevBuf params, park, park_small, zpart, zx, dx, fallback, arrive, abort_flag, xcc_ids, prof;
     int resident_groups = 0;
     size_t lds_bytes = 0;
-    MlpState* mlp = nullptr;
+    std::vector<MlpState*> mlp;      // two-layer network: one state per replica
 
     double last_ms = 0;
     int64_t last_launches = 0;
@@ -361,7 +361,7 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
                 e = hipStreamWaitEvent(c->stream, written[k], 0);
                 if (e != hipSuccess) break;
                 if (c->model.kind == SSGD_MLP2)
-                    e = mlp_run_segment(c->mlp, c->tr, c->ws, c->j + off, std::min(kPiece, seg - off), agg_out, c->stream,
+                    e = mlp_run_segment(c->mlp.data(), c->R, c->tr, c->ws, c->j + off, std::min(kPiece, seg - off), agg_out, c->stream,
                                         &c->last_ms, &c->last_launches, &msg);
                 else
                     lin_st = run_segment_linear(c, c->j + off, std::min(kPiece, seg - off), agg_out, &events);
@@ -391,7 +391,7 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
             // done above
         } else if (c->model.kind == SSGD_MLP2) {
             std::string msg;
-            hipError_t e = mlp_run_segment(c->mlp, c->tr, c->ws, c->j, seg, agg_out, c->stream, &c->last_ms, &c->last_launches, &msg);
+            hipError_t e = mlp_run_segment(c->mlp.data(), c->R, c->tr, c->ws, c->j, seg, agg_out, c->stream, &c->last_ms, &c->last_launches, &msg);
             if (e != hipSuccess) { c->broken = true; return fail(c, SSGD_EDEVICE, "mlp segment: " + msg); }
         } else {
             st = run_segment_linear(c, c->j, seg, agg_out, &events);
@@ -469,8 +469,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
     } else if (model->kind == SSGD_MLP2) {
         // the same limits as mlp_create, so that every invalid shape is refused here, before anything is allocated
         if (model->classes < 2 || model->classes > kClassPad || model->hidden < 128 || model->hidden % 128 || model->d % 128 ||
-            replicas != 1 || !model->bf16 || m > 64)
-            return fail(nullptr, SSGD_EINVAL, "MLP needs 2..16 classes, hidden % 128 == 0, d % 128 == 0, m <= 64, bf16 = 1, replicas == 1");
+            !model->bf16 || m > 64 || (replicas > 1 && ada.mode >= 2))
+            return fail(nullptr, SSGD_EINVAL, "MLP needs 2..16 classes, hidden % 128 == 0, d % 128 == 0, m <= 64, bf16 = 1; several replicas with a fixed K or plateau doubling only");
     } else {
         return fail(nullptr, SSGD_EINVAL, "unknown model kind");
     }
@@ -517,9 +517,13 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
 
     if (model->kind == SSGD_MLP2) {
         std::string msg;
-        hipError_t e = mlp_create(&c->mlp, *model, P, m, variant, Kcap, lr, seed, c->stream, &msg);
-        if (e != hipSuccess)
-            return bail(e == hipErrorOutOfMemory ? SSGD_ENOMEM : (e == hipErrorInvalidValue ? SSGD_EINVAL : SSGD_EDEVICE), "mlp_create: " + msg);
+        for (int r = 0; r < replicas; ++r) {
+            MlpState* ms = nullptr;
+            hipError_t e = mlp_create(&ms, *model, P, m, variant, Kcap, lr, seed, r, c->stream, &msg);
+            if (e != hipSuccess)
+                return bail(e == hipErrorOutOfMemory ? SSGD_ENOMEM : (e == hipErrorInvalidValue ? SSGD_EINVAL : SSGD_EDEVICE), "mlp_create: " + msg);
+            c->mlp.push_back(ms);
+        }
     } else {
         const int d = model->d;
         c->nbw = d <= 64 ? 1 : (d <= 128 ? 2 : 4);
@@ -631,7 +635,7 @@ ssgd_status ssgd_get_params(ssgd_ctx* c, int32_t replica, float* w_out) {
     if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
     HIP_OK(c, hipSetDevice(c->device));
     HIP_OK(c, hipStreamSynchronize(c->stream));
-    const float* src = c->model.kind == SSGD_MLP2 ? mlp_params(c->mlp) : c->params.as<float>() + (int64_t)replica * c->nw;
+    const float* src = c->model.kind == SSGD_MLP2 ? mlp_params(c->mlp[(size_t)replica]) : c->params.as<float>() + (int64_t)replica * c->nw;
     HIP_OK(c, hipMemcpy(w_out, src, sizeof(float) * c->nw, hipMemcpyDeviceToHost));
     return SSGD_OK;
 }
@@ -641,7 +645,7 @@ ssgd_status ssgd_set_params(ssgd_ctx* c, int32_t replica, const float* w_in) {
     if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
     HIP_OK(c, hipSetDevice(c->device));
     HIP_OK(c, hipStreamSynchronize(c->stream));
-    float* dst = c->model.kind == SSGD_MLP2 ? mlp_params(c->mlp) : c->params.as<float>() + (int64_t)replica * c->nw;
+    float* dst = c->model.kind == SSGD_MLP2 ? mlp_params(c->mlp[(size_t)replica]) : c->params.as<float>() + (int64_t)replica * c->nw;
     HIP_OK(c, hipMemcpy(dst, w_in, sizeof(float) * c->nw, hipMemcpyHostToDevice));
     return SSGD_OK;
 }
@@ -664,7 +668,8 @@ ssgd_status ssgd_full_loss(ssgd_ctx* c, int32_t replica, double* loss_out) {
     if (c->model.kind == SSGD_MLP2) {
         HIP_OK(c, hipSetDevice(c->device));
         std::string msg;
-        hipError_t em = mlp_full_loss(c->mlp, loss_out, c->stream, &msg);
+        HIP_OK(c, hipStreamSynchronize(c->stream));
+        hipError_t em = mlp_full_loss(c->mlp[(size_t)replica], loss_out, c->stream, &msg);
         if (em == hipErrorOutOfMemory) return fail(c, SSGD_ENOMEM, "full objective: " + msg);
         if (em != hipSuccess) return fail(c, SSGD_EDEVICE, "full objective: " + msg);
         return SSGD_OK;
@@ -775,7 +780,8 @@ StateHeader make_header(ssgd_ctx* c) {
     h.kind = c->model.kind; h.d = c->model.d; h.classes = c->model.classes; h.hidden = c->model.hidden;
     h.P = c->P; h.m = c->m; h.variant = c->variant; h.R = c->R; h.Kcap = c->Kcap; h.S = c->S; h.G = c->G;
     h.ada_mode = c->ada.mode; h.N = c->model.N; h.nw = c->nw; h.j = c->j; h.seed = c->seed; h.win_cnt = c->win_cnt;
-    h.mlp_bytes = c->mlp ? mlp_state_bytes(c->mlp) : 0;
+    h.mlp_bytes = 0;
+    for (MlpState* ms : c->mlp) h.mlp_bytes += mlp_state_bytes(ms);
     int64_t n = (int64_t)sizeof(StateHeader) + trace_bytes(c, c->j) + h.mlp_bytes;
     for (DevBuf* b : state_buffers(c)) n += (int64_t)b->bytes;
     h.total_bytes = n;
@@ -814,7 +820,10 @@ ssgd_status ssgd_get_state(ssgd_ctx* c, void* host_buf, int64_t bytes) {
         HIP_OK(c, hipMemcpy(out + off, b->p, b->bytes, hipMemcpyDeviceToHost));
         off += b->bytes;
     }
-    if (c->mlp) HIP_OK(c, mlp_get_state(c->mlp, out + off));
+    for (MlpState* ms : c->mlp) {
+        HIP_OK(c, mlp_get_state(ms, out + off));
+        off += (size_t)mlp_state_bytes(ms);
+    }
     return SSGD_OK;
 }
 
@@ -862,7 +871,10 @@ ssgd_status ssgd_set_state(ssgd_ctx* c, const void* host_buf, int64_t bytes) {
         HIP_OK(c, hipMemcpy(b->p, in + off, b->bytes, hipMemcpyHostToDevice));
         off += b->bytes;
     }
-    if (c->mlp) HIP_OK(c, mlp_set_state(c->mlp, in + off));
+    for (MlpState* ms : c->mlp) {
+        HIP_OK(c, mlp_set_state(ms, in + off));
+        off += (size_t)mlp_state_bytes(ms);
+    }
     c->j = h.j;
     c->win_cnt = h.win_cnt;
     guard.ok = true;
@@ -973,7 +985,7 @@ void ssgd_destroy(ssgd_ctx* c) {
                 fprintf(stderr, "\n");
             }
     }
-    if (c->mlp) mlp_destroy(c->mlp);
+    for (MlpState* ms : c->mlp) mlp_destroy(ms);
     if (c->side) (void)hipStreamDestroy(c->side);
     DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,
                       &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx, &c->ws_F0,

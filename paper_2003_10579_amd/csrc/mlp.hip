@@ -51,7 +51,8 @@ struct MlpArgs {
     const int32_t* y;
     uint32_t N;
     uint64_t seed;
-    Trace tr;
+    uint32_t rep;              // replica: a field of the counters of its delays and sample ids
+    Trace tr;                  // this replica's rows
     int64_t v;
     int32_t nrec, Kv;
     float lr;
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(256) void mlp_gather_kernel(MlpArgs a) {
             const int64_t row = a.eval_base + (int64_t)r * MP + tid;
             if (row < (int64_t)a.N) id = (uint32_t)row;
         } else if (tid < a.m) {
-            id = batch_index(a.seed, 0u, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)tid, a.N);
+            id = batch_index(a.seed, a.rep, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)tid, a.N);
         }
         ids[tid] = id;
         if (cb == 0) a.ylab[slot * MP + tid] = (id == 0xFFFFFFFFu) ? -1 : a.y[id];
@@ -413,7 +414,7 @@ __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
         if (r < a.nrec) {
             int worker, ordinal, slot;
             record_of(a, r, worker, ordinal, slot);
-            if (row < a.m) id = batch_index(a.seed, 0u, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)row, a.N);
+            if (row < a.m) id = batch_index(a.seed, a.rep, (uint32_t)worker, (uint32_t)ordinal, (uint32_t)a.v, (uint32_t)row, a.N);
             if (bn == 0 && blockIdx.z == 0) a.ylab[slot * MP + row] = (id == 0xFFFFFFFFu) ? -1 : a.y[id];
             if (row == 0) slot_s[tid / MP] = slot;
         } else if (row == 0) slot_s[tid / MP] = -1;
@@ -970,12 +971,14 @@ struct MlpState {
     int S = 0;
     int64_t nw = 0;
     int prevK = 0;          // size of the consume list of the last update run (records of the next K-async step)
+    int replica = 0;
+    hipStream_t own = nullptr;   // replicas beyond the first run on streams of their own, beside each other
     DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, dw_part, plan, quartered;
     hipStream_t stream = nullptr;
 };
 
 hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int variant, int Kcap, double lr,
-                      uint64_t seed, hipStream_t stream, std::string* msg) {
+                      uint64_t seed, int replica, hipStream_t stream, std::string* msg) {
     auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
     if (!model.bf16) return fail(hipErrorInvalidValue, "the MLP runs with bf16 operands only (model.bf16 = 1)");
     if (m > MP) return fail(hipErrorInvalidValue, "the MLP keeps at most 64 rows per mini-batch");
@@ -983,7 +986,9 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     if (model.classes > 16) return fail(hipErrorInvalidValue, "at most 16 classes");
     MlpState* s = new MlpState();
     s->stream = stream;
+    s->replica = replica;
     MlpArgs& a = s->a;
+    a.rep = (uint32_t)replica;
     a.d = model.d; a.H = model.hidden; a.C = model.classes; a.P = P; a.m = m; a.variant = variant; a.Kcap = Kcap;
     a.X = model.X; a.y = (const int32_t*)model.y; a.N = (uint32_t)model.N; a.seed = seed; a.lr = (float)lr;
     s->S = (variant == kAsync) ? P : (variant == kBatchAsync ? P + Kcap : Kcap);
@@ -1050,80 +1055,138 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     return hipSuccess;
 }
 
-hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n, float* agg_out,
-                           hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg) {
-    auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
-    MlpArgs a = s->a;
-    a.tr = tr;
-    a.agg_out = agg_out;
-    const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
-    // the parameters may have been set from outside since the last segment
-    hipLaunchKernelGGL(mlp_refresh_kernel, dim3(1024), dim3(256), 0, stream, a.params, a.w1r, a.w2r, n1, off2, n2);
-    // K is constant inside a segment; it is read back once
-    std::vector<int32_t> Ks((size_t)n);
-    hipError_t e = hipMemcpyAsync(Ks.data(), tr.K + v0, sizeof(int32_t) * n, hipMemcpyDeviceToHost, stream);
-    if (e != hipSuccess) return fail(e, "reading K of the segment");
-    e = hipStreamSynchronize(stream);
-    if (e != hipSuccess) return fail(e, "reading K of the segment");
-    int32_t prevK = 0;
-    if (a.variant == kAsync && v0 > 0) {
-        e = hipMemcpy(&prevK, tr.K + (v0 - 1), sizeof(int32_t), hipMemcpyDeviceToHost);
-        if (e != hipSuccess) return fail(e, "reading K of the previous update");
+namespace {
+
+// this replica's rows of the trace
+Trace trace_of(const Trace& tr, int r) {
+    Trace t = tr;
+    t.t += (int64_t)r * tr.cap; t.loss += (int64_t)r * tr.cap; t.K += (int64_t)r * tr.cap;
+    t.sel += (int64_t)r * tr.cap * tr.Kcap; t.tau += (int64_t)r * tr.cap * tr.Kcap; t.ord += (int64_t)r * tr.cap * tr.Kcap;
+    return t;
+}
+
+// the launches of one update (a.v, a.Kv, a.nrec set) on `stream`
+void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
+    if (a.variant == kBatchAsync) hipLaunchKernelGGL(mlp_batch_plan_kernel, dim3(1), dim3(64), 0, stream, a);
+    const int wgs64 = a.nrec * (a.H / 64);
+    if (a.nrec > 0 && a.nrec <= kSmallRec && wgs64 <= 128 && a.H <= 1024 &&
+        (int64_t)a.nrec * MP * a.H * 8 <= (int64_t)kMaxSplit * a.H * a.d) {
+        // few records: two launches; the depth is split so that two workgroups share every CU and none walks all of d
+        a.fsplit = std::max(2, std::min(8, 512 / wgs64));
+        hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, true>), dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), contract_lds(64), stream, a);
+        hipLaunchKernelGGL(mlp_mid_kernel, dim3(a.nrec * 4), dim3(256), mid_lds_bytes(a.H), stream, a);
+    } else if (a.nrec > 0 && ((a.nrec + 1) / 2) * (a.H / 128) >= 192) {
+        // many records: large tiles, the rows again straight from the sample matrix
+        hipLaunchKernelGGL((mlp_fwd_gather_kernel<128, false>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
+        hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
+    } else if (a.nrec > 0) {
+        // in between: rows to bf16 first, then small tiles (the large ones would not fill the chip)
+        hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
+        hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
     }
-    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (a.Kv >= 64) {
+        // many slots: 128 x 128 tiles (half the operand traffic of the small ones), the slots split into shares so
+        // that the chip is still full; the shares are added, in order, by the update kernel
+        a.nsplit = std::min(kMaxSplit, a.Kv / 16);
+        hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3(a.H / 128, a.d / 128, a.nsplit), dim3(256), contract_lds(128), stream, a);
+        hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
+    } else {
+        // small tiles: 384 workgroups instead of 96 matter more than the reuse inside a larger tile; one more row of
+        // workgroups takes the small parameters
+        hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64 + 1), dim3(256), contract_lds(64), stream, a);
+    }
+    (void)s;
+}
+
+}  // namespace
+
+// Updates [v0, v0 + n) of every replica.  The replicas are independent runs: replica r's launches go to a stream of
+// its own (created here, default priority), update by update in turn, so that the latency chains of the replicas'
+// small kernels overlap on the device; the streams start after everything queued on `stream` and `stream` waits for them.
+hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n,
+                           float* agg_out, hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg) {
+    auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
+    std::vector<MlpArgs> args((size_t)R);
+    std::vector<std::vector<int32_t>> Ks((size_t)R, std::vector<int32_t>((size_t)n));
+    std::vector<int32_t> prevK((size_t)R, 0);
+    hipError_t e = hipSuccess;
+    for (int r = 0; r < R && e == hipSuccess; ++r) {
+        MlpState* s = states[r];
+        MlpArgs& a = args[(size_t)r];
+        a = s->a;
+        a.tr = trace_of(tr, r);
+        a.agg_out = r == 0 ? agg_out : nullptr;
+        const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
+        // the parameters may have been set from outside since the last segment
+        hipLaunchKernelGGL(mlp_refresh_kernel, dim3(1024), dim3(256), 0, stream, a.params, a.w1r, a.w2r, n1, off2, n2);
+        // K is constant inside a segment; it is read back once
+        e = hipMemcpyAsync(Ks[(size_t)r].data(), a.tr.K + v0, sizeof(int32_t) * n, hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess && a.variant == kAsync && v0 > 0)
+            e = hipMemcpyAsync(&prevK[(size_t)r], a.tr.K + (v0 - 1), sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+        if (r > 0 && s->own == nullptr && e == hipSuccess) e = hipStreamCreateWithFlags(&s->own, hipStreamNonBlocking);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(e, "reading K of the segment");
+    hipEvent_t e0 = nullptr, e1 = nullptr, fork = nullptr;
     (void)hipEventCreate(&e0); (void)hipEventCreate(&e1);
+    (void)hipEventCreateWithFlags(&fork, hipEventDisableTiming);
+    auto drop = [&]() { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipEventDestroy(fork); };
     (void)hipEventRecord(e0, stream);
+    (void)hipEventRecord(fork, stream);
+    for (int r = 1; r < R; ++r) (void)hipStreamWaitEvent(states[r]->own, fork, 0);
+    // the K of every update is checked before anything is launched
+    for (int r = 0; r < R; ++r) {
+        const MlpArgs& a = args[(size_t)r];
+        const std::vector<int32_t>& K = Ks[(size_t)r];
+        for (int64_t q = 0; q < n; ++q) {
+            const int64_t v = v0 + q;
+            int nrec = (a.variant == kAsync) ? (v == 0 ? a.P : (q == 0 ? prevK[(size_t)r] : K[(size_t)q - 1])) : K[(size_t)q];
+            if (a.variant == kBatchAsync) nrec = (v == 0 ? a.P : 1) + K[(size_t)q] - 1;
+            if (K[(size_t)q] < 1 || K[(size_t)q] > a.Kcap || nrec < 0 || nrec > states[r]->S) {
+                drop();
+                return fail(hipErrorInvalidValue, "inconsistent K in the trace");
+            }
+        }
+    }
+    // update by update, the replicas in turn: nothing in one replica's launches depends on another's.  (Launching every
+    // replica from a host thread of its own gave the same rate: the device, not the host, is what limits it.)
     for (int64_t q = 0; q < n; ++q) {
-        a.v = v0 + q;
-        a.Kv = Ks[(size_t)q];
-        a.nrec = (a.variant == kAsync) ? (a.v == 0 ? a.P : (q == 0 ? prevK : Ks[(size_t)q - 1])) : a.Kv;
-        if (a.variant == kBatchAsync) a.nrec = (a.v == 0 ? a.P : 1) + a.Kv - 1;
-        if (a.Kv < 1 || a.Kv > a.Kcap || a.nrec < 0 || a.nrec > s->S) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return fail(hipErrorInvalidValue, "inconsistent K in the trace"); }
-        if (a.variant == kBatchAsync) hipLaunchKernelGGL(mlp_batch_plan_kernel, dim3(1), dim3(64), 0, stream, a);
-        const int wgs64 = a.nrec * (a.H / 64);
-        if (a.nrec > 0 && a.nrec <= kSmallRec && wgs64 <= 128 && a.H <= 1024 &&
-            (int64_t)a.nrec * MP * a.H * 8 <= (int64_t)kMaxSplit * a.H * a.d) {
-            // few records: two launches; the depth is split so that two workgroups share every CU and none walks all of d
-            a.fsplit = std::max(2, std::min(getenv("SSGD_FS") ? atoi(getenv("SSGD_FS")) : 8, 512 / wgs64));
-            hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, true>), dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), contract_lds(64), stream, a);
-            hipLaunchKernelGGL(mlp_mid_kernel, dim3(a.nrec * 4), dim3(256), mid_lds_bytes(a.H), stream, a);
-        } else if (a.nrec > 0 && ((a.nrec + 1) / 2) * (a.H / 128) >= 192) {
-            // many records: large tiles, the rows again straight from the sample matrix
-            hipLaunchKernelGGL((mlp_fwd_gather_kernel<128, false>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
-            hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
-            hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
-        } else if (a.nrec > 0) {
-            // in between: rows to bf16 first, then small tiles (the large ones would not fill the chip)
-            hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
-            hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
-            hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
-            hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
+        for (int r = 0; r < R; ++r) {
+            MlpArgs& a = args[(size_t)r];
+            const std::vector<int32_t>& K = Ks[(size_t)r];
+            a.v = v0 + q;
+            a.Kv = K[(size_t)q];
+            a.nrec = (a.variant == kAsync) ? (a.v == 0 ? a.P : (q == 0 ? prevK[(size_t)r] : K[(size_t)q - 1])) : a.Kv;
+            if (a.variant == kBatchAsync) a.nrec = (a.v == 0 ? a.P : 1) + a.Kv - 1;
+            launch_update(states[r], a, r == 0 ? stream : states[r]->own);
         }
-        if (a.Kv >= 64) {
-            // many slots: 128 x 128 tiles (half the operand traffic of the small ones), the slots split into shares so
-            // that the chip is still full; the shares are added, in order, by the update kernel
-            a.nsplit = std::min(kMaxSplit, a.Kv / 16);
-            hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3(a.H / 128, a.d / 128, a.nsplit), dim3(256), contract_lds(128), stream, a);
-            hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
-            hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
-        } else {
-            // small tiles: 384 workgroups instead of 96 matter more than the reuse inside a larger tile; one more row of
-            // workgroups takes the small parameters
-            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64 + 1), dim3(256), contract_lds(64), stream, a);
+    }
+    if (launches) *launches += n;
+    // the first replica's stream waits for the others
+    for (int r = 1; r < R; ++r) {
+        hipEvent_t done = nullptr;
+        if (hipEventCreateWithFlags(&done, hipEventDisableTiming) == hipSuccess) {
+            (void)hipEventRecord(done, states[r]->own);
+            (void)hipStreamWaitEvent(stream, done, 0);
+            (void)hipEventDestroy(done);
         }
-        if (launches) *launches += 1;
     }
     (void)hipEventRecord(e1, stream);
     e = hipStreamSynchronize(stream);
     float ms = 0.0f;
     if (e == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms_accum) *ms_accum += ms;
-    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    drop();
     if (e != hipSuccess) return fail(e, "running the segment");
     e = hipGetLastError();
     if (e != hipSuccess) return fail(e, "launching the segment");
-    if (a.variant == kBatchAsync) {
+    for (int r = 0; r < R; ++r) {
+        if (args[(size_t)r].variant != kBatchAsync) continue;
         int32_t meta[4] = {0, 0, 0, 0};
-        e = hipMemcpy(meta, a.plan, sizeof(meta), hipMemcpyDeviceToHost);
+        e = hipMemcpy(meta, args[(size_t)r].plan, sizeof(meta), hipMemcpyDeviceToHost);
         if (e != hipSuccess) return fail(e, "reading the slot plan");
         if (meta[2] != 0) return fail(hipErrorInvalidValue, "the slot pool of K-batch-async ran dry: inconsistent trace");
     }
@@ -1220,6 +1283,7 @@ float* mlp_params(MlpState* s) { return s ? (float*)s->params.p : nullptr; }
 
 void mlp_destroy(MlpState* s) {
     if (!s) return;
+    if (s->own) { (void)hipStreamSynchronize(s->own); (void)hipStreamDestroy(s->own); }
     DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss, &s->ylab,
                       &s->dw_part, &s->plan, &s->quartered};
     for (DevMem* b : bufs) b->release();

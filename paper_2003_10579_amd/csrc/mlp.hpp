@@ -9,11 +9,12 @@ namespace ssgd {
 
 struct MlpState;
 
+// One state per replica (independent runs that differ in the replica field of their random draws).
 hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int variant, int Kcap, double lr,
-                      uint64_t seed, hipStream_t stream, std::string* msg);
-// Runs updates [v0, v0+n) whose schedule is already in the trace.
-hipError_t mlp_run_segment(MlpState* s, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n, float* agg_out,
-                           hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg);
+                      uint64_t seed, int replica, hipStream_t stream, std::string* msg);
+// Runs updates [v0, v0+n) of all R replicas, whose schedules are already in the trace; agg_out: replica 0's.
+hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n,
+                           float* agg_out, hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg);
 float* mlp_params(MlpState* s);
 // Objective over the whole data set at the current parameters, with the trainer's forward pass.
 hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::string* msg);

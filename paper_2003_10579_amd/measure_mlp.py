@@ -5,7 +5,9 @@ shifted-exponential delays; K is forced to 8, 16, ..., 256 in turn (the controll
 it) and 200 updates are timed at each.  Prints one JSON line per K: microseconds per update,
 worker-gradients/s, and the rate of the two bf16 contractions (hidden layer forward, first-layer gradient)
 against the 2.5 PFLOP/s dense bf16 MFMA peak.  `--full [J]` runs the whole AdaSync schedule of config 4
-instead (J = 20000 updates, K doubling on plateaus) and prints one line for it.
+instead (J = 20000 updates, K doubling on plateaus) and prints one line for it.  `--replicas R` times K = 8, 16, 32
+with R independent replicas in one context (they run beside each other; `us_per_update` is then per update of one
+replica, i.e. wall time / (updates x R)).
 """
 import json
 import os
@@ -19,7 +21,7 @@ if ROOT not in sys.path:
 BF16_PEAK_TFLOPS = 2500.0
 
 
-def main(updates=200, ks=(8, 16, 32, 64, 128, 256)):
+def main(updates=200, ks=(8, 16, 32, 64, 128, 256), replicas=1):
     import torch
 
     from paper_2003_10579_amd import ssgd, synth
@@ -29,7 +31,8 @@ def main(updates=200, ks=(8, 16, 32, 64, 128, 256)):
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
     ada = dict(mode=1, K0=ks[0], Kmax=256, window=200, rel_tol=-1e9)   # a window never counts as a plateau
     ctx = ssgd.Context("mlp2", Xd, yd, P, ks[0], m, "k_async", ssgd.delay_dist("shifted_exp", 0.5, 1.0), 0.05, seed=0,
-                       classes=C, hidden=H, bf16=1, adasync=ada)
+                       classes=C, hidden=H, bf16=1, adasync=ada, replicas=replicas)
+    R = replicas
     for K in ks:
         ctx.force_K(K)
         ctx.run(updates // 2)          # the first updates after a change still start the previous K's workers
@@ -40,8 +43,8 @@ def main(updates=200, ks=(8, 16, 32, 64, 128, 256)):
         dt = time.perf_counter() - t0
         tr = ctx.trace(0, ctx.updates - updates, updates)
         assert (tr["K"] == K).all()
-        flop = updates * K * m * 2 * (2 * d * H)          # forward + first-layer gradient contraction
-        print(json.dumps({"K": K, "us_per_update": dt / updates * 1e6, "worker_gradients_per_s": updates * K / dt,
+        flop = R * updates * K * m * 2 * (2 * d * H)      # forward + first-layer gradient contraction
+        print(json.dumps({"K": K, "replicas": R, "us_per_update": dt / updates / R * 1e6, "worker_gradients_per_s": R * updates * K / dt,
                           "contraction_tflops": flop / dt / 1e12, "frac_of_bf16_peak": flop / dt / 1e12 / BF16_PEAK_TFLOPS,
                           "mean_loss": float(tr["loss"].mean())}), flush=True)
     ctx.close()
@@ -81,5 +84,7 @@ def full_run(J=20000):
 if __name__ == "__main__":
     if len(sys.argv) > 1 and sys.argv[1] == "--full":
         full_run(int(sys.argv[2]) if len(sys.argv) > 2 else 20000)
+    elif len(sys.argv) > 2 and sys.argv[1] == "--replicas":
+        main(ks=(8, 16, 32), replicas=int(sys.argv[2]))
     else:
         main()

@@ -534,6 +534,39 @@ def test_mlp_kasync_training_run(ssgd, oracle, torch_cuda):
     ctx.close()
 
 
+def test_mlp_replicas_are_independent_runs(ssgd, oracle, torch_cuda):
+    """Three replicas of the network in one context (they run beside each other on streams of their own): each follows
+    the oracle's run with its replica index, through a change of K by plateau doubling, and a snapshot taken half-way
+    resumes all of them."""
+    torch = torch_cuda
+    X, y = synth.mixture_data(3000, 256, 10, seed=8)
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    ada = dict(mode=1, K0=2, Kmax=8, window=20, rel_tol=0.3)
+    ctx = ssgd.Context("mlp2", Xd, yd, 12, 2, 32, "k_async", gd, 0.05, seed=7, classes=10, hidden=128, bf16=1, adasync=ada,
+                       replicas=3)
+    ctx.run(60)
+    snap = ctx.get_state()
+    ctx.run(60)
+    finals = []
+    M = oracle.Model("mlp2", X, y, classes=10, hidden=128, bf16=1)
+    for r in range(3):
+        tr = oracle.Trainer(M, 12, 2, 32, "k_async", od, 0.05, seed=7, adasync=ada, replica=r)
+        tr.run(120)
+        assert_trace_equal(ctx.trace(r), tr.trace())
+        pr = rel(ctx.params(r), tr.params())
+        assert pr <= MLP_PARAM_TOL, (r, pr)
+        fo = M.full_loss(ctx.params(r))
+        assert abs(ctx.full_loss(r) - fo) <= 2e-3 * max(1.0, abs(fo))
+        finals.append(ctx.params(r).copy())
+    assert not np.array_equal(finals[0], finals[1])
+    ctx.set_state(snap)
+    ctx.run(60)
+    for r in range(3):
+        assert np.array_equal(ctx.params(r), finals[r])
+    ctx.close()
+
+
 def test_mlp_kbatch_async_training_run_with_plateau_doubling(ssgd, oracle, torch_cuda):
     """K-batch-async on the MLP, free-running for 120 updates while AdaSync doubles K (2 -> 8) on plateaus: the slot
     of every mini-batch in flight survives the changes of K."""

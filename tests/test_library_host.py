@@ -55,7 +55,8 @@ def _model(kind=ssgd.SOFTMAX, d=8, classes=3, X=0x1000, y=0x1000, N=10, hidden=0
     dict(model=dict(kind=ssgd.MLP2, d=128, hidden=192, classes=4, bf16=1)),      # hidden % 128
     dict(model=dict(kind=ssgd.MLP2, d=96, hidden=128, classes=4, bf16=1)),       # d % 128
     dict(model=dict(kind=ssgd.MLP2, d=128, hidden=128, classes=4, bf16=1), m=65),
-    dict(model=dict(kind=ssgd.MLP2, d=128, hidden=128, classes=4, bf16=1), replicas=2),
+    dict(model=dict(kind=ssgd.MLP2, d=128, hidden=128, classes=4, bf16=1), replicas=2,
+         ada=dict(mode=2, K0=2, Kmax=4, window=0, interval_t=1.0)),   # the paper's rules run one replica
     dict(model=dict(kind=ssgd.MLP2, d=128, hidden=128, classes=17, bf16=1)),
     dict(ada=dict(mode=2, K0=2, Kmax=4, window=0, interval_t=0.0)),
 ])
