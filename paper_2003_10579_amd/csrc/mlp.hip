@@ -35,7 +35,7 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 constexpr int MP = 64;         // rows kept per worker (m <= 64; the rest is zero)
 constexpr int KT = 64;         // contraction depth per stage
 constexpr int LDT = KT + 8;    // padded LDS row (bf16 elements): 144 bytes, keeps 16-byte reads conflict-poor
-constexpr int kSmallRec = 16;  // most records per update that take the few-record path
+constexpr int kSmallRec = 32;  // most records per update that take the few-record path
 
 // round to nearest even, as a 16-bit pattern; infinities and NaNs are truncated
 __device__ __forceinline__ unsigned short bf16_bits(float x) {
@@ -1050,6 +1050,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_mid_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)mid_lds_bytes(1024)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fwd_gather_kernel<128, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(128)));
     TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fwd_gather_kernel<64, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
+    TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fwd_gather_kernel<64, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)contract_lds(64)));
 #undef TRY
     *out = s;
     return hipSuccess;
@@ -1069,7 +1070,7 @@ Trace trace_of(const Trace& tr, int r) {
 void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
     if (a.variant == kBatchAsync) hipLaunchKernelGGL(mlp_batch_plan_kernel, dim3(1), dim3(64), 0, stream, a);
     const int wgs64 = a.nrec * (a.H / 64);
-    if (a.nrec > 0 && a.nrec <= kSmallRec && wgs64 <= 128 && a.H <= 1024 &&
+    if (a.nrec > 0 && a.nrec <= kSmallRec && wgs64 <= 256 && a.H <= 1024 &&
         (int64_t)a.nrec * MP * a.H * 8 <= (int64_t)kMaxSplit * a.H * a.d) {
         // few records: two launches; the depth is split so that two workgroups share every CU and none walks all of d
         a.fsplit = std::max(2, std::min(8, 512 / wgs64));
@@ -1081,9 +1082,8 @@ void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
         hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
         hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
     } else if (a.nrec > 0) {
-        // in between: rows to bf16 first, then small tiles (the large ones would not fill the chip)
-        hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
-        hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
+        // in between: small tiles (the large ones would not fill the chip), the whole depth per workgroup
+        hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, false>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
         hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
         hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
     }
