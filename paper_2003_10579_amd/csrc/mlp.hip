@@ -1087,13 +1087,13 @@ void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
         hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
         hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
     }
-    if (a.Kv >= 64) {
+    if (a.Kv >= 32) {
         // many slots: 128 x 128 tiles (half the operand traffic of the small ones), the slots split into shares so
         // that the chip is still full; the shares are added, in order, by the update kernel
         // (as many shares as keep all workgroups resident at once, two per CU on 256 CUs: a second, partial round of
         // workgroups costs more than the shorter shares gain)
         const int tiles = (a.H / 128) * (a.d / 128);
-        a.nsplit = std::max(1, std::min({kMaxSplit, a.Kv / 16, 512 / tiles}));
+        a.nsplit = std::max(1, std::min({kMaxSplit, a.Kv / 8, 512 / tiles}));
         hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3(a.H / 128, a.d / 128, a.nsplit), dim3(256), contract_lds(128), stream, a);
         hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
         hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
