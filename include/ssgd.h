@@ -55,7 +55,7 @@ typedef enum {
     SSGD_K_BATCH_ASYNC = 3 /* first K mini-batches, nobody is cancelled: a worker that pushes re-reads the
                               current parameters and starts its next mini-batch at once.  Fixed K or
                               AdaSync mode 1.  Linear models: d % 4 == 0, at most 15 classes,
-                              K <= 32 (any m); MLP2: its usual limits, K <= 256;
+                              K <= 64 (any m); MLP2: its usual limits, K <= 256;
                               else SSGD_EINVAL */
 } ssgd_variant;
 

@@ -459,8 +459,8 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         if (ada.mode >= 2) return fail(nullptr, SSGD_EINVAL, "K-batch-async runs with a fixed K or plateau doubling");
         // the linear models run this variant through the steady-state kernel only
         const int32_t classes = model->kind == SSGD_LSQ ? 1 : model->classes;
-        if (model->kind != SSGD_MLP2 && (model->d % 4 != 0 || classes > 15 || Kcap > 32))
-            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models need d % 4 == 0, at most 15 classes, K <= 32");
+        if (model->kind != SSGD_MLP2 && (model->d % 4 != 0 || classes > 15 || Kcap > 64))
+            return fail(nullptr, SSGD_EINVAL, "K-batch-async: linear models need d % 4 == 0, at most 15 classes, K <= 64");
     }
     if (model->kind == SSGD_LSQ) {
         if (model->bf16) return fail(nullptr, SSGD_EINVAL, "bf16 is for the MLP only");

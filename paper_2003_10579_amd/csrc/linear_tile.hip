@@ -38,7 +38,7 @@ constexpr int ROWS = 64;        // rows of the LDS tile
 constexpr int SL = 256;         // columns per workgroup
 constexpr int NTC = 256;        // compute threads
 constexpr int LLOADS = 16;      // 16-byte loads per loader lane per tile
-constexpr int KC = 32;          // list entries per step
+constexpr int KC = 64;          // list entries per step (one lane of a wave each)
 constexpr int kAgentLoad = 16;  // cache policy: served by the L2, never by a CU's L1
 constexpr int kStream = 2;      // cache policy: non-temporal
 constexpr uint32_t kNoRow = 0xFFFFFFFFu;

@@ -915,6 +915,8 @@ def test_mlp_snapshot_resume(ssgd, oracle, torch_cuda, variant, K):
     ("lsq", 5, 3, 72, 132, 1, ("exp", 1.0)),                      # 72 rows: a full tile and one of 8 rows per record
     ("softmax", 4, 6, 200, 516, 7, ("pareto", 2.5, 1.0)),         # four tiles per record (the last of 8 rows), K > P
     ("softmax", 64, 16, 128, 320, 10, ("pareto", 2.5, 1.0)),      # config 2's P, K and m: 158 tiles at version 0
+    ("softmax", 20, 48, 16, 260, 5, ("exp", 1.0)),                # K = 48 > P: lists longer than 32 entries
+    ("lsq", 70, 64, 8, 132, 1, ("shifted_exp", 0.5, 1.0)),        # K = 64, the most a wave's lanes hold
 ])
 def test_kbatch_async_parity(ssgd, oracle, torch_cuda, kind, P, K, m, d, classes, spec):
     """K-batch-async (Sec. 2.2): delays, selections, ordinals and staleness bit for bit, per-update averaged gradients
@@ -958,8 +960,8 @@ def test_kbatch_async_unsupported_shapes_are_refused(ssgd, torch_cuda):
     torch = torch_cuda
     X, y, _ = synth.lsq_data(64, 66, 1)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
-    for P, K, m, cols in ((4, 2, 8, 66), (8, 33, 8, 64)):
-        # d % 4 != 0; K > 32
+    for P, K, m, cols in ((4, 2, 8, 66), (8, 65, 8, 64)):
+        # d % 4 != 0; K > 64
         Xc = Xd[:, :cols].contiguous()
         with pytest.raises(ssgd.SsgdError):
             ssgd.Context("lsq", Xc, yd, P, K, m, "k_batch_async", ssgd.delay_dist("exp", 1.0), 0.01)

@@ -46,7 +46,7 @@ def _model(kind=ssgd.SOFTMAX, d=8, classes=3, X=0x1000, y=0x1000, N=10, hidden=0
 
 @pytest.mark.parametrize("case", [
     dict(K=0), dict(K=5, P=4), dict(P=0), dict(P=257), dict(m=0), dict(replicas=0), dict(variant=7),
-    dict(variant=ssgd.K_BATCH_ASYNC, K=33, P=40), dict(dist=("exp", 0.0)), dict(dist=("pareto", -1.0, 1.0)),
+    dict(variant=ssgd.K_BATCH_ASYNC, K=65, P=70), dict(dist=("exp", 0.0)), dict(dist=("pareto", -1.0, 1.0)),
     dict(dist=("shifted_exp", 0.5, -2.0)), dict(model=dict(X=None)), dict(model=dict(N=0)),
     dict(model=dict(classes=17)), dict(model=dict(kind=ssgd.LSQ, bf16=1)), dict(model=dict(kind=9)),
     dict(model=dict(kind=ssgd.MLP2, hidden=100)), dict(ada=dict(mode=1, K0=2, Kmax=1, window=10)),
