@@ -163,8 +163,10 @@ ssgd_status ssgd_full_loss(ssgd_ctx *ctx, int32_t replica, double *loss_out);
  * parameters: the quantity in which the staleness bound (fifth assumption of Sec. 4.1) is stated
  * (E||grad F(w_j) - grad F(w_tau)||^2 <= gamma E||grad F(w_j)||^2).  grad_out: HOST, |w| floats in the
  * layout of the parameters.  Two passes over X in fp32 with fp64 sums over chunks of samples, through
- * temporary device buffers (SSGD_ENOMEM if they do not fit).  Linear models with d % 4 == 0, else
- * SSGD_EINVAL. */
+ * temporary device buffers (SSGD_ENOMEM if they do not fit).  Linear models need d % 4 == 0, else
+ * SSGD_EINVAL.  The two-layer network: with the arithmetic of its training gradients (bf16 operands in
+ * the two large contractions, fp32 accumulation), the data set in blocks of up to 256 x 64 rows that are
+ * added on the host in fp64; parameters, trace and mini-batches in flight are untouched. */
 ssgd_status ssgd_full_gradient(ssgd_ctx *ctx, int32_t replica, float *grad_out);
 
 /* ssgd_full_gradient for callers that cannot allocate device memory (code under HIP graph capture,

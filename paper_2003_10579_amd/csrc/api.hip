@@ -698,8 +698,17 @@ ssgd_status ssgd_full_gradient(ssgd_ctx* c, int32_t replica, float* grad_out) {
     if (replica < 0 || replica >= c->R) return fail(c, SSGD_EINVAL, "replica out of range");
     if (c->broken) return fail(c, SSGD_ESTATE, "context is unusable after a device error");
     const int C = c->model.kind == SSGD_LSQ ? 1 : c->model.classes;
-    if (c->model.kind == SSGD_MLP2 || !full_grad_supports(c->model.kind, c->model.d, C))
-        return fail(c, SSGD_EINVAL, "the full gradient is built for the linear models with d % 4 == 0");
+    if (c->model.kind == SSGD_MLP2) {
+        HIP_OK(c, hipSetDevice(c->device));
+        HIP_OK(c, hipStreamSynchronize(c->stream));
+        std::string msg;
+        hipError_t em = mlp_full_gradient(c->mlp[(size_t)replica], grad_out, c->stream, &msg);
+        if (em == hipErrorOutOfMemory) return fail(c, SSGD_ENOMEM, "full gradient: " + msg);
+        if (em != hipSuccess) return fail(c, SSGD_EDEVICE, "full gradient: " + msg);
+        return SSGD_OK;
+    }
+    if (!full_grad_supports(c->model.kind, c->model.d, C))
+        return fail(c, SSGD_EINVAL, "the full gradient of the linear models needs d % 4 == 0");
     HIP_OK(c, hipSetDevice(c->device));
     DevBuf scratch, out;
     hipError_t e = scratch.alloc(sizeof(float) * (size_t)full_grad_scratch_floats(c->model.N, c->model.d, C, nullptr));

@@ -121,6 +121,7 @@ __device__ __forceinline__ void record_of(const MlpArgs& a, int r, int& worker, 
     }
 }
 __device__ __forceinline__ int consumed_slot(const MlpArgs& a, int l) {
+    if (a.eval_base >= 0) return l;       // evaluation over the data set: every record of the block
     if (a.variant == kBatchAsync) return PlanView(a.plan, a.P, a.S, a.Kcap).cons_slot[l];
     return a.variant == kAsync ? a.tr.sel[a.v * a.tr.Kcap + l] : l;
 }
@@ -1243,6 +1244,78 @@ hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::stri
     return hipSuccess;
 }
 
+
+// Gradient of the objective over the whole data set, with the arithmetic of the trainer's gradients (bf16 operands in
+// the two large contractions, fp32 accumulation): the data set goes through the training kernels in blocks of up to
+// 256 slots of 64 rows, each block as one "update" that consumes all its slots with a step size of zero, so that the
+// parameters keep their values and the block's averaged gradient lands in a device buffer; the blocks are added on the
+// host in fp64; rows left over after the last whole slot form a mini-batch of their own size.  Buffers of its own, so
+// that the mini-batches in flight stay untouched.
+hipError_t mlp_full_gradient(MlpState* s, float* grad_out_host, hipStream_t stream, std::string* msg) {
+    auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
+    MlpArgs a = s->a;
+    const int64_t N = (int64_t)a.N, nslot = (N + MP - 1) / MP;
+    const size_t E = (size_t)std::min<int64_t>(nslot, 256);
+    DevMem xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, quart, agg, tloss;
+    DevMem* all[] = {&xb, &xbt, &hbuf, &d1t, &gb1, &gw2, &gb2, &d2, &loss, &ylab, &quart, &agg, &tloss};
+    auto release = [&]() { for (DevMem* b : all) b->release(); };
+    const size_t sizes[] = {2 * E * MP * a.d, 2 * E * MP * a.d, sizeof(float) * E * MP * a.H, 2 * E * MP * a.H,
+                            sizeof(float) * E * 4 * a.H, sizeof(float) * E * 4 * a.C * a.H, sizeof(float) * E * 4 * 16,
+                            sizeof(float) * E * MP * 16, sizeof(float) * E * 4, sizeof(int32_t) * E * MP, sizeof(int32_t) * E,
+                            sizeof(float) * (size_t)s->nw, sizeof(float) * 16};
+    hipError_t e = hipSuccess;
+    for (size_t q = 0; q < sizeof(all) / sizeof(all[0]) && e == hipSuccess; ++q) e = all[q]->alloc(sizes[q]);
+    if (e != hipSuccess) { release(); return fail(e, "allocating the evaluation buffers"); }
+    a.xb = (unsigned short*)xb.p; a.xbt = (unsigned short*)xbt.p; a.hbuf = (float*)hbuf.p; a.d1t = (unsigned short*)d1t.p;
+    a.gb1 = (float*)gb1.p; a.gw2 = (float*)gw2.p; a.gb2 = (float*)gb2.p; a.d2 = (float*)d2.p; a.loss = (float*)loss.p;
+    a.ylab = (int32_t*)ylab.p; a.quartered = (int32_t*)quart.p; a.agg_out = (float*)agg.p;
+    a.tr.loss = (float*)tloss.p;       // the loss record of the pretended update goes nowhere
+    a.m = MP; a.v = 0; a.lr = 0.0f; a.variant = kSync; a.S = (int32_t)E;
+    const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
+    hipLaunchKernelGGL(mlp_refresh_kernel, dim3(1024), dim3(256), 0, stream, a.params, a.w1r, a.w2r, n1, off2, n2);
+    std::vector<float> h((size_t)s->nw);
+    std::vector<double> total((size_t)s->nw, 0.0);
+    // whole slots in blocks; the rows that are left over (fewer than 64) as a mini-batch of their own size, so that
+    // delta1 is scaled and rounded as in a mini-batch of that size
+    const int64_t nfull = N / MP;
+    struct Block { int64_t slot0; int nrec, m; };
+    std::vector<Block> blocks;
+    for (int64_t s0 = 0; s0 < nfull; s0 += (int64_t)E) blocks.push_back({s0, (int)std::min<int64_t>((int64_t)E, nfull - s0), MP});
+    if (nfull * MP < N) blocks.push_back({nfull, 1, (int)(N - nfull * MP)});
+    for (const Block& blk : blocks) {
+        if (e != hipSuccess) break;
+        a.eval_base = blk.slot0 * MP;
+        a.nrec = blk.nrec;
+        a.m = blk.m;
+        a.Kv = a.nrec;
+        hipLaunchKernelGGL(mlp_gather_kernel, dim3(a.nrec, a.d / 128), dim3(256), 0, stream, a);
+        if (((a.nrec + 1) / 2) * (a.H / 128) >= 192)
+            hipLaunchKernelGGL((mlp_contract_kernel<true, 128>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
+        else
+            hipLaunchKernelGGL((mlp_contract_kernel<true, 64>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
+        hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
+        if (a.Kv >= 32) {
+            const int tiles = (a.H / 128) * (a.d / 128);
+            a.nsplit = std::max(1, std::min({kMaxSplit, a.Kv / 8, 512 / tiles}));
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3(a.H / 128, a.d / 128, a.nsplit), dim3(256), contract_lds(128), stream, a);
+            hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
+        } else {
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64 + 1), dim3(256), contract_lds(64), stream, a);
+        }
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipMemcpyAsync(h.data(), a.agg_out, sizeof(float) * (size_t)s->nw, hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        // the block's gradient is the mean over its Kv slots of the slots' means over their rows
+        const double wgt = (double)a.Kv * (double)a.m;
+        if (e == hipSuccess) for (size_t q = 0; q < h.size(); ++q) total[q] += (double)h[q] * wgt;
+    }
+    release();
+    if (e != hipSuccess) return fail(e, "evaluating the gradient of the objective");
+    for (size_t q = 0; q < h.size(); ++q) grad_out_host[q] = (float)(total[q] / (double)N);
+    return hipSuccess;
+}
 
 // Everything a later update depends on: parameters (fp32 master and operand copies) and the factors of the
 // mini-batches in flight, slot by slot.

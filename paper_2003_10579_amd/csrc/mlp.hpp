@@ -18,6 +18,8 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
 float* mlp_params(MlpState* s);
 // Objective over the whole data set at the current parameters, with the trainer's forward pass.
 hipError_t mlp_full_loss(MlpState* s, double* out, hipStream_t stream, std::string* msg);
+// Its gradient, |w| floats on the host, with the arithmetic of the trainer's gradients.
+hipError_t mlp_full_gradient(MlpState* s, float* grad_out_host, hipStream_t stream, std::string* msg);
 // Snapshot of everything later updates depend on (host memory; the stream must be idle).
 int64_t mlp_state_bytes(MlpState* s);
 hipError_t mlp_get_state(MlpState* s, unsigned char* host);

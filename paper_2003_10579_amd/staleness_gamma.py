@@ -19,9 +19,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def gamma_estimate(ssgd, Xd, yd, P, K, m, variant, dist_spec, lr, J, replicas, seed=0, keep_params=False):
-    """Runs J updates one at a time; returns the estimate and, on request, every replica's iterates w_0 .. w_J."""
-    ctx = ssgd.Context("lsq", Xd, yd, P, K, m, variant, ssgd.delay_dist(*dist_spec), lr, seed=seed, replicas=replicas)
+def gamma_estimate(ssgd, Xd, yd, P, K, m, variant, dist_spec, lr, J, replicas, seed=0, keep_params=False, kind="lsq",
+                   **model):
+    """Runs J updates one at a time; returns the estimate and, on request, every replica's iterates w_0 .. w_J.
+    `kind` and `model` (classes=, hidden=, bf16=) choose the model: least squares, softmax regression or the network."""
+    ctx = ssgd.Context(kind, Xd, yd, P, K, m, variant, ssgd.delay_dist(*dist_spec), lr, seed=seed, replicas=replicas, **model)
     grads = [[ctx.full_gradient(r).astype(np.float64)] for r in range(replicas)]       # grads[r][j] = grad F(w_j)
     params = [[ctx.params(r)] for r in range(replicas)] if keep_params else None
     for _ in range(J):

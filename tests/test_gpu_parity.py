@@ -1047,6 +1047,44 @@ def test_full_gradient_against_the_oracle(ssgd, oracle, torch_cuda, kind, N, d, 
     ctx.close()
 
 
+def test_staleness_gamma_estimate_for_the_network(ssgd, torch_cuda):
+    """The same estimate on the two-layer network with two replicas: zero for K-sync, positive for K-async."""
+    from paper_2003_10579_amd import staleness_gamma
+    torch = torch_cuda
+    X, y = synth.mixture_data(1500, 256, 5, seed=9)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    kw = dict(kind="mlp2", classes=5, hidden=128, bf16=1)
+    sync = staleness_gamma.gamma_estimate(ssgd, Xd, yd, 8, 4, 16, "k_sync", ("exp", 1.0), 0.05, 12, 2, seed=3, **kw)
+    assert sync["gamma"] == 0.0 and sync["p0"] == 1.0
+    asy = staleness_gamma.gamma_estimate(ssgd, Xd, yd, 8, 2, 16, "k_async", ("exp", 1.0), 0.05, 25, 2, seed=3, **kw)
+    assert asy["gamma"] > 0.0 and 0.0 < asy["p0"] < 1.0
+
+
+@pytest.mark.parametrize("N,d,hidden,classes", [(1000, 256, 128, 10), (20000, 384, 256, 7)])
+def test_full_gradient_of_the_network_against_the_oracle(ssgd, oracle, torch_cuda, N, d, hidden, classes):
+    """grad F of Eq. (1) for the two-layer network, at the initial parameters and after some training (a ragged last
+    block of rows; the second shape takes more than one block of 256 slots), against the oracle's gradient; the
+    parameters, the trace and the mini-batches in flight are untouched by the call."""
+    torch = torch_cuda
+    X, y = synth.mixture_data(N, d, classes, seed=46)
+    gd, od = dist_pair(ssgd, oracle, ("shifted_exp", 0.5, 1.0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    ctx = ssgd.Context("mlp2", Xd, yd, 8, 2, 32, "k_async", gd, 0.05, seed=47, classes=classes, hidden=hidden, bf16=1)
+    M = oracle.Model("mlp2", X, y, classes=classes, hidden=hidden, bf16=1)
+    tr = oracle.Trainer(M, 8, 2, 32, "k_async", od, 0.05, seed=47)
+    e0 = rel(ctx.full_gradient(0), M.full_grad(ctx.params(0)))
+    ctx.run(20); tr.run(20)
+    w = ctx.params(0).copy()
+    e1 = rel(ctx.full_gradient(0), M.full_grad(w))
+    print(f"network full gradient: {e0:.3e} at w_0, {e1:.3e} after 20 updates")
+    assert e0 <= MLP_GRAD_TOL and e1 <= MLP_GRAD_TOL, (e0, e1)
+    assert np.array_equal(ctx.params(0), w)
+    ctx.run(20); tr.run(20)                       # the run goes on as if the call had not happened
+    assert_trace_equal(ctx.trace(), tr.trace())
+    assert rel(ctx.params(0), tr.params()) <= MLP_PARAM_TOL
+    ctx.close()
+
+
 def test_staleness_gamma_estimate(ssgd, oracle, torch_cuda):
     """gamma of the staleness bound (fifth assumption of Sec. 4.1) from the driver: zero for a synchronous variant (every gradient is fresh), positive and
     growing with the staleness for K-async (K = 1 against K = P / 2 at P = 8), and equal to the same ratio formed
