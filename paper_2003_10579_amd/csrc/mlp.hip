@@ -227,8 +227,20 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     unsigned short* As = lds;                       // [2][BT][LDT]
     unsigned short* Bs = lds + 2 * BT * LDT;        // [2][BT][LDT]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int bm = blockIdx.x, bn = blockIdx.y;
     const int d = a.d, H = a.H;
+    int bm = blockIdx.x, bn = blockIdx.y, bz = blockIdx.z;
+    if constexpr (!FWD && SPLIT) {
+        // One-dimensional launch.  Consecutive block ids go to different XCDs; the H / BT workgroups that read the same
+        // columns of the same slots (the large operand) take consecutive places on one XCD, so that they run together
+        // and those columns come from HBM once.
+        const int nbm = H / BT, nbn = d / BT;
+        const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+        const int group = (idx / nbm) * 8 + xcd;          // (column tile, share)
+        bm = idx % nbm;
+        if (group >= nbn * a.nsplit) return;
+        bn = group % nbn;
+        bz = group / nbn;
+    }
     if constexpr (!FWD && !SPLIT) {
         // a launch with one more row of workgroups than there are column tiles: that row takes the small parameters of
         // the update (they do not depend on the contraction), which saves a launch per update
@@ -246,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
         static_assert(!FWD, "only the gradient contraction is split here");
         const int total = a.Kv, shares = a.nsplit;
         const int per = (total + shares - 1) / shares;
-        stage0 = blockIdx.z * per;
+        stage0 = bz * per;
         stages = max(0, min(per, total - stage0));
     }
 
@@ -373,7 +385,7 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
             }
         } else if constexpr (SPLIT) {
             const int64_t p = (int64_t)(bm * BT + row) * d + bn * BT + 4 * c4;
-            *reinterpret_cast<f32x4*>(a.dw_part + (int64_t)blockIdx.z * H * d + p) = v;
+            *reinterpret_cast<f32x4*>(a.dw_part + (int64_t)bz * H * d + p) = v;
         } else {
             const int64_t p = (int64_t)(bm * BT + row) * d + bn * BT + 4 * c4;
             f32x4 w = *reinterpret_cast<const f32x4*>(a.params + p);
@@ -1095,7 +1107,7 @@ void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
         // workgroups costs more than the shorter shares gain)
         const int tiles = (a.H / 128) * (a.d / 128);
         a.nsplit = std::max(1, std::min({kMaxSplit, a.Kv / 8, 512 / tiles}));
-        hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3(a.H / 128, a.d / 128, a.nsplit), dim3(256), contract_lds(128), stream, a);
+        hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3((a.H / 128) * 8 * (((a.d / 128) * a.nsplit + 7) / 8)), dim3(256), contract_lds(128), stream, a);
         hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
         hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
     } else {
@@ -1298,7 +1310,7 @@ hipError_t mlp_full_gradient(MlpState* s, float* grad_out_host, hipStream_t stre
         if (a.Kv >= 32) {
             const int tiles = (a.H / 128) * (a.d / 128);
             a.nsplit = std::max(1, std::min({kMaxSplit, a.Kv / 8, 512 / tiles}));
-            hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3(a.H / 128, a.d / 128, a.nsplit), dim3(256), contract_lds(128), stream, a);
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3((a.H / 128) * 8 * (((a.d / 128) * a.nsplit + 7) / 8)), dim3(256), contract_lds(128), stream, a);
             hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
             hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
         } else {
