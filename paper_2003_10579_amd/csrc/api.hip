@@ -538,15 +538,15 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         c->lds_bytes = linear_lds_bytes(c->nbw, C, c->S, async);
         if (variant == SSGD_K_BATCH_ASYNC) {
             // the general kernel is never used for this variant; what has to fit is the steady-state kernel's LDS
-            if (linear_tile_lds_bytes(C, c->S) > 160 * 1024) return bail(SSGD_EINVAL, "too many gradient slots for the LDS of one workgroup");
+            if (linear_tile_lds_bytes(C, c->S, Kcap) > 160 * 1024) return bail(SSGD_EINVAL, "too many gradient slots for the LDS of one workgroup");
             c->lds_bytes = std::min<size_t>(c->lds_bytes, 160 * 1024);
         }
         if (c->lds_bytes > 160 * 1024) return bail(SSGD_EINVAL, "too many gradient slots for the LDS of one workgroup");
         c->resident_groups = linear_max_resident_groups(c->nbw, c->lds_bytes);
         if (c->resident_groups < c->G) return bail(SSGD_EINVAL, "d is too large for a co-resident cluster of workgroups");
         { hipDeviceProp_t prop; HIP_C(hipGetDeviceProperties(&prop, c->device)); c->cu_count = prop.multiProcessorCount; }
-        if (c->nbw == 4 && C <= 15 && linear_tile_lds_bytes(C, c->S) <= 160 * 1024)
-            c->tile_resident_groups = linear_tile_resident_groups(linear_tile_lds_bytes(C, c->S));
+        if (c->nbw == 4 && C <= 15 && linear_tile_lds_bytes(C, c->S, Kcap) <= 160 * 1024)
+            c->tile_resident_groups = linear_tile_resident_groups(linear_tile_lds_bytes(C, c->S, Kcap));
         if (c->nbw == 4 && C <= 15 && variant == SSGD_K_ASYNC && c->S <= 8 && linear_defer_lds_bytes(C, c->S) <= 160 * 1024)
             c->defer_per_launch = linear_defer_replicas_per_launch(c->G, c->cu_count);
         HIP_C(c->params.alloc(sizeof(float) * R * c->nw));

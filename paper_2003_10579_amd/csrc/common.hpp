@@ -119,7 +119,7 @@ hipError_t launch_linear(const LinArgs& a, int nbw, hipStream_t s);
 // Single-tile steady-state kernel (256 columns per workgroup, same state layout as launch_linear with nbw = 4).
 // max_records: the most mini-batches any step of the segment computes.
 bool linear_tile_supports(const LinArgs& a, int max_records);
-size_t linear_tile_lds_bytes(int C, int S);
+size_t linear_tile_lds_bytes(int C, int S, int Kcap);
 int linear_tile_resident_groups(size_t lds_bytes);
 hipError_t launch_linear_tile(const LinArgs& a, hipStream_t s);
 // Steady-state kernel of K-async with at most 8 workers (linear_defer.hip): one workgroup per CU, the gradients in

@@ -62,7 +62,8 @@ struct Lds {
     int* s_rec;       // [KC] compute list of v: slot of record r; bit 16: consumed by update v itself
 };
 
-__device__ __forceinline__ Lds carve(unsigned char* smem, int C, int S) {
+// (kc: places of the two lists, 32 or 64: the second workgroup of a CU fits only while the lists are short)
+__device__ __forceinline__ Lds carve(unsigned char* smem, int C, int S, int kc) {
     Lds l;
     l.tile = reinterpret_cast<float*>(smem);
     l.wlds = l.tile + ROWS * SL;
@@ -72,8 +73,8 @@ __device__ __forceinline__ Lds carve(unsigned char* smem, int C, int S) {
     l.bias = l.ylab + ROWS;
     l.ctl = reinterpret_cast<int*>(l.bias + 16);      // 16-byte aligned: words 4..7 are read as one vector
     l.s_stale = l.ctl + 8;
-    l.s_rec = l.s_stale + KC;
-    l.small = reinterpret_cast<float*>(l.s_rec + KC);
+    l.s_rec = l.s_stale + kc;
+    l.small = reinterpret_cast<float*>(l.s_rec + kc);
     return l;
 }
 
@@ -133,7 +134,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
     const int mpt = (chunked || spr > 1) ? ROWS : mp;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const Lds L = carve(smem, C, S);
+    const int kc = Kcap > 32 ? KC : 32;      // places of the lists in LDS
+    const Lds L = carve(smem, C, S, kc);
 
     if (wave >= 4) {
         // =============================== loader waves ===============================
@@ -319,8 +321,8 @@ __global__ __launch_bounds__(512, 4) void linear_tile_kernel(LinArgs a) {
             if (lw == 0) {
                 L.rowid[lane] = row_id; L.ylab[lane] = row_lab;
                 if (lane == 0) { L.ctl[4] = n_K; L.ctl[5] = n_nrec; L.ctl[6] = n_nstale; L.ctl[7] = flags; }
-                if (n_stale_pos < KC) L.s_stale[n_stale_pos] = n_stale;
-                if (lane < KC) L.s_rec[lane] = n_rec_word;
+                if (n_stale_pos < kc) L.s_stale[n_stale_pos] = n_stale;
+                if (lane < kc) L.s_rec[lane] = n_rec_word;
             }
         };
 
@@ -993,8 +995,8 @@ hipError_t launch_k(const LinArgs& a, size_t lds, hipStream_t s) {
 
 }  // namespace
 
-size_t linear_tile_lds_bytes(int C, int S) {
-    const size_t words = (size_t)ROWS * SL + (size_t)C * SL + ROWS * 16 + 2 * ROWS + 16 + 8 + 2 * KC + (size_t)S * 17;
+size_t linear_tile_lds_bytes(int C, int S, int Kcap) {
+    const size_t words = (size_t)ROWS * SL + (size_t)C * SL + ROWS * 16 + 2 * ROWS + 16 + 8 + 2 * (Kcap > 32 ? 64 : 32) + (size_t)S * 17;
     return sizeof(float) * words;
 }
 
@@ -1005,10 +1007,10 @@ bool linear_tile_supports(const LinArgs& a, int max_records) {
     if ((uint64_t)a.N * (uint64_t)a.d * 4u >= (1ull << 32)) return false;   // one buffer descriptor spans the sample matrix
     if (a.variant == kBatchAsync) {
         // whole records per tile, or tiles of one record; the consume list and the restarts of an update sit in one lane each
-        return linear_tile_lds_bytes(a.C, a.S) <= 160 * 1024;
+        return linear_tile_lds_bytes(a.C, a.S, a.tr.Kcap) <= 160 * 1024;
     }
     if (a.variant == kAsync && a.v0 < 1) return false;    // step 0 of K-async starts all P workers
-    return linear_tile_lds_bytes(a.C, a.S) <= 160 * 1024;
+    return linear_tile_lds_bytes(a.C, a.S, a.tr.Kcap) <= 160 * 1024;
 }
 
 int linear_tile_resident_groups(size_t lds_bytes) {
@@ -1022,7 +1024,7 @@ int linear_tile_resident_groups(size_t lds_bytes) {
 }
 
 hipError_t launch_linear_tile(const LinArgs& a, hipStream_t s) {
-    const size_t lds = linear_tile_lds_bytes(a.C, a.S);
+    const size_t lds = linear_tile_lds_bytes(a.C, a.S, a.tr.Kcap);
     const bool prof = a.prof != nullptr;
     if (a.kind == kLsq) return prof ? launch_k<kLsq, true>(a, lds, s) : launch_k<kLsq, false>(a, lds, s);
     return prof ? launch_k<kSoftmax, true>(a, lds, s) : launch_k<kSoftmax, false>(a, lds, s);
