@@ -18,6 +18,9 @@
 //   consume   W1 -= lr/K * sum_l delta1_l^T X_l (MFMA), then b1, W2, b2 and the loss record
 #include "mlp.hpp"
 
+#include <algorithm>
+#include <atomic>
+#include <thread>
 #include <cmath>
 #include <cstring>
 #include <type_traits>
@@ -59,6 +62,8 @@ struct MlpArgs {
     float* params;             // W1[H][d], b1[H], W2[C][H], b2[C]
     unsigned short* w1r;       // bf16 copy of W1
     float* w2r;                // W2 rounded to bf16, kept as fp32
+    float* b1r;                // nullable: a copy of b1 (read by the layer-2 kernel, written by the small update) ...
+    float* b2r;                // ... and of b2, when updates overlap and every version of the parameters has copies of its own
     unsigned short* xb;        // [S][MP][d]   bf16 rows of the slot's mini-batch
     unsigned short* xbt;       // [S][d][MP]   the same, transposed
     float* hbuf;               // [S][MP][H]   hidden activations
@@ -591,7 +596,7 @@ __global__ __launch_bounds__(256) void mlp_mid_kernel(MlpArgs a) {
         const int h4 = H / 4;                  // 16-byte groups per row; 16 rows = 16 h4 groups, 16 h4 / 256 per thread
         const float* src = a.dw_part + ((int64_t)r * MP + 16 * q) * H;
         const int64_t zs = (int64_t)a.nrec * MP * H;
-        const float* b1 = a.params + (int64_t)H * a.d;
+        const float* b1 = a.b1r ? a.b1r : a.params + (int64_t)H * a.d;
         for (int p0 = tid; p0 < 16 * h4; p0 += 4 * 256) {
             f32x4 v[4][8];
 #pragma unroll
@@ -620,7 +625,7 @@ __global__ __launch_bounds__(256) void mlp_mid_kernel(MlpArgs a) {
         }
     }
     const int cls = lane & 15, kq = lane >> 4;
-    const float b2 = a.params[(int64_t)H * a.d + H + (int64_t)C * H + min(cls, C - 1)];
+    const float b2 = a.b2r ? a.b2r[min(cls, C - 1)] : a.params[(int64_t)H * a.d + H + (int64_t)C * H + min(cls, C - 1)];
     __syncthreads();
     // ---- layer 2: wave w sums over its quarter of the hidden units
     {
@@ -926,13 +931,18 @@ __device__ __forceinline__ void small_update_body(const MlpArgs& a, int block, i
         for (int o = 1; o < G; o <<= 1) sum += __shfl_xor(sum, o, 64);
         if (live && g == 0) {
             const float gr = sum * invKm;
-            if (q < H) { b1[q] -= a.lr * gr; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr; }
+            if (q < H) { const float nb = b1[q] - a.lr * gr; b1[q] = nb; if (a.b1r) a.b1r[q] = nb; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr; }
             else if (q < H + C * H) {
                 const float w = W2[q - H] - a.lr * gr;
                 W2[q - H] = w;
                 a.w2r[q - H] = bf16_round(w);
                 if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr;
-            } else if (q < H + C * H + C) { b2[q - H - C * H] -= a.lr * gr; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr; }
+            } else if (q < H + C * H + C) {
+                const float nb = b2[q - H - C * H] - a.lr * gr;
+                b2[q - H - C * H] = nb;
+                if (a.b2r) a.b2r[q - H - C * H] = nb;
+                if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr;
+            }
             else a.tr.loss[a.v] = gr;
         }
     }
@@ -967,6 +977,7 @@ __global__ void mlp_init_kernel(float* params, uint64_t seed, int64_t nw, int64_
 
 // operand double buffer; the epilogue's fp32 tile [BT][BT + 4] fits inside it
 size_t contract_lds(int bt) { return (size_t)4 * bt * LDT * 2; }
+constexpr int kVer = 8;          // versions of the operand copies of the parameters when updates overlap
 constexpr int kMaxSplit = 8;     // shares of the consumed slots in the split gradient contraction
 size_t mid_lds_bytes(int H) { return sizeof(float) * (16 * (size_t)(H + 4) + 4 * 256 + 256 + 4); }
 
@@ -986,6 +997,11 @@ struct MlpState {
     int prevK = 0;          // size of the consume list of the last update run (records of the next K-async step)
     int replica = 0;
     hipStream_t own = nullptr;   // replicas beyond the first run on streams of their own, beside each other
+    // overlapped updates (few records, one replica): kVer versions of the operand copies of the parameters, three
+    // streams for the forward halves of consecutive updates, a pool of events
+    DevMem w1v, w2v, b1v, b2v, fwd_part;   // allocated by the first segment that overlaps
+    hipStream_t fwd_stream[3] = {nullptr, nullptr, nullptr};
+    std::vector<hipEvent_t> ev_pool;
     DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, dw_part, plan, quartered;
     hipStream_t stream = nullptr;
 };
@@ -1052,6 +1068,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     a.d1t = (unsigned short*)s->d1t.p; a.gb1 = (float*)s->gb1.p; a.gw2 = (float*)s->gw2.p; a.gb2 = (float*)s->gb2.p;
     a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p; a.d2 = (float*)s->d2.p; a.quartered = (int32_t*)s->quartered.p;
     a.dw_part = (float*)s->dw_part.p; a.nsplit = 1; a.fsplit = 1; a.eval_base = -1;
+    a.b1r = nullptr; a.b2r = nullptr;
 
     const float bound1 = (float)(1.0 / sqrt((double)a.d)), bound2 = (float)(1.0 / sqrt((double)a.H));
     hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
@@ -1079,14 +1096,19 @@ Trace trace_of(const Trace& tr, int r) {
     return t;
 }
 
+// few records start at this version: the forward pass splits the depth d over workgroups
+bool few_records(const MlpArgs& a, int nrec, int regions) {
+    return nrec > 0 && nrec <= kSmallRec && nrec * (a.H / 64) <= 256 && a.H <= 1024 &&
+           (int64_t)regions * nrec * MP * a.H * 8 <= (int64_t)kMaxSplit * a.H * a.d;
+}
+int few_records_split(const MlpArgs& a, int nrec) { return std::max(2, std::min(8, 512 / (nrec * (a.H / 64)))); }
+
 // the launches of one update (a.v, a.Kv, a.nrec set) on `stream`
 void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
     if (a.variant == kBatchAsync) hipLaunchKernelGGL(mlp_batch_plan_kernel, dim3(1), dim3(64), 0, stream, a);
-    const int wgs64 = a.nrec * (a.H / 64);
-    if (a.nrec > 0 && a.nrec <= kSmallRec && wgs64 <= 256 && a.H <= 1024 &&
-        (int64_t)a.nrec * MP * a.H * 8 <= (int64_t)kMaxSplit * a.H * a.d) {
+    if (few_records(a, a.nrec, 1)) {
         // few records: two launches; the depth is split so that two workgroups share every CU and none walks all of d
-        a.fsplit = std::max(2, std::min(8, 512 / wgs64));
+        a.fsplit = few_records_split(a, a.nrec);
         hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, true>), dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), contract_lds(64), stream, a);
         hipLaunchKernelGGL(mlp_mid_kernel, dim3(a.nrec * 4), dim3(256), mid_lds_bytes(a.H), stream, a);
     } else if (a.nrec > 0 && ((a.nrec + 1) / 2) * (a.H / 128) >= 192) {
@@ -1145,6 +1167,12 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             e = hipMemcpyAsync(&prevK[(size_t)r], a.tr.K + (v0 - 1), sizeof(int32_t), hipMemcpyDeviceToHost, stream);
         if (r > 0 && s->own == nullptr && e == hipSuccess) e = hipStreamCreateWithFlags(&s->own, hipStreamNonBlocking);
     }
+    // the versions of the consumed gradients, where updates may overlap (below)
+    std::vector<int32_t> tau_host;
+    if (R == 1 && args[0].variant == kAsync && agg_out == nullptr && e == hipSuccess) {
+        tau_host.resize((size_t)(n * tr.Kcap));
+        e = hipMemcpyAsync(tau_host.data(), args[0].tr.tau + v0 * tr.Kcap, sizeof(int32_t) * tau_host.size(), hipMemcpyDeviceToHost, stream);
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail(e, "reading K of the segment");
     hipEvent_t e0 = nullptr, e1 = nullptr, fork = nullptr;
@@ -1168,9 +1196,155 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             }
         }
     }
+    auto nrec_of = [&](int r, int64_t q) {
+        const MlpArgs& a = args[(size_t)r];
+        const std::vector<int32_t>& K = Ks[(size_t)r];
+        if (a.variant == kBatchAsync) return (v0 + q == 0 ? a.P : 1) + K[(size_t)q] - 1;
+        if (a.variant == kAsync) return v0 + q == 0 ? a.P : (q == 0 ? prevK[(size_t)r] : K[(size_t)q - 1]);
+        return K[(size_t)q];
+    };
+    // One K-async run whose updates all start few gradients and consume few: the two halves of an update overlap with
+    // those of its neighbours.  The gradients that update v consumes were computed at versions tau <= v (Sec. 2.2), as
+    // a rule many updates ago, so the contraction and update of v (which give w_{v+1}) need the contraction of v - 1 and
+    // the forward halves of the versions in its list, not the forward half of v itself; that one needs w_v only.  The
+    // contractions follow each other on `stream`; the forward halves of consecutive versions go to three streams in
+    // turn, each fed by a host thread of its own (the host's calls, not the device, would otherwise set the pace).
+    // The operand copies of the parameters (bf16 W1, rounded W2, the biases) and the partial sums of the split forward
+    // pass exist kVer times, indexed by version modulo kVer: the update of v writes the copies of v + 1 after the
+    // forward half of v + 1 - kVer, their last reader, has ended.
+    // (the updates of the segment from q0 on, when all of those qualify; the ones before them, the first update of a run
+    // among them, are launched one after the other as below)
+    int64_t q0 = n;
+    if (tau_host.size() == (size_t)(n * tr.Kcap))
+        while (q0 > 0 && Ks[0][(size_t)q0 - 1] < 32 && few_records(args[0], nrec_of(0, q0 - 1), 1)) --q0;
+    if (n - q0 < 4) q0 = n;
+    if (q0 < n) {
+        // the updates before q0
+        for (int64_t q = 0; q < q0; ++q) {
+            MlpArgs& a = args[0];
+            a.v = v0 + q; a.Kv = Ks[0][(size_t)q]; a.nrec = nrec_of(0, q);
+            launch_update(states[0], a, stream);
+        }
+        MlpState* s = states[0];
+        const MlpArgs& base = args[0];
+        const int64_t n1 = (int64_t)base.H * base.d, off2 = n1 + base.H, n2 = (int64_t)base.C * base.H;
+        int nrec_max = 1;
+        for (int64_t q = q0; q < n; ++q) nrec_max = std::max(nrec_max, nrec_of(0, q));
+        const int64_t region = (int64_t)8 * nrec_max * MP * base.H;
+        hipError_t oe = hipSuccess;
+        for (hipStream_t& f : s->fwd_stream)
+            if (f == nullptr && oe == hipSuccess) oe = hipStreamCreateWithFlags(&f, hipStreamNonBlocking);
+        constexpr int kRing = 32;
+        while (s->ev_pool.size() < 2 * kRing + 1 && oe == hipSuccess) {
+            hipEvent_t ev = nullptr;
+            oe = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+            if (oe == hipSuccess) s->ev_pool.push_back(ev);
+        }
+        if (s->w1v.p == nullptr && oe == hipSuccess) {
+            oe = s->w1v.alloc(2 * kVer * (size_t)n1);
+            if (oe == hipSuccess) oe = s->w2v.alloc(sizeof(float) * kVer * (size_t)n2);
+            if (oe == hipSuccess) oe = s->b1v.alloc(sizeof(float) * kVer * (size_t)base.H);
+            if (oe == hipSuccess) oe = s->b2v.alloc(sizeof(float) * kVer * 16);
+        }
+        if (s->fwd_part.bytes < sizeof(float) * kVer * (size_t)region && oe == hipSuccess) {
+            // (nothing of an earlier segment still uses the smaller one: every segment ends with a wait for its streams)
+            s->fwd_part.release();
+            oe = s->fwd_part.alloc(sizeof(float) * kVer * (size_t)region);
+        }
+        int dev = 0;
+        if (oe == hipSuccess) oe = hipGetDevice(&dev);
+        if (oe != hipSuccess) { drop(); return fail(oe, "streams, events and buffers of the overlapped updates"); }
+        auto ev_upd = [&](int64_t v) { return s->ev_pool[(size_t)(v % kRing)]; };            // contraction and update of v done
+        auto ev_fwd = [&](int64_t v) { return s->ev_pool[(size_t)(kRing + v % kRing)]; };    // forward half of v done
+        auto versioned = [&](MlpArgs& a, int64_t ver) {
+            const int k = (int)(ver % kVer);
+            a.w1r = (unsigned short*)s->w1v.p + (int64_t)k * n1;
+            a.w2r = (float*)s->w2v.p + (int64_t)k * n2;
+            a.b1r = (float*)s->b1v.p + (int64_t)k * base.H;
+            a.b2r = (float*)s->b2v.p + (int64_t)k * 16;
+        };
+        const int64_t vs = v0 + q0;  // the first overlapped update
+        // the copies of version vs
+        {
+            MlpArgs a = base;
+            versioned(a, vs);
+            hipLaunchKernelGGL(mlp_refresh_kernel, dim3(1024), dim3(256), 0, stream, a.params, a.w1r, a.w2r, n1, off2, n2);
+            (void)hipMemcpyAsync(a.b1r, a.params + n1, sizeof(float) * base.H, hipMemcpyDeviceToDevice, stream);
+            (void)hipMemcpyAsync(a.b2r, a.params + off2 + n2, sizeof(float) * base.C, hipMemcpyDeviceToDevice, stream);
+        }
+        hipEvent_t start = s->ev_pool[2 * kRing];
+        (void)hipEventRecord(start, stream);
+        // what the host threads tell each other: an event may be waited for only after the call that records it
+        std::atomic<int64_t> upd_recorded{vs - 1};                 // ev_upd of every version up to here has been recorded
+        std::atomic<int64_t> fwd_recorded[3];                      // per forward stream: its newest version with ev_fwd recorded
+        for (auto& f : fwd_recorded) f.store(-1);
+        std::atomic<int> thread_error{0};
+        auto forward_half = [&](int k) {
+            if (hipSetDevice(dev) != hipSuccess) { thread_error.store((int)hipErrorInvalidDevice); return; }
+            hipStream_t fs = s->fwd_stream[k];
+            for (int64_t q = q0; q < n; ++q) {
+                const int64_t v = v0 + q;
+                if ((int)(v % 3) != k) continue;
+                while (upd_recorded.load(std::memory_order_acquire) < v - 1) {
+                    if (thread_error.load(std::memory_order_relaxed) != 0) return;
+                }
+                MlpArgs f = base;
+                f.v = v; f.Kv = Ks[0][(size_t)q]; f.nrec = nrec_of(0, q);
+                versioned(f, v);
+                f.dw_part = (float*)s->fwd_part.p + (v % kVer) * region;
+                f.fsplit = few_records_split(f, f.nrec);
+                (void)hipStreamWaitEvent(fs, q == q0 ? start : ev_upd(v - 1), 0);
+                hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, true>), dim3(f.nrec, f.H / 64, f.fsplit), dim3(256), contract_lds(64), fs, f);
+                hipLaunchKernelGGL(mlp_mid_kernel, dim3(f.nrec * 4), dim3(256), mid_lds_bytes(f.H), fs, f);
+                const hipError_t fe = hipEventRecord(ev_fwd(v), fs);
+                const hipError_t le = hipGetLastError();
+                if (fe != hipSuccess || le != hipSuccess) { thread_error.store((int)(fe != hipSuccess ? fe : le)); return; }
+                fwd_recorded[k].store(v, std::memory_order_release);
+            }
+        };
+        std::thread feeders[3];
+        for (int k = 0; k < 3; ++k) feeders[k] = std::thread(forward_half, k);
+        int64_t waited = vs - 1;     // the contractions have waited for the forward halves of every version up to here
+        auto wait_forward = [&](int64_t t) {
+            while (fwd_recorded[t % 3].load(std::memory_order_acquire) < t)
+                if (thread_error.load(std::memory_order_relaxed) != 0) return;
+            // (an event that has already happened needs no entry in the stream)
+            if (hipEventQuery(ev_fwd(t)) != hipSuccess) {
+                (void)hipGetLastError();   // "not ready" is no error of this thread's launches, which are checked one by one
+                (void)hipStreamWaitEvent(stream, ev_fwd(t), 0);
+            }
+        };
+        for (int64_t q = q0; q < n && thread_error.load() == 0; ++q) {
+            const int64_t v = v0 + q;
+            const int Kv = Ks[0][(size_t)q];
+            // contraction and update of v: after the forward halves of every version in its list, and of v + 1 - kVer
+            int64_t need = v + 1 - kVer;
+            for (int l = 0; l < Kv; ++l) need = std::max<int64_t>(need, tau_host[(size_t)(q * tr.Kcap + l)]);
+            need = std::min(need, v);
+            for (int64_t t = std::max(waited + 1, vs); t <= need; ++t) wait_forward(t);
+            waited = std::max(waited, need);
+            MlpArgs u = base;
+            u.v = v; u.Kv = Kv; u.nrec = nrec_of(0, q);
+            versioned(u, v + 1);
+            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(u.H / 64, u.d / 64 + 1), dim3(256), contract_lds(64), stream, u);
+            const hipError_t le = hipGetLastError();
+            const hipError_t re = hipEventRecord(ev_upd(v), stream);
+            if (le != hipSuccess || re != hipSuccess) { thread_error.store((int)(le != hipSuccess ? le : re)); break; }
+            upd_recorded.store(v, std::memory_order_release);
+        }
+        for (std::thread& f : feeders) f.join();
+        if (thread_error.load() == 0)
+            for (int64_t t = std::max(waited + 1, vs); t < v0 + n; ++t) (void)hipStreamWaitEvent(stream, ev_fwd(t), 0);
+        if (thread_error.load() != 0) {
+            for (hipStream_t f : s->fwd_stream) (void)hipStreamSynchronize(f);
+            (void)hipStreamSynchronize(stream);
+            drop();
+            return fail((hipError_t)thread_error.load(), "launching the overlapped updates");
+        }
+    }
     // update by update, the replicas in turn: nothing in one replica's launches depends on another's.  (Launching every
     // replica from a host thread of its own gave the same rate: the device, not the host, is what limits it.)
-    for (int64_t q = 0; q < n; ++q) {
+    for (int64_t q = 0; q < n && q0 == n; ++q) {
         for (int r = 0; r < R; ++r) {
             MlpArgs& a = args[(size_t)r];
             const std::vector<int32_t>& K = Ks[(size_t)r];
@@ -1372,8 +1546,10 @@ float* mlp_params(MlpState* s) { return s ? (float*)s->params.p : nullptr; }
 void mlp_destroy(MlpState* s) {
     if (!s) return;
     if (s->own) { (void)hipStreamSynchronize(s->own); (void)hipStreamDestroy(s->own); }
+    for (hipStream_t& f : s->fwd_stream) if (f) { (void)hipStreamSynchronize(f); (void)hipStreamDestroy(f); }
+    for (hipEvent_t ev : s->ev_pool) (void)hipEventDestroy(ev);
     DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss, &s->ylab,
-                      &s->dw_part, &s->plan, &s->quartered};
+                      &s->dw_part, &s->plan, &s->quartered, &s->w1v, &s->w2v, &s->b1v, &s->b2v, &s->fwd_part};
     for (DevMem* b : bufs) b->release();
     delete s;
 }

@@ -567,6 +567,30 @@ def test_mlp_replicas_are_independent_runs(ssgd, oracle, torch_cuda):
     ctx.close()
 
 
+def test_mlp_overlapped_updates_match_updates_one_after_the_other(ssgd, torch_cuda):
+    """A single K-async replica with few gradients per update overlaps the forward half of an update with the
+    contractions of its neighbours; the first replica of a two-replica context takes the same run with one update's
+    launches after the other's.  Same trace, same losses, bit-identical parameters -- with 4 workers and K = 2 most
+    consumed gradients were started one or two versions back, some at the very version that consumes them."""
+    torch = torch_cuda
+    X, y = synth.mixture_data(2000, 256, 10, seed=4)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    gd = ssgd.delay_dist("shifted_exp", 0.5, 1.0)
+    runs = []
+    for replicas in (1, 2):
+        ctx = ssgd.Context("mlp2", Xd, yd, 4, 2, 32, "k_async", gd, 0.05, seed=11, classes=10, hidden=128, bf16=1,
+                           replicas=replicas)
+        ctx.run(7); ctx.run(150); ctx.run(43)
+        runs.append((ctx.trace(0), ctx.params(0).copy()))
+        ctx.close()
+    (t1, p1), (t2, p2) = runs
+    staleness = t1["staleness"][:, :2]
+    assert (staleness == 0).any() and (staleness == 1).any()
+    for key in ("t", "K", "sel", "staleness", "loss"):
+        assert np.array_equal(t1[key], t2[key]), key
+    assert np.array_equal(p1, p2)
+
+
 def test_mlp_kbatch_async_training_run_with_plateau_doubling(ssgd, oracle, torch_cuda):
     """K-batch-async on the MLP, free-running for 120 updates while AdaSync doubles K (2 -> 8) on plateaus: the slot
     of every mini-batch in flight survives the changes of K."""
