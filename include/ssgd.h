@@ -80,7 +80,8 @@ typedef struct {
     int32_t d, classes, hidden;
     int32_t bf16;    /* SSGD_MLP2: 1 = bf16 operands, fp32 accumulation, in the two
                         contractions over d; must be 0 for the linear models */
-    const float *X;  /* DEVICE, N x d row-major fp32; must outlive the context */
+    const float *X;  /* DEVICE, N x d row-major fp32; must outlive the context and stay unchanged:
+                      * SSGD_MLP2 keeps its values rounded to bf16, taken when the context is made */
     const void *y;   /* DEVICE, float[N] (LSQ) or int32[N] labels in [0, classes) */
     int64_t N;       /* 1 <= N < 2^32 */
 } ssgd_model;

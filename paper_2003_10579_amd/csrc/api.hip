@@ -519,7 +519,7 @@ ssgd_status ssgd_create(const ssgd_model* model, int32_t P, int32_t K, int32_t m
         std::string msg;
         for (int r = 0; r < replicas; ++r) {
             MlpState* ms = nullptr;
-            hipError_t e = mlp_create(&ms, *model, P, m, variant, Kcap, lr, seed, r, c->stream, &msg);
+            hipError_t e = mlp_create(&ms, *model, P, m, variant, Kcap, lr, seed, r, c->mlp.empty() ? nullptr : c->mlp[0], c->stream, &msg);
             if (e != hipSuccess)
                 return bail(e == hipErrorOutOfMemory ? SSGD_ENOMEM : (e == hipErrorInvalidValue ? SSGD_EINVAL : SSGD_EDEVICE), "mlp_create: " + msg);
             c->mlp.push_back(ms);
@@ -994,7 +994,7 @@ void ssgd_destroy(ssgd_ctx* c) {
                 fprintf(stderr, "\n");
             }
     }
-    for (MlpState* ms : c->mlp) mlp_destroy(ms);
+    for (size_t r = c->mlp.size(); r-- > 0;) mlp_destroy(c->mlp[r]);   // the first one owns what the others share
     if (c->side) (void)hipStreamDestroy(c->side);
     DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,
                       &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx, &c->ws_F0,

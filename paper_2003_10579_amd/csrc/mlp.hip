@@ -62,6 +62,7 @@ struct MlpArgs {
     float* params;             // W1[H][d], b1[H], W2[C][H], b2[C]
     unsigned short* w1r;       // bf16 copy of W1
     float* w2r;                // W2 rounded to bf16, kept as fp32
+    const unsigned short* Xb;  // [N + 1][d] the sample matrix rounded to bf16 (taken when the context is made); row N is zero
     float* b1r;                // nullable: a copy of b1 (read by the layer-2 kernel, written by the small update) ...
     float* b2r;                // ... and of b2, when updates overlap and every version of the parameters has copies of its own
     unsigned short* xb;        // [S][MP][d]   bf16 rows of the slot's mini-batch
@@ -407,7 +408,7 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
 // ---- Few records (small K): the forward pass straight from the sample matrix --------------------------------
 // One launch does what the gather kernel, the split forward contraction and its finishing kernel do otherwise:
 // workgroup (record r, 64 hidden units bn, share z of the depth d) draws the sample ids of the record, reads its rows
-// from X in fp32, rounds them to bf16 on the way to LDS and leaves its partial sums of Z1 in dw_part; the workgroups
+// from the bf16 copy of X and leaves its partial sums of Z1 in dw_part; the workgroups
 // with bn = 0 also write the rows' transposed bf16 copy, which the first-layer gradient contraction of a later update
 // reads.  (Workgroups of one launch do not hand results to each other: making one workgroup's stores visible to
 // another on a different XCD costs a write-back of the L2, far more than the launch it would save.)  A launch of this
@@ -446,23 +447,21 @@ __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
         stages = max(0, min(per, total - stage0));
     }
     const int lchunk = tid & 7, lrow = tid >> 3;
-    const float* xrow[LP];
-    bool has[LP];
+    // (rows from the bf16 copy of the sample matrix; row N of it is all zero and stands for the rows a record lacks)
+    const unsigned short* xrow[LP];
 #pragma unroll
     for (int i = 0; i < LP; ++i) {
         const uint32_t id = ids[lrow + 32 * i];
-        has[i] = id != 0xFFFFFFFFu;
-        xrow[i] = a.X + (int64_t)(has[i] ? id : 0u) * d + 8 * lchunk;
+        xrow[i] = a.Xb + (int64_t)(id != 0xFFFFFFFFu ? id : a.N) * d + 8 * lchunk;
     }
     const unsigned short* wrow = a.w1r + (int64_t)(bn * BT + lrow) * d + 8 * lchunk;
-    f32x4 ra[PF][LP][2];
+    u16x8 ra[PF][LP];
     u16x8 rb[PF][LP];
     auto fetch = [&](auto ring, int stage) {
         constexpr int Q = decltype(ring)::value;
 #pragma unroll
         for (int i = 0; i < LP; ++i) {
-            ra[Q][i][0] = *reinterpret_cast<const f32x4*>(xrow[i] + stage * KT);
-            ra[Q][i][1] = *reinterpret_cast<const f32x4*>(xrow[i] + stage * KT + 4);
+            ra[Q][i] = *reinterpret_cast<const u16x8*>(xrow[i] + stage * KT);
             rb[Q][i] = *reinterpret_cast<const u16x8*>(wrow + (int64_t)32 * i * d + stage * KT);
         }
     };
@@ -471,11 +470,7 @@ __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
 #pragma unroll
         for (int i = 0; i < LP; ++i) {
             const int row = lrow + 32 * i;
-            // eight floats -> bf16, round to nearest even, on the packed conversion unit
-            f32x8 w;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) w[e] = has[i] ? ra[Q][i][e >> 2][e & 3] : 0.0f;
-            *reinterpret_cast<bf16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = __builtin_convertvector(w, bf16x8);
+            *reinterpret_cast<u16x8*>(As + (buf * BT + row) * LDT + 8 * lchunk) = ra[Q][i];
             *reinterpret_cast<u16x8*>(Bs + (buf * BT + row) * LDT + 8 * lchunk) = rb[Q][i];
         }
     };
@@ -956,6 +951,22 @@ __global__ void mlp_refresh_kernel(const float* params, unsigned short* w1r, flo
     for (int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; q < n2; q += stride) w2r[q] = bf16_round(params[off2 + q]);
 }
 
+// the sample matrix in bf16 (round to nearest even, eight values per thread and pass), and a row of zeros behind it
+__global__ void mlp_rows_bf16_kernel(const float* X, unsigned short* Xb, int64_t n8, int64_t zero8) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; q < n8 + zero8; q += stride) {
+        f32x8 w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = 0.0f;
+        if (q < n8) {
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(X + 8 * q), hi = *reinterpret_cast<const f32x4*>(X + 8 * q + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { w[e] = lo[e]; w[4 + e] = hi[e]; }
+        }
+        *reinterpret_cast<bf16x8*>(Xb + 8 * q) = __builtin_convertvector(w, bf16x8);
+    }
+}
+
 // W1, W2 uniform on (-1/sqrt(fan_in), 1/sqrt(fan_in)) from the INIT stream, biases zero
 __global__ void mlp_init_kernel(float* params, uint64_t seed, int64_t nw, int64_t n1, int64_t off2, int64_t n2, float bound1, float bound2) {
 #pragma clang fp contract(off)
@@ -999,6 +1010,7 @@ struct MlpState {
     hipStream_t own = nullptr;   // replicas beyond the first run on streams of their own, beside each other
     // overlapped updates (few records, one replica): kVer versions of the operand copies of the parameters, three
     // streams for the forward halves of consecutive updates, a pool of events
+    DevMem xb16;                 // the first replica's bf16 copy of the sample matrix; the others use it too
     DevMem w1v, w2v, b1v, b2v, fwd_part;   // allocated by the first segment that overlaps
     hipStream_t fwd_stream[3] = {nullptr, nullptr, nullptr};
     std::vector<hipEvent_t> ev_pool;
@@ -1007,7 +1019,7 @@ struct MlpState {
 };
 
 hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int variant, int Kcap, double lr,
-                      uint64_t seed, int replica, hipStream_t stream, std::string* msg) {
+                      uint64_t seed, int replica, const MlpState* first, hipStream_t stream, std::string* msg) {
     auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
     if (!model.bf16) return fail(hipErrorInvalidValue, "the MLP runs with bf16 operands only (model.bf16 = 1)");
     if (m > MP) return fail(hipErrorInvalidValue, "the MLP keeps at most 64 rows per mini-batch");
@@ -1043,6 +1055,15 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     TRY(s->quartered.alloc(sizeof(int32_t) * S));
     TRY(hipMemsetAsync(s->quartered.p, 0, sizeof(int32_t) * S, stream));
     TRY(s->dw_part.alloc(sizeof(float) * kMaxSplit * (size_t)n1));
+    if (first != nullptr) {
+        a.Xb = first->a.Xb;
+    } else {
+        TRY(s->xb16.alloc(2 * ((size_t)model.N + 1) * a.d));
+        a.Xb = (const unsigned short*)s->xb16.p;
+        hipLaunchKernelGGL(mlp_rows_bf16_kernel, dim3(2048), dim3(256), 0, stream, model.X, (unsigned short*)s->xb16.p,
+                           (int64_t)model.N * a.d / 8, (int64_t)a.d / 8);
+        TRY(hipGetLastError());
+    }
     {
         // every slot free (popped in the order 0, 1, ...), no worker has a mini-batch yet
         std::vector<int32_t> h(PlanView::words(P, s->S, Kcap), 0);
@@ -1549,7 +1570,7 @@ void mlp_destroy(MlpState* s) {
     for (hipStream_t& f : s->fwd_stream) if (f) { (void)hipStreamSynchronize(f); (void)hipStreamDestroy(f); }
     for (hipEvent_t ev : s->ev_pool) (void)hipEventDestroy(ev);
     DevMem* bufs[] = {&s->params, &s->w1r, &s->w2r, &s->xb, &s->xbt, &s->hbuf, &s->d1t, &s->gb1, &s->gw2, &s->gb2, &s->d2, &s->loss, &s->ylab,
-                      &s->dw_part, &s->plan, &s->quartered, &s->w1v, &s->w2v, &s->b1v, &s->b2v, &s->fwd_part};
+                      &s->dw_part, &s->plan, &s->quartered, &s->w1v, &s->w2v, &s->b1v, &s->b2v, &s->fwd_part, &s->xb16};
     for (DevMem* b : bufs) b->release();
     delete s;
 }

@@ -9,9 +9,11 @@ namespace ssgd {
 
 struct MlpState;
 
-// One state per replica (independent runs that differ in the replica field of their random draws).
+// One state per replica (independent runs that differ in the replica field of their random draws).  The first replica
+// (first == nullptr) makes a bf16 copy of the sample matrix as it is at this call; the others read that copy, so the first
+// state is destroyed last.
 hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int variant, int Kcap, double lr,
-                      uint64_t seed, int replica, hipStream_t stream, std::string* msg);
+                      uint64_t seed, int replica, const MlpState* first, hipStream_t stream, std::string* msg);
 // Runs updates [v0, v0+n) of all R replicas, whose schedules are already in the trace; agg_out: replica 0's.
 hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n,
                            float* agg_out, hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg);
