@@ -1314,7 +1314,13 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
                 versioned(f, v);
                 f.dw_part = (float*)s->fwd_part.p + (v % kVer) * region;
                 f.fsplit = few_records_split(f, f.nrec);
-                (void)hipStreamWaitEvent(fs, q == q0 ? start : ev_upd(v - 1), 0);
+                // (asked for on the host until it has happened: making the stream wait for an event that has not happened yet
+                // is the most expensive call there is here, 12 us, and a waiting entry holds up the kernels of the other
+                // streams that share its hardware queue)
+                while (hipEventQuery(q == q0 ? start : ev_upd(v - 1)) != hipSuccess) {
+                    (void)hipGetLastError();
+                    if (thread_error.load(std::memory_order_relaxed) != 0) return;
+                }
                 hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, true>), dim3(f.nrec, f.H / 64, f.fsplit), dim3(256), contract_lds(64), fs, f);
                 hipLaunchKernelGGL(mlp_mid_kernel, dim3(f.nrec * 4), dim3(256), mid_lds_bytes(f.H), fs, f);
                 const hipError_t fe = hipEventRecord(ev_fwd(v), fs);
