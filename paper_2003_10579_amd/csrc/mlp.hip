@@ -552,7 +552,7 @@ __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
 #pragma unroll
         for (int j = 0; j < NF; ++j) {
             const int col = bn * BT + wn * WT + j * 32 + (lane & 31);
-            const float b1 = SPLIT ? 0.0f : a.params[(int64_t)H * d + col];
+            const float b1 = SPLIT ? 0.0f : (a.b1r ? a.b1r[col] : a.params[(int64_t)H * d + col]);
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int row = wm * WT + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
@@ -759,7 +759,7 @@ __global__ __launch_bounds__(256) void mlp_output_kernel(MlpArgs a) {
     const int cls = lane & 15, kq = lane >> 4;
     const float* hp = a.hbuf + ((int64_t)slot * MP + 16 * wave + (lane & 15)) * H + 4 * kq;
     const float* wp = a.w2r + (int64_t)min(cls, C - 1) * H + 4 * kq;
-    const float b2 = a.params[(int64_t)H * a.d + H + (int64_t)C * H + min(cls, C - 1)];
+    const float b2 = a.b2r ? a.b2r[min(cls, C - 1)] : a.params[(int64_t)H * a.d + H + (int64_t)C * H + min(cls, C - 1)];
     int labs[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) labs[e] = a.ylab[slot * MP + 16 * wave + 4 * kq + e];
@@ -1124,8 +1124,9 @@ bool few_records(const MlpArgs& a, int nrec, int regions) {
 }
 int few_records_split(const MlpArgs& a, int nrec) { return std::max(2, std::min(8, 512 / (nrec * (a.H / 64)))); }
 
-// the launches of one update (a.v, a.Kv, a.nrec set) on `stream`
-void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
+// The launches of one update (a.v, a.Kv, a.nrec set), in two halves.  Forward half: the mini-batches that start at
+// version v, up to delta1 and the second-layer gradient records of their slots.
+void launch_forward(MlpArgs& a, hipStream_t stream) {
     if (a.variant == kBatchAsync) hipLaunchKernelGGL(mlp_batch_plan_kernel, dim3(1), dim3(64), 0, stream, a);
     if (few_records(a, a.nrec, 1)) {
         // few records: two launches; the depth is split so that two workgroups share every CU and none walks all of d
@@ -1143,6 +1144,9 @@ void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
         hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
         hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
     }
+}
+// Backward half: the first-layer gradient over the consumed slots and the update of every parameter.
+void launch_backward(MlpArgs& a, hipStream_t stream) {
     if (a.Kv >= 32) {
         // many slots: 128 x 128 tiles (half the operand traffic of the small ones), the slots split into shares so
         // that the chip is still full; the shares are added, in order, by the update kernel
@@ -1158,7 +1162,10 @@ void launch_update(MlpState* s, MlpArgs& a, hipStream_t stream) {
         // workgroups takes the small parameters
         hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64 + 1), dim3(256), contract_lds(64), stream, a);
     }
-    (void)s;
+}
+void launch_update(MlpArgs& a, hipStream_t stream) {
+    launch_forward(a, stream);
+    launch_backward(a, stream);
 }
 
 }  // namespace
@@ -1224,33 +1231,40 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
         if (a.variant == kAsync) return v0 + q == 0 ? a.P : (q == 0 ? prevK[(size_t)r] : K[(size_t)q - 1]);
         return K[(size_t)q];
     };
-    // One K-async run whose updates all start few gradients and consume few: the two halves of an update overlap with
-    // those of its neighbours.  The gradients that update v consumes were computed at versions tau <= v (Sec. 2.2), as
-    // a rule many updates ago, so the contraction and update of v (which give w_{v+1}) need the contraction of v - 1 and
-    // the forward halves of the versions in its list, not the forward half of v itself; that one needs w_v only.  The
-    // contractions follow each other on `stream`; the forward halves of consecutive versions go to three streams in
-    // turn, each fed by a host thread of its own (the host's calls, not the device, would otherwise set the pace).
+    // One K-async run: the two halves of an update overlap with those of its neighbours.  The gradients that update v
+    // consumes were computed at versions tau <= v (Sec. 2.2), with few gradients per update many updates ago, so the
+    // backward half of v (which gives w_{v+1}) needs the backward half of v - 1 and the forward halves of the versions in
+    // its list, not the forward half of v itself unless the list names it; that one needs w_v only.  The backward halves
+    // follow each other on `stream`; the forward halves of consecutive versions go to three streams in turn, each fed
+    // by a host thread of its own (the host's calls, not the device, would otherwise set the pace).
     // The operand copies of the parameters (bf16 W1, rounded W2, the biases) and the partial sums of the split forward
     // pass exist kVer times, indexed by version modulo kVer: the update of v writes the copies of v + 1 after the
-    // forward half of v + 1 - kVer, their last reader, has ended.
-    // (the updates of the segment from q0 on, when all of those qualify; the ones before them, the first update of a run
-    // among them, are launched one after the other as below)
+    // forward half of v + 1 - kVer, their last reader, has ended.  (With K near P most lists name the version itself and
+    // the halves run one after the other as they would on one stream.)
+    // (worth it where at most a quarter of the lists of the segment name their own version)
     int64_t q0 = n;
-    if (tau_host.size() == (size_t)(n * tr.Kcap))
-        while (q0 > 0 && Ks[0][(size_t)q0 - 1] < 32 && few_records(args[0], nrec_of(0, q0 - 1), 1)) --q0;
-    if (n - q0 < 4) q0 = n;
+    if (tau_host.size() == (size_t)(n * tr.Kcap) && n >= 4) {
+        int64_t own = 0;
+        for (int64_t q = 0; q < n; ++q) {
+            bool names_itself = false;
+            for (int l = 0; l < Ks[0][(size_t)q]; ++l) names_itself |= tau_host[(size_t)(q * tr.Kcap + l)] >= (int32_t)(v0 + q);
+            own += names_itself ? 1 : 0;
+        }
+        if (4 * own <= n) q0 = 0;
+    }
     if (q0 < n) {
         // the updates before q0
         for (int64_t q = 0; q < q0; ++q) {
             MlpArgs& a = args[0];
             a.v = v0 + q; a.Kv = Ks[0][(size_t)q]; a.nrec = nrec_of(0, q);
-            launch_update(states[0], a, stream);
+            launch_update(a, stream);
         }
         MlpState* s = states[0];
         const MlpArgs& base = args[0];
         const int64_t n1 = (int64_t)base.H * base.d, off2 = n1 + base.H, n2 = (int64_t)base.C * base.H;
         int nrec_max = 1;
-        for (int64_t q = q0; q < n; ++q) nrec_max = std::max(nrec_max, nrec_of(0, q));
+        for (int64_t q = q0; q < n; ++q)
+            if (few_records(base, nrec_of(0, q), 1)) nrec_max = std::max(nrec_max, nrec_of(0, q));
         const int64_t region = (int64_t)8 * nrec_max * MP * base.H;
         hipError_t oe = hipSuccess;
         for (hipStream_t& f : s->fwd_stream)
@@ -1313,7 +1327,6 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
                 f.v = v; f.Kv = Ks[0][(size_t)q]; f.nrec = nrec_of(0, q);
                 versioned(f, v);
                 f.dw_part = (float*)s->fwd_part.p + (v % kVer) * region;
-                f.fsplit = few_records_split(f, f.nrec);
                 // (asked for on the host until it has happened: making the stream wait for an event that has not happened yet
                 // is the most expensive call there is here, 12 us, and a waiting entry holds up the kernels of the other
                 // streams that share its hardware queue)
@@ -1321,8 +1334,7 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
                     (void)hipGetLastError();
                     if (thread_error.load(std::memory_order_relaxed) != 0) return;
                 }
-                hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, true>), dim3(f.nrec, f.H / 64, f.fsplit), dim3(256), contract_lds(64), fs, f);
-                hipLaunchKernelGGL(mlp_mid_kernel, dim3(f.nrec * 4), dim3(256), mid_lds_bytes(f.H), fs, f);
+                launch_forward(f, fs);
                 const hipError_t fe = hipEventRecord(ev_fwd(v), fs);
                 const hipError_t le = hipGetLastError();
                 if (fe != hipSuccess || le != hipSuccess) { thread_error.store((int)(fe != hipSuccess ? fe : le)); return; }
@@ -1353,7 +1365,7 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             MlpArgs u = base;
             u.v = v; u.Kv = Kv; u.nrec = nrec_of(0, q);
             versioned(u, v + 1);
-            hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(u.H / 64, u.d / 64 + 1), dim3(256), contract_lds(64), stream, u);
+            launch_backward(u, stream);
             const hipError_t le = hipGetLastError();
             const hipError_t re = hipEventRecord(ev_upd(v), stream);
             if (le != hipSuccess || re != hipSuccess) { thread_error.store((int)(le != hipSuccess ? le : re)); break; }
@@ -1379,7 +1391,7 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             a.Kv = K[(size_t)q];
             a.nrec = (a.variant == kAsync) ? (a.v == 0 ? a.P : (q == 0 ? prevK[(size_t)r] : K[(size_t)q - 1])) : a.Kv;
             if (a.variant == kBatchAsync) a.nrec = (a.v == 0 ? a.P : 1) + a.Kv - 1;
-            launch_update(states[r], a, r == 0 ? stream : states[r]->own);
+            launch_update(a, r == 0 ? stream : states[r]->own);
         }
     }
     if (launches) *launches += n;
