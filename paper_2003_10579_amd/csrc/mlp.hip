@@ -293,6 +293,7 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     // asked for and not yet stored to LDS, so that PF stages (PF x BT x 256 bytes) are in flight per workgroup: with one
     // stage in flight a workgroup is bound by the latency of its loads, whatever the tile size.
     constexpr int PF = 3;
+    constexpr bool kAlways = FWD || SPLIT;   // the loops of these are long (d / 64 stages, or a share of many slots)
     u16x8 ra[PF][LP], rb[PF][LP];
     auto fetch = [&](auto slot, int stage) {
         constexpr int Q = decltype(slot)::value;
@@ -333,7 +334,14 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
     // stage st is in LDS buffer st & 1 and came from ring slot st % PF, which is free again
     auto one_stage = [&](auto cur, auto nxt, int st) {
         const int buf = st & 1;
-        if (st + PF < stages) fetch(cur, stage0 + st + PF);
+        // (long loops: always issued, the last stages over again at the end.  Behind a branch the compiler no longer knows
+        // how many loads are in flight and makes the stores to LDS below wait for all of them, these new ones included.)
+        if constexpr (kAlways) {
+            fetch(cur, stage0 + min(st + PF, stages - 1));
+            // the loads go out before anything else of the stage: moved down between the MFMAs, their registers get
+            // shared with the operand fragments, and every stage then starts by waiting for all loads in flight
+            __builtin_amdgcn_sched_barrier(0);
+        } else if (st + PF < stages) fetch(cur, stage0 + st + PF);
 #pragma unroll
         for (int kk = 0; kk < KT / 16; ++kk) {
             bf16x8 fa[NF], fb[NF];
@@ -350,13 +358,27 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
                 for (int j = 0; j < NF; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
-        if (st + 1 < stages) stash(nxt, buf ^ 1);
+        // (long loops: also after the last stage, whose other buffer nobody reads any more -- no branch, see above)
+        if constexpr (kAlways) stash(nxt, buf ^ 1);
+        else if (st + 1 < stages) stash(nxt, buf ^ 1);
         __syncthreads();
     };
-    for (int st = 0; st < stages; st += PF) {
-        one_stage(I0{}, I1{}, st);
+    if constexpr (kAlways) {
+        // whole rounds of the ring without a branch inside, then what is left
+        int st = 0;
+        for (; st + PF <= stages; st += PF) {
+            one_stage(I0{}, I1{}, st);
+            one_stage(I1{}, I2{}, st + 1);
+            one_stage(I2{}, I0{}, st + 2);
+        }
+        if (st < stages) one_stage(I0{}, I1{}, st);
         if (st + 1 < stages) one_stage(I1{}, I2{}, st + 1);
-        if (st + 2 < stages) one_stage(I2{}, I0{}, st + 2);
+    } else {
+        for (int st = 0; st < stages; st += PF) {
+            one_stage(I0{}, I1{}, st);
+            if (st + 1 < stages) one_stage(I1{}, I2{}, st + 1);
+            if (st + 2 < stages) one_stage(I2{}, I0{}, st + 2);
+        }
     }
 
     // The result goes through LDS so that the global accesses of the epilogue run along rows.
@@ -417,6 +439,7 @@ template <int BT, bool SPLIT>
 __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
     constexpr int LP = BT / 32;         // row chunks per thread, operand and stage
     constexpr int PF = BT == 64 ? 3 : 2;
+    constexpr bool kAlways = !SPLIT;         // d / 64 stages; a share of them when the depth is split
     constexpr int RPT = BT / MP;        // records per workgroup
     constexpr int WT = BT / 2, NF = WT / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
@@ -496,7 +519,14 @@ __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
     __syncthreads();
     auto one_stage = [&](auto cur, auto nxt, int st) {
         const int buf = st & 1;
-        if (st + PF < stages) fetch(cur, stage0 + st + PF);
+        // (long loops: always issued, the last stages over again at the end.  Behind a branch the compiler no longer knows
+        // how many loads are in flight and makes the stores to LDS below wait for all of them, these new ones included.)
+        if constexpr (kAlways) {
+            fetch(cur, stage0 + min(st + PF, stages - 1));
+            // the loads go out before anything else of the stage: moved down between the MFMAs, their registers get
+            // shared with the operand fragments, and every stage then starts by waiting for all loads in flight
+            __builtin_amdgcn_sched_barrier(0);
+        } else if (st + PF < stages) fetch(cur, stage0 + st + PF);
 #pragma unroll
         for (int kk = 0; kk < KT / 16; ++kk) {
             bf16x8 fa[NF], fb[NF];
@@ -531,10 +561,29 @@ __global__ __launch_bounds__(256, 2) void mlp_fwd_gather_kernel(MlpArgs a) {
                 }
             }
         }
-        if (st + 1 < stages) stash(nxt, buf ^ 1);
+        // (long loops: also after the last stage, whose other buffer nobody reads any more -- no branch, see above)
+        if constexpr (kAlways) stash(nxt, buf ^ 1);
+        else if (st + 1 < stages) stash(nxt, buf ^ 1);
         __syncthreads();
     };
-    if constexpr (PF == 3) {
+    if constexpr (kAlways && PF == 3) {
+        // whole rounds of the ring without a branch inside, then what is left
+        int st = 0;
+        for (; st + 3 <= stages; st += 3) {
+            one_stage(I0{}, I1{}, st);
+            one_stage(I1{}, I2{}, st + 1);
+            one_stage(I2{}, I0{}, st + 2);
+        }
+        if (st < stages) one_stage(I0{}, I1{}, st);
+        if (st + 1 < stages) one_stage(I1{}, I2{}, st + 1);
+    } else if constexpr (kAlways) {
+        int st = 0;
+        for (; st + 2 <= stages; st += 2) {
+            one_stage(I0{}, I1{}, st);
+            one_stage(I1{}, I0{}, st + 1);
+        }
+        if (st < stages) one_stage(I0{}, I1{}, st);
+    } else if constexpr (PF == 3) {
         for (int st = 0; st < stages; st += 3) {
             one_stage(I0{}, I1{}, st);
             if (st + 1 < stages) one_stage(I1{}, I2{}, st + 1);
@@ -724,24 +773,6 @@ __global__ __launch_bounds__(256) void mlp_mid_kernel(MlpArgs a) {
     }
     if (tid == 16) a.loss[slot * 4 + q] = (red[0] + red[1]) + (red[2] + red[3]);
     if (tid == 17 && q == 0) a.quartered[slot] = 1;
-}
-
-// ---- first-layer update from the partial sums of a split gradient contraction: shares added in order --------
-__global__ __launch_bounds__(256) void mlp_w1_update_kernel(MlpArgs a) {
-    const int64_t n4 = (int64_t)a.H * a.d / 4;
-    const float scale = a.lr / (float)a.Kv, invK = 1.0f / (float)a.Kv;
-    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < n4; q += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t p = 4 * q;
-        f32x4 v = *reinterpret_cast<const f32x4*>(a.dw_part + p);
-        for (int sp = 1; sp < a.nsplit; ++sp) v += *reinterpret_cast<const f32x4*>(a.dw_part + (int64_t)sp * a.H * a.d + p);
-        f32x4 w = *reinterpret_cast<const f32x4*>(a.params + p);
-        unsigned short wb[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) { w[c] -= scale * v[c]; wb[c] = bf16_bits(w[c]); }
-        *reinterpret_cast<f32x4*>(a.params + p) = w;
-        *reinterpret_cast<uint2*>(a.w1r + p) = make_uint2((uint32_t)wb[0] | ((uint32_t)wb[1] << 16), (uint32_t)wb[2] | ((uint32_t)wb[3] << 16));
-        if (a.agg_out) *reinterpret_cast<f32x4*>(a.agg_out + p) = v * invK;
-    }
 }
 
 // ---- layer 2 and softmax: one workgroup per record; wave w takes rows 16 w .. 16 w + 15 -------------
@@ -942,8 +973,29 @@ __device__ __forceinline__ void small_update_body(const MlpArgs& a, int block, i
         }
     }
 }
-template <int G>
-__global__ __launch_bounds__(256) void mlp_small_update_kernel(MlpArgs a) { small_update_body<G>(a, blockIdx.x, gridDim.x); }
+
+// ---- first-layer update from the partial sums of a split gradient contraction: shares added in order; the
+// first kSmallBlocks16 workgroups take the small parameters of the update instead, which need nothing from the others
+// (first, because theirs is the longer chain of loads)
+constexpr int kW1Blocks = 1024, kSmallBlocks16 = 360;
+__global__ __launch_bounds__(256) void mlp_w1_update_kernel(MlpArgs a) {
+    if ((int)blockIdx.x < kSmallBlocks16) { small_update_body<16>(a, blockIdx.x, kSmallBlocks16); return; }
+    const int block = blockIdx.x - kSmallBlocks16;
+    const int64_t n4 = (int64_t)a.H * a.d / 4;
+    const float scale = a.lr / (float)a.Kv, invK = 1.0f / (float)a.Kv;
+    for (int64_t q = (int64_t)block * blockDim.x + threadIdx.x; q < n4; q += (int64_t)kW1Blocks * blockDim.x) {
+        const int64_t p = 4 * q;
+        f32x4 v = *reinterpret_cast<const f32x4*>(a.dw_part + p);
+        for (int sp = 1; sp < a.nsplit; ++sp) v += *reinterpret_cast<const f32x4*>(a.dw_part + (int64_t)sp * a.H * a.d + p);
+        f32x4 w = *reinterpret_cast<const f32x4*>(a.params + p);
+        unsigned short wb[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { w[c] -= scale * v[c]; wb[c] = bf16_bits(w[c]); }
+        *reinterpret_cast<f32x4*>(a.params + p) = w;
+        *reinterpret_cast<uint2*>(a.w1r + p) = make_uint2((uint32_t)wb[0] | ((uint32_t)wb[1] << 16), (uint32_t)wb[2] | ((uint32_t)wb[3] << 16));
+        if (a.agg_out) *reinterpret_cast<f32x4*>(a.agg_out + p) = v * invK;
+    }
+}
 
 __global__ void mlp_refresh_kernel(const float* params, unsigned short* w1r, float* w2r, int64_t n1, int64_t off2, int64_t n2) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -1155,8 +1207,7 @@ void launch_backward(MlpArgs& a, hipStream_t stream) {
         const int tiles = (a.H / 128) * (a.d / 128);
         a.nsplit = std::max(1, std::min({kMaxSplit, a.Kv / 8, 512 / tiles}));
         hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3((a.H / 128) * 8 * (((a.d / 128) * a.nsplit + 7) / 8)), dim3(256), contract_lds(128), stream, a);
-        hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
-        hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(kW1Blocks + kSmallBlocks16), dim3(256), 0, stream, a);
     } else {
         // small tiles: 384 workgroups instead of 96 matter more than the reuse inside a larger tile; one more row of
         // workgroups takes the small parameters
@@ -1524,8 +1575,7 @@ hipError_t mlp_full_gradient(MlpState* s, float* grad_out_host, hipStream_t stre
             const int tiles = (a.H / 128) * (a.d / 128);
             a.nsplit = std::max(1, std::min({kMaxSplit, a.Kv / 8, 512 / tiles}));
             hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3((a.H / 128) * 8 * (((a.d / 128) * a.nsplit + 7) / 8)), dim3(256), contract_lds(128), stream, a);
-            hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(1024), dim3(256), 0, stream, a);
-            hipLaunchKernelGGL(mlp_small_update_kernel<16>, dim3(360), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(kW1Blocks + kSmallBlocks16), dim3(256), 0, stream, a);
         } else {
             hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64 + 1), dim3(256), contract_lds(64), stream, a);
         }

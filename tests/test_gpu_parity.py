@@ -465,7 +465,7 @@ def test_mc_kbatch_async_closed_form_at_scale(ssgd, torch_cuda):
 # the difference visible are decisions taken on those sums -- a hidden unit whose pre-activation is
 # within that error of zero switches its ReLU mask, and a delta1 value within it of a bf16 rounding
 # boundary moves by one bf16 ulp (2^-8 relative) -- each a rare, isolated change of one entry.
-MLP_GRAD_TOL = 3e-4     # observed: 6e-7 ... 9e-5
+MLP_GRAD_TOL = 3e-4     # observed: 6e-7 ... 9e-5, and 1.9e-4 for the mean of 256 gradients at full size (more cancellation)
 MLP_PARAM_TOL = 2e-3
 
 
