@@ -18,6 +18,8 @@
 //   consume   W1 -= lr/K * sum_l delta1_l^T X_l (MFMA), then b1, W2, b2 and the loss record
 #include "mlp.hpp"
 
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 #include <atomic>
 #include <thread>
@@ -63,6 +65,12 @@ struct MlpArgs {
     unsigned short* w1r;       // bf16 copy of W1
     float* w2r;                // W2 rounded to bf16, kept as fp32
     const unsigned short* Xb;  // [N + 1][d] the sample matrix rounded to bf16 (taken when the context is made); row N is zero
+    // The lists of the update when the host has them at hand and they are short: a kernel that finds them in its
+    // arguments is spared a first load that everything else would wait for.
+    int32_t n_cons_inline;     // > 0: cons_inline holds the slots of the Kv consumed gradients (K-async)
+    int32_t n_rec_inline;      // > 0: rec_inline holds the workers of the nrec mini-batches that start (K-async)
+    int16_t cons_inline[32];
+    int16_t rec_inline[32];
     float* b1r;                // nullable: a copy of b1 (read by the layer-2 kernel, written by the small update) ...
     float* b2r;                // ... and of b2, when updates overlap and every version of the parameters has copies of its own
     unsigned short* xb;        // [S][MP][d]   bf16 rows of the slot's mini-batch
@@ -117,7 +125,7 @@ __device__ __forceinline__ void record_of(const MlpArgs& a, int r, int& worker, 
         const PlanView pl(a.plan, a.P, a.S, a.Kcap);
         worker = pl.rec_worker[r]; ordinal = pl.rec_ord[r]; slot = pl.rec_slot[r];
     } else if (a.variant == kAsync) {
-        worker = (a.v == 0) ? r : a.tr.sel[(a.v - 1) * a.tr.Kcap + r];
+        worker = a.n_rec_inline > 0 ? (int)a.rec_inline[r] : ((a.v == 0) ? r : a.tr.sel[(a.v - 1) * a.tr.Kcap + r]);
         ordinal = 0;
         slot = worker;
     } else {
@@ -129,6 +137,7 @@ __device__ __forceinline__ void record_of(const MlpArgs& a, int r, int& worker, 
 __device__ __forceinline__ int consumed_slot(const MlpArgs& a, int l) {
     if (a.eval_base >= 0) return l;       // evaluation over the data set: every record of the block
     if (a.variant == kBatchAsync) return PlanView(a.plan, a.P, a.S, a.Kcap).cons_slot[l];
+    if (a.n_cons_inline > 0) return (int)a.cons_inline[l];
     return a.variant == kAsync ? a.tr.sel[a.v * a.tr.Kcap + l] : l;
 }
 
@@ -251,6 +260,17 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
         // a launch with one more row of workgroups than there are column tiles: that row takes the small parameters of
         // the update (they do not depend on the contraction), which saves a launch per update
         if ((int)blockIdx.y == d / BT) { small_update_body<1>(a, blockIdx.x, gridDim.x); return; }
+    }
+    // the fused update reads its tile of the fp32 parameters now, not after the contraction that it does not depend on
+    constexpr int C4 = BT / 4;           // float4 groups per row
+    constexpr int NPRE = (!FWD && !SPLIT) ? BT * C4 / 256 : 1;
+    f32x4 wpre[NPRE];
+    if constexpr (!FWD && !SPLIT) {
+#pragma unroll
+        for (int j = 0; j < NPRE; ++j) {
+            const int q = tid + 256 * j, row = q / C4, c4 = q % C4;
+            wpre[j] = *reinterpret_cast<const f32x4*>(a.params + (int64_t)(bm * BT + row) * d + bn * BT + 4 * c4);
+        }
     }
     // gradient contraction: the slots of the consumed gradients are read once, not once per stage in front of the
     // operand loads that depend on them
@@ -397,8 +417,9 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
             }
     __syncthreads();
     const float scale = a.lr / (float)a.Kv, invK = 1.0f / (float)a.Kv;
-    constexpr int C4 = BT / 4;           // float4 groups per row
-    for (int q = tid; q < BT * C4; q += 256) {
+#pragma unroll
+    for (int j = 0; j < BT * C4 / 256; ++j) {
+        const int q = tid + 256 * j;
         const int row = q / C4, c4 = q % C4;
         const f32x4 v = *reinterpret_cast<const f32x4*>(Cs + row * LDC + 4 * c4);
         if (FWD) {
@@ -416,7 +437,7 @@ __global__ __launch_bounds__(256, 2) void mlp_contract_kernel(MlpArgs a) {
             *reinterpret_cast<f32x4*>(a.dw_part + (int64_t)bz * H * d + p) = v;
         } else {
             const int64_t p = (int64_t)(bm * BT + row) * d + bn * BT + 4 * c4;
-            f32x4 w = *reinterpret_cast<const f32x4*>(a.params + p);
+            f32x4 w = wpre[NPRE == 1 ? 0 : j];
             unsigned short wb[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) { w[c] -= scale * v[c]; wb[c] = bf16_bits(w[c]); }
@@ -908,16 +929,17 @@ template <int G>
 __device__ __forceinline__ void small_update_body(const MlpArgs& a, int block, int nblocks) {
     const int H = a.H, C = a.C, d = a.d;
     const float invKm = 1.0f / ((float)a.Kv * (float)a.m);
-    float* b1 = a.params + (int64_t)H * d;
-    float* W2 = b1 + H;
-    float* b2 = W2 + (int64_t)C * H;
+    float* small = a.params + (int64_t)H * d;          // [b1 | W2 | b2]
     const int total = H + C * H + C + 1;
+    // G == 1 (few slots, a kernel that is all latency): the flag of a slot is loaded beside its record, all four
+    // quarters of it.  Larger G (many slots): the flags first, so that whole records are read once, not four times.
+    constexpr bool kBeside = G == 1;
     __shared__ int slots[256];
-    __shared__ int nquart[256];
+    __shared__ int nquart[kBeside ? 1 : 256];
     for (int l = threadIdx.x; l < a.Kv; l += blockDim.x) {
         const int sl = consumed_slot(a, l);
         slots[l] = sl;
-        nquart[l] = a.quartered[sl] != 0 ? 4 : 1;
+        if constexpr (!kBeside) nquart[l] = a.quartered[sl];
     }
     __syncthreads();
     const int g = threadIdx.x % G;
@@ -933,47 +955,59 @@ __device__ __forceinline__ void small_update_body(const MlpArgs& a, int block, i
             else if (q < H + C * H) { base = a.gw2 + (q - H); stride = C * H; }
             else if (q < H + C * H + C) { base = a.gb2 + (q - H - C * H); stride = 16; }
         }
+        // Everything the element needs is asked for at once: its old value, and of every slot the flag and all four
+        // quarters of the record (the quarters a whole record does not have are there in memory and are dropped by the
+        // select), so that the kernel is one round trip to memory deep, not three.
+        const float oldv = (live && g == 0 && q < total - 1) ? small[q] : 0.0f;
         float sum = 0.0f;
         if (live) {
             int l = g;
             for (; l + 3 * G < a.Kv; l += 4 * G) {
                 float v[4][4];
+                int nq[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < 4; ++u) {
+                    const int sl = slots[l + u * G];
+                    if constexpr (kBeside) nq[u] = a.quartered[sl]; else nq[u] = nquart[l + u * G];
+                    v[u][0] = base[(int64_t)sl * 4 * stride];
 #pragma unroll
-                    for (int qq = 0; qq < 4; ++qq)
-                        v[u][qq] = qq < nquart[l + u * G] ? base[((int64_t)slots[l + u * G] * 4 + qq) * stride] : 0.0f;
+                    for (int qq = 1; qq < 4; ++qq) v[u][qq] = (kBeside || nq[u] != 0) ? base[((int64_t)sl * 4 + qq) * stride] : 0.0f;
+                }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) sum += ((v[u][0] + v[u][1]) + v[u][2]) + v[u][3];
+                for (int u = 0; u < 4; ++u) {
+                    const bool four = nq[u] != 0;
+                    sum += ((v[u][0] + (four ? v[u][1] : 0.0f)) + (four ? v[u][2] : 0.0f)) + (four ? v[u][3] : 0.0f);
+                }
             }
             for (; l < a.Kv; l += G) {
+                const int sl = slots[l];
+                int nq1;
+                if constexpr (kBeside) nq1 = a.quartered[sl]; else nq1 = nquart[l];
+                const bool four = nq1 != 0;
                 float v[4];
+                v[0] = base[(int64_t)sl * 4 * stride];
 #pragma unroll
-                for (int qq = 0; qq < 4; ++qq) v[qq] = qq < nquart[l] ? base[((int64_t)slots[l] * 4 + qq) * stride] : 0.0f;
-                sum += ((v[0] + v[1]) + v[2]) + v[3];
+                for (int qq = 1; qq < 4; ++qq) v[qq] = (kBeside || four) ? base[((int64_t)sl * 4 + qq) * stride] : 0.0f;
+                sum += ((v[0] + (four ? v[1] : 0.0f)) + (four ? v[2] : 0.0f)) + (four ? v[3] : 0.0f);
             }
         }
 #pragma unroll
         for (int o = 1; o < G; o <<= 1) sum += __shfl_xor(sum, o, 64);
         if (live && g == 0) {
             const float gr = sum * invKm;
-            if (q < H) { const float nb = b1[q] - a.lr * gr; b1[q] = nb; if (a.b1r) a.b1r[q] = nb; if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr; }
-            else if (q < H + C * H) {
-                const float w = W2[q - H] - a.lr * gr;
-                W2[q - H] = w;
-                a.w2r[q - H] = bf16_round(w);
-                if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr;
-            } else if (q < H + C * H + C) {
-                const float nb = b2[q - H - C * H] - a.lr * gr;
-                b2[q - H - C * H] = nb;
-                if (a.b2r) a.b2r[q - H - C * H] = nb;
+            if (q == total - 1) {
+                a.tr.loss[a.v] = gr;
+            } else {
+                const float nv = oldv - a.lr * gr;
+                small[q] = nv;
+                if (q < H) { if (a.b1r) a.b1r[q] = nv; }
+                else if (q < H + C * H) a.w2r[q - H] = bf16_round(nv);
+                else if (a.b2r) a.b2r[q - H - C * H] = nv;
                 if (a.agg_out) a.agg_out[(int64_t)H * d + q] = gr;
             }
-            else a.tr.loss[a.v] = gr;
         }
     }
 }
-
 // ---- first-layer update from the partial sums of a split gradient contraction: shares added in order; the
 // first kSmallBlocks16 workgroups take the small parameters of the update instead, which need nothing from the others
 // (first, because theirs is the longer chain of loads)
@@ -1141,7 +1175,7 @@ hipError_t mlp_create(MlpState** out, const ssgd_model& model, int P, int m, int
     a.d1t = (unsigned short*)s->d1t.p; a.gb1 = (float*)s->gb1.p; a.gw2 = (float*)s->gw2.p; a.gb2 = (float*)s->gb2.p;
     a.loss = (float*)s->loss.p; a.ylab = (int32_t*)s->ylab.p; a.d2 = (float*)s->d2.p; a.quartered = (int32_t*)s->quartered.p;
     a.dw_part = (float*)s->dw_part.p; a.nsplit = 1; a.fsplit = 1; a.eval_base = -1;
-    a.b1r = nullptr; a.b2r = nullptr;
+    a.b1r = nullptr; a.b2r = nullptr; a.n_cons_inline = 0; a.n_rec_inline = 0;
 
     const float bound1 = (float)(1.0 / sqrt((double)a.d)), bound2 = (float)(1.0 / sqrt((double)a.H));
     hipLaunchKernelGGL(mlp_init_kernel, dim3(1024), dim3(256), 0, stream, a.params, seed, s->nw, n1, off2, n2, bound1, bound2);
@@ -1178,27 +1212,28 @@ int few_records_split(const MlpArgs& a, int nrec) { return std::max(2, std::min(
 
 // The launches of one update (a.v, a.Kv, a.nrec set), in two halves.  Forward half: the mini-batches that start at
 // version v, up to delta1 and the second-layer gradient records of their slots.
-void launch_forward(MlpArgs& a, hipStream_t stream) {
+void launch_forward(MlpArgs& a, hipStream_t stream, hipEvent_t done = nullptr) {
     if (a.variant == kBatchAsync) hipLaunchKernelGGL(mlp_batch_plan_kernel, dim3(1), dim3(64), 0, stream, a);
     if (few_records(a, a.nrec, 1)) {
         // few records: two launches; the depth is split so that two workgroups share every CU and none walks all of d
         a.fsplit = few_records_split(a, a.nrec);
         hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, true>), dim3(a.nrec, a.H / 64, a.fsplit), dim3(256), contract_lds(64), stream, a);
-        hipLaunchKernelGGL(mlp_mid_kernel, dim3(a.nrec * 4), dim3(256), mid_lds_bytes(a.H), stream, a);
+        hipExtLaunchKernelGGL(mlp_mid_kernel, dim3(a.nrec * 4), dim3(256), mid_lds_bytes(a.H), stream, nullptr, done, 0, a);
     } else if (a.nrec > 0 && ((a.nrec + 1) / 2) * (a.H / 128) >= 192) {
         // many records: large tiles, the rows again straight from the sample matrix
         hipLaunchKernelGGL((mlp_fwd_gather_kernel<128, false>), dim3((a.nrec + 1) / 2, a.H / 128), dim3(256), contract_lds(128), stream, a);
         hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
-        hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
+        hipExtLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, nullptr, done, 0, a);
     } else if (a.nrec > 0) {
         // in between: small tiles (the large ones would not fill the chip), the whole depth per workgroup
         hipLaunchKernelGGL((mlp_fwd_gather_kernel<64, false>), dim3(a.nrec, a.H / 64), dim3(256), contract_lds(64), stream, a);
         hipLaunchKernelGGL(mlp_output_kernel, dim3(a.nrec), dim3(256), 0, stream, a);
-        hipLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, a);
+        hipExtLaunchKernelGGL(mlp_delta1_kernel, dim3(a.nrec, a.H / 64), dim3(256), 0, stream, nullptr, done, 0, a);
     }
 }
 // Backward half: the first-layer gradient over the consumed slots and the update of every parameter.
-void launch_backward(MlpArgs& a, hipStream_t stream) {
+// (done: an event that the completion of the last launch records by itself, without an entry of its own in the stream)
+void launch_backward(MlpArgs& a, hipStream_t stream, hipEvent_t done = nullptr) {
     if (a.Kv >= 32) {
         // many slots: 128 x 128 tiles (half the operand traffic of the small ones), the slots split into shares so
         // that the chip is still full; the shares are added, in order, by the update kernel
@@ -1207,11 +1242,11 @@ void launch_backward(MlpArgs& a, hipStream_t stream) {
         const int tiles = (a.H / 128) * (a.d / 128);
         a.nsplit = std::max(1, std::min({kMaxSplit, a.Kv / 8, 512 / tiles}));
         hipLaunchKernelGGL((mlp_contract_kernel<false, 128, true>), dim3((a.H / 128) * 8 * (((a.d / 128) * a.nsplit + 7) / 8)), dim3(256), contract_lds(128), stream, a);
-        hipLaunchKernelGGL(mlp_w1_update_kernel, dim3(kW1Blocks + kSmallBlocks16), dim3(256), 0, stream, a);
+        hipExtLaunchKernelGGL(mlp_w1_update_kernel, dim3(kW1Blocks + kSmallBlocks16), dim3(256), 0, stream, nullptr, done, 0, a);
     } else {
         // small tiles: 384 workgroups instead of 96 matter more than the reuse inside a larger tile; one more row of
         // workgroups takes the small parameters
-        hipLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64 + 1), dim3(256), contract_lds(64), stream, a);
+        hipExtLaunchKernelGGL((mlp_contract_kernel<false, 64>), dim3(a.H / 64, a.d / 64 + 1), dim3(256), contract_lds(64), stream, nullptr, done, 0, a);
     }
 }
 void launch_update(MlpArgs& a, hipStream_t stream) {
@@ -1247,10 +1282,17 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
         if (r > 0 && s->own == nullptr && e == hipSuccess) e = hipStreamCreateWithFlags(&s->own, hipStreamNonBlocking);
     }
     // the versions of the consumed gradients, where updates may overlap (below)
-    std::vector<int32_t> tau_host;
+    std::vector<int32_t> tau_host, sel_host;
+    int64_t sel_first = 0;
     if (R == 1 && args[0].variant == kAsync && agg_out == nullptr && e == hipSuccess) {
         tau_host.resize((size_t)(n * tr.Kcap));
         e = hipMemcpyAsync(tau_host.data(), args[0].tr.tau + v0 * tr.Kcap, sizeof(int32_t) * tau_host.size(), hipMemcpyDeviceToHost, stream);
+        // ... and who they came from, one row more in front (the mini-batches that start at v0 are those of update v0 - 1)
+        const int64_t first = v0 > 0 ? v0 - 1 : 0;
+        sel_host.resize((size_t)((v0 + n - first) * tr.Kcap));
+        sel_first = first;
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(sel_host.data(), args[0].tr.sel + first * tr.Kcap, sizeof(int32_t) * sel_host.size(), hipMemcpyDeviceToHost, stream);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail(e, "reading K of the segment");
@@ -1350,6 +1392,18 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             a.b2r = (float*)s->b2v.p + (int64_t)k * 16;
         };
         const int64_t vs = v0 + q0;  // the first overlapped update
+        // short lists travel in the kernel arguments
+        auto inline_lists = [&](MlpArgs& a, int64_t v, int Kv, int nrec) {
+            a.n_cons_inline = 0; a.n_rec_inline = 0;
+            if (Kv <= 32) {
+                a.n_cons_inline = Kv;
+                for (int l = 0; l < Kv; ++l) a.cons_inline[l] = (int16_t)sel_host[(size_t)((v - sel_first) * tr.Kcap + l)];
+            }
+            if (v >= 1 && nrec <= 32) {
+                a.n_rec_inline = nrec;
+                for (int r = 0; r < nrec; ++r) a.rec_inline[r] = (int16_t)sel_host[(size_t)((v - 1 - sel_first) * tr.Kcap + r)];
+            }
+        };
         // the copies of version vs
         {
             MlpArgs a = base;
@@ -1378,6 +1432,7 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
                 f.v = v; f.Kv = Ks[0][(size_t)q]; f.nrec = nrec_of(0, q);
                 versioned(f, v);
                 f.dw_part = (float*)s->fwd_part.p + (v % kVer) * region;
+                inline_lists(f, v, f.Kv, f.nrec);
                 // (asked for on the host until it has happened: making the stream wait for an event that has not happened yet
                 // is the most expensive call there is here, 12 us, and a waiting entry holds up the kernels of the other
                 // streams that share its hardware queue)
@@ -1385,8 +1440,8 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
                     (void)hipGetLastError();
                     if (thread_error.load(std::memory_order_relaxed) != 0) return;
                 }
-                launch_forward(f, fs);
-                const hipError_t fe = hipEventRecord(ev_fwd(v), fs);
+                launch_forward(f, fs, f.nrec > 0 ? ev_fwd(v) : nullptr);
+                const hipError_t fe = f.nrec > 0 ? hipSuccess : hipEventRecord(ev_fwd(v), fs);
                 const hipError_t le = hipGetLastError();
                 if (fe != hipSuccess || le != hipSuccess) { thread_error.store((int)(fe != hipSuccess ? fe : le)); return; }
                 fwd_recorded[k].store(v, std::memory_order_release);
@@ -1416,9 +1471,10 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             MlpArgs u = base;
             u.v = v; u.Kv = Kv; u.nrec = nrec_of(0, q);
             versioned(u, v + 1);
-            launch_backward(u, stream);
+            inline_lists(u, v, u.Kv, u.nrec);
+            launch_backward(u, stream, ev_upd(v));
             const hipError_t le = hipGetLastError();
-            const hipError_t re = hipEventRecord(ev_upd(v), stream);
+            const hipError_t re = hipSuccess;
             if (le != hipSuccess || re != hipSuccess) { thread_error.store((int)(le != hipSuccess ? le : re)); break; }
             upd_recorded.store(v, std::memory_order_release);
         }
