@@ -41,6 +41,8 @@ struct ssgd_ctx {
     uint64_t seed = 0;
     hipStream_t stream = nullptr;
     hipStream_t side = nullptr;     // second stream for the schedule of the network's next piece (default priority)
+    int32_t* host_rows = nullptr;   // pinned: copies of replica 0's K, tau and sel rows of the segment being run (network)
+    size_t host_rows_words = 0;
     int device = 0;
     int64_t nw = 0;
     int32_t Kcap = 0, S = 0, G = 0, nbw = 0, maxrows = 0, table_ord = 1;
@@ -347,9 +349,34 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
             hipError_t e = hipEventRecord(before, c->stream);
             if (e == hipSuccess) e = hipStreamWaitEvent(c->side, before, 0);
             std::vector<hipEvent_t> written;
+            // One replica of the network: the rows that the host needs of every piece (K, tau, sel of replica 0; one row
+            // of sel in front) follow the schedule kernel to pinned memory, and the whole segment is one call below that
+            // takes them piece by piece, so that its kernels keep flowing from one piece to the next.
+            const bool one_call = c->model.kind == SSGD_MLP2 && c->R == 1;
+            const size_t W = (size_t)c->Kcap;
+            int32_t *hK = nullptr, *htau = nullptr, *hsel = nullptr;
+            if (one_call && e == hipSuccess) {
+                const size_t words = (size_t)seg * (1 + 2 * W) + W;
+                if (c->host_rows_words < words) {
+                    if (c->host_rows) (void)hipHostFree(c->host_rows);
+                    c->host_rows = nullptr; c->host_rows_words = 0;
+                    e = hipHostMalloc((void**)&c->host_rows, sizeof(int32_t) * words, hipHostMallocDefault);
+                    if (e == hipSuccess) c->host_rows_words = words;
+                }
+                hK = c->host_rows; htau = hK + seg; hsel = htau + (size_t)seg * W;
+                if (e == hipSuccess && c->j > 0)
+                    e = hipMemcpyAsync(hsel, c->tr.sel + (size_t)(c->j - 1) * W, sizeof(int32_t) * W, hipMemcpyDeviceToHost, c->side);
+            }
             for (int64_t off = 0; off < seg && e == hipSuccess; off += kPiece) {
                 sa.j0 = c->j + off; sa.count = std::min(kPiece, seg - off);
                 launch_schedule(sa, c->R, c->side);
+                if (one_call) {
+                    const size_t cnt = (size_t)sa.count;
+                    e = hipMemcpyAsync(hK + off, c->tr.K + sa.j0, sizeof(int32_t) * cnt, hipMemcpyDeviceToHost, c->side);
+                    if (e == hipSuccess) e = hipMemcpyAsync(htau + (size_t)off * W, c->tr.tau + (size_t)sa.j0 * W, sizeof(int32_t) * cnt * W, hipMemcpyDeviceToHost, c->side);
+                    if (e == hipSuccess) e = hipMemcpyAsync(hsel + (size_t)(off + 1) * W, c->tr.sel + (size_t)sa.j0 * W, sizeof(int32_t) * cnt * W, hipMemcpyDeviceToHost, c->side);
+                    if (e != hipSuccess) break;
+                }
                 hipEvent_t ev = nullptr;
                 e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
                 if (e == hipSuccess) { written.push_back(ev); e = hipEventRecord(ev, c->side); }
@@ -357,7 +384,12 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
             std::string msg;
             size_t k = 0;
             ssgd_status lin_st = SSGD_OK;
-            for (int64_t off = 0; off < seg && e == hipSuccess && lin_st == SSGD_OK; off += kPiece, ++k) {
+            if (one_call && e == hipSuccess) {
+                // (the kernels are launched after the host has seen a piece's event: no stream has to wait for it)
+                MlpPieces pc{written.data(), (int)written.size(), kPiece, hK, htau, hsel};
+                e = mlp_run_segment(c->mlp.data(), c->R, c->tr, c->ws, c->j, seg, agg_out, c->stream, &c->last_ms, &c->last_launches, &msg, &pc);
+            }
+            for (int64_t off = 0; off < seg && e == hipSuccess && lin_st == SSGD_OK && !one_call; off += kPiece, ++k) {
                 e = hipStreamWaitEvent(c->stream, written[k], 0);
                 if (e != hipSuccess) break;
                 if (c->model.kind == SSGD_MLP2)
@@ -996,6 +1028,7 @@ void ssgd_destroy(ssgd_ctx* c) {
     }
     for (size_t r = c->mlp.size(); r-- > 0;) mlp_destroy(c->mlp[r]);   // the first one owns what the others share
     if (c->side) (void)hipStreamDestroy(c->side);
+    if (c->host_rows) (void)hipHostFree(c->host_rows);
     DevBuf* bufs[] = {&c->table, &c->tr_t, &c->tr_loss, &c->tr_K, &c->tr_sel, &c->tr_tau, &c->tr_ord, &c->ws_finish,
                       &c->ws_tau, &c->ws_ord, &c->ws_clock, &c->ws_curK, &c->ws_winprev, &c->ws_winidx, &c->ws_F0,
                       &c->ws_intstart, &c->ws_crossed, &c->ws_ndone, &c->params, &c->park, &c->park_small, &c->zpart, &c->zx, &c->dx, &c->fallback,

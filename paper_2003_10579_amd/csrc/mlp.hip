@@ -1260,8 +1260,11 @@ void launch_update(MlpArgs& a, hipStream_t stream) {
 // its own (created here, default priority), update by update in turn, so that the latency chains of the replicas'
 // small kernels overlap on the device; the streams start after everything queued on `stream` and `stream` waits for them.
 hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, const WorkerState& ws, int64_t v0, int64_t n,
-                           float* agg_out, hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg) {
+                           float* agg_out, hipStream_t stream, double* ms_accum, int64_t* launches, std::string* msg,
+                           const MlpPieces* pieces) {
     auto fail = [&](hipError_t e, const char* what) { if (msg) *msg = what; return e; };
+    if (pieces != nullptr && (R != 1 || pieces->count < 1 || pieces->len < 1 || pieces->count * pieces->len < n))
+        return fail(hipErrorInvalidValue, "pieces of a segment: one replica, and they cover the segment");
     std::vector<MlpArgs> args((size_t)R);
     std::vector<std::vector<int32_t>> Ks((size_t)R, std::vector<int32_t>((size_t)n));
     std::vector<int32_t> prevK((size_t)R, 0);
@@ -1275,8 +1278,8 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
         const int64_t n1 = (int64_t)a.H * a.d, off2 = n1 + a.H, n2 = (int64_t)a.C * a.H;
         // the parameters may have been set from outside since the last segment
         hipLaunchKernelGGL(mlp_refresh_kernel, dim3(1024), dim3(256), 0, stream, a.params, a.w1r, a.w2r, n1, off2, n2);
-        // K is constant inside a segment; it is read back once
-        e = hipMemcpyAsync(Ks[(size_t)r].data(), a.tr.K + v0, sizeof(int32_t) * n, hipMemcpyDeviceToHost, stream);
+        // K is constant inside a segment; it is read back once (or comes piece by piece, see below)
+        if (pieces == nullptr) e = hipMemcpyAsync(Ks[(size_t)r].data(), a.tr.K + v0, sizeof(int32_t) * n, hipMemcpyDeviceToHost, stream);
         if (e == hipSuccess && a.variant == kAsync && v0 > 0)
             e = hipMemcpyAsync(&prevK[(size_t)r], a.tr.K + (v0 - 1), sizeof(int32_t), hipMemcpyDeviceToHost, stream);
         if (r > 0 && s->own == nullptr && e == hipSuccess) e = hipStreamCreateWithFlags(&s->own, hipStreamNonBlocking);
@@ -1284,7 +1287,11 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
     // the versions of the consumed gradients, where updates may overlap (below)
     std::vector<int32_t> tau_host, sel_host;
     int64_t sel_first = 0;
-    if (R == 1 && args[0].variant == kAsync && agg_out == nullptr && e == hipSuccess) {
+    if (pieces != nullptr) {
+        tau_host.resize((size_t)(n * tr.Kcap));
+        sel_host.resize((size_t)((n + 1) * tr.Kcap));
+        sel_first = v0 - 1;
+    } else if (R == 1 && args[0].variant == kAsync && agg_out == nullptr && e == hipSuccess) {
         tau_host.resize((size_t)(n * tr.Kcap));
         e = hipMemcpyAsync(tau_host.data(), args[0].tr.tau + v0 * tr.Kcap, sizeof(int32_t) * tau_host.size(), hipMemcpyDeviceToHost, stream);
         // ... and who they came from, one row more in front (the mini-batches that start at v0 are those of update v0 - 1)
@@ -1303,19 +1310,49 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
     (void)hipEventRecord(e0, stream);
     (void)hipEventRecord(fork, stream);
     for (int r = 1; r < R; ++r) (void)hipStreamWaitEvent(states[r]->own, fork, 0);
-    // the K of every update is checked before anything is launched
-    for (int r = 0; r < R; ++r) {
+    // the K of every update is checked before anything of it is launched
+    auto valid_K = [&](int r, int64_t qa, int64_t qb) {
         const MlpArgs& a = args[(size_t)r];
         const std::vector<int32_t>& K = Ks[(size_t)r];
-        for (int64_t q = 0; q < n; ++q) {
+        for (int64_t q = qa; q < qb; ++q) {
             const int64_t v = v0 + q;
             int nrec = (a.variant == kAsync) ? (v == 0 ? a.P : (q == 0 ? prevK[(size_t)r] : K[(size_t)q - 1])) : K[(size_t)q];
             if (a.variant == kBatchAsync) nrec = (v == 0 ? a.P : 1) + K[(size_t)q] - 1;
-            if (K[(size_t)q] < 1 || K[(size_t)q] > a.Kcap || nrec < 0 || nrec > states[r]->S) {
-                drop();
-                return fail(hipErrorInvalidValue, "inconsistent K in the trace");
-            }
+            if (K[(size_t)q] < 1 || K[(size_t)q] > a.Kcap || nrec < 0 || nrec > states[r]->S) return false;
         }
+        return true;
+    };
+    // Pieces: the rows of piece k are taken from the pinned copies once its event has happened.  avail = number of
+    // updates of the segment whose rows are here (all of them without pieces).
+    int64_t avail = pieces ? 0 : n;
+    int pieces_taken = 0;
+    int nrec_cap = 0;            // set by the overlapped path: the most records its forward buffers hold
+    auto take_piece = [&]() -> hipError_t {
+        const int k = pieces_taken;
+        const hipError_t pe = hipEventSynchronize(pieces->ready[k]);
+        if (pe != hipSuccess) return pe;
+        const int64_t qa = (int64_t)k * pieces->len, qb = std::min<int64_t>(n, qa + pieces->len);
+        const size_t W = (size_t)tr.Kcap;
+        std::memcpy(Ks[0].data() + qa, pieces->K + qa, sizeof(int32_t) * (size_t)(qb - qa));
+        std::memcpy(tau_host.data() + (size_t)qa * W, pieces->tau + (size_t)qa * W, sizeof(int32_t) * (size_t)(qb - qa) * W);
+        const int64_t ra = k == 0 ? 0 : qa + 1;     // rows of the copy of sel: one in front
+        std::memcpy(sel_host.data() + (size_t)ra * W, pieces->sel + (size_t)ra * W, sizeof(int32_t) * (size_t)(qb + 1 - ra) * W);
+        if (!valid_K(0, qa, qb)) return hipErrorInvalidValue;
+        if (nrec_cap > 0)
+            for (int64_t q = qa; q < qb; ++q) {
+                const int nr = (v0 + q == 0) ? args[0].P : (q == 0 ? prevK[0] : Ks[0][(size_t)q - 1]);
+                if (args[0].variant == kAsync && few_records(args[0], nr, 1) && nr > nrec_cap) return hipErrorInvalidValue;
+            }
+        ++pieces_taken;
+        avail = qb;
+        return hipSuccess;
+    };
+    if (pieces) {
+        const hipError_t pe = take_piece();
+        if (pe != hipSuccess) { drop(); return fail(pe, "the first piece of the schedule"); }
+    } else {
+        for (int r = 0; r < R; ++r)
+            if (!valid_K(r, 0, n)) { drop(); return fail(hipErrorInvalidValue, "inconsistent K in the trace"); }
     }
     auto nrec_of = [&](int r, int64_t q) {
         const MlpArgs& a = args[(size_t)r];
@@ -1336,14 +1373,14 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
     // the halves run one after the other as they would on one stream.)
     // (worth it where at most a quarter of the lists of the segment name their own version)
     int64_t q0 = n;
-    if (tau_host.size() == (size_t)(n * tr.Kcap) && n >= 4) {
+    if (tau_host.size() == (size_t)(n * tr.Kcap) && n >= 4 && args[0].variant == kAsync && agg_out == nullptr) {
         int64_t own = 0;
-        for (int64_t q = 0; q < n; ++q) {
+        for (int64_t q = 0; q < avail; ++q) {
             bool names_itself = false;
             for (int l = 0; l < Ks[0][(size_t)q]; ++l) names_itself |= tau_host[(size_t)(q * tr.Kcap + l)] >= (int32_t)(v0 + q);
             own += names_itself ? 1 : 0;
         }
-        if (4 * own <= n) q0 = 0;
+        if (4 * own <= avail) q0 = 0;
     }
     if (q0 < n) {
         // the updates before q0
@@ -1356,8 +1393,10 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
         const MlpArgs& base = args[0];
         const int64_t n1 = (int64_t)base.H * base.d, off2 = n1 + base.H, n2 = (int64_t)base.C * base.H;
         int nrec_max = 1;
-        for (int64_t q = q0; q < n; ++q)
+        // (K does not change inside a segment: the pieces still to come start no more records than these)
+        for (int64_t q = q0; q < avail; ++q)
             if (few_records(base, nrec_of(0, q), 1)) nrec_max = std::max(nrec_max, nrec_of(0, q));
+        nrec_cap = nrec_max;
         const int64_t region = (int64_t)8 * nrec_max * MP * base.H;
         hipError_t oe = hipSuccess;
         for (hipStream_t& f : s->fwd_stream)
@@ -1476,6 +1515,11 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             const hipError_t le = hipGetLastError();
             const hipError_t re = hipSuccess;
             if (le != hipSuccess || re != hipSuccess) { thread_error.store((int)(le != hipSuccess ? le : re)); break; }
+            // the rows of the next update are here before anybody is told that this one has been launched
+            if (q + 1 < n && q + 1 >= avail) {
+                const hipError_t pe = take_piece();
+                if (pe != hipSuccess) { thread_error.store((int)pe); break; }
+            }
             upd_recorded.store(v, std::memory_order_release);
         }
         for (std::thread& f : feeders) f.join();
@@ -1491,6 +1535,14 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
     // update by update, the replicas in turn: nothing in one replica's launches depends on another's.  (Launching every
     // replica from a host thread of its own gave the same rate: the device, not the host, is what limits it.)
     for (int64_t q = 0; q < n && q0 == n; ++q) {
+        if (q >= avail) {
+            const hipError_t pe = take_piece();
+            if (pe != hipSuccess) {
+                (void)hipStreamSynchronize(stream);
+                drop();
+                return fail(pe, "a piece of the schedule");
+            }
+        }
         for (int r = 0; r < R; ++r) {
             MlpArgs& a = args[(size_t)r];
             const std::vector<int32_t>& K = Ks[(size_t)r];
