@@ -340,7 +340,9 @@ ssgd_status run_updates(ssgd_ctx* c, int64_t J, float* agg_out) {
         // on the linear models leaves CUs free).  The pieces of the linear models are long: every piece is a launch of
         // its own, which reads the gradients in flight from HBM and writes them back.
         const bool linear_pipe = c->model.kind != SSGD_MLP2 && c->variant == SSGD_K_ASYNC && c->defer_per_launch >= 1 && agg_out == nullptr;
-        const int64_t kPiece = c->model.kind == SSGD_MLP2 ? 64 : 1024;
+        // (one replica of the network takes the rows of a piece as they come: short pieces, so that the first one of a
+        // segment, whose schedule nothing hides, is soon there)
+        const int64_t kPiece = c->model.kind == SSGD_MLP2 ? (c->R == 1 ? 16 : 64) : 1024;
         const bool pipelined = (c->model.kind == SSGD_MLP2 || linear_pipe) && c->ada.mode < 2 && seg > kPiece;
         if (pipelined) {
             if (!c->side) HIP_OK(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));

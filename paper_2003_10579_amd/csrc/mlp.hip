@@ -1074,6 +1074,10 @@ __global__ void mlp_init_kernel(float* params, uint64_t seed, int64_t nw, int64_
 
 // operand double buffer; the epilogue's fp32 tile [BT][BT + 4] fits inside it
 size_t contract_lds(int bt) { return (size_t)4 * bt * LDT * 2; }
+// Forward streams of the overlapped updates.  With the caller's stream and the stream of the schedule they are four:
+// a process has four hardware queues here, and streams that share one run their kernels one after the other (a long
+// schedule kernel in front of a forward kernel, say).
+constexpr int kFwdStreams = 2;
 constexpr int kVer = 8;          // versions of the operand copies of the parameters when updates overlap
 constexpr int kMaxSplit = 8;     // shares of the consumed slots in the split gradient contraction
 size_t mid_lds_bytes(int H) { return sizeof(float) * (16 * (size_t)(H + 4) + 4 * 256 + 256 + 4); }
@@ -1098,7 +1102,7 @@ struct MlpState {
     // streams for the forward halves of consecutive updates, a pool of events
     DevMem xb16;                 // the first replica's bf16 copy of the sample matrix; the others use it too
     DevMem w1v, w2v, b1v, b2v, fwd_part;   // allocated by the first segment that overlaps
-    hipStream_t fwd_stream[3] = {nullptr, nullptr, nullptr};
+    hipStream_t fwd_stream[kFwdStreams] = {};
     std::vector<hipEvent_t> ev_pool;
     DevMem params, w1r, w2r, xb, xbt, hbuf, d1t, gb1, gw2, gb2, d2, loss, ylab, dw_part, plan, quartered;
     hipStream_t stream = nullptr;
@@ -1365,7 +1369,7 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
     // consumes were computed at versions tau <= v (Sec. 2.2), with few gradients per update many updates ago, so the
     // backward half of v (which gives w_{v+1}) needs the backward half of v - 1 and the forward halves of the versions in
     // its list, not the forward half of v itself unless the list names it; that one needs w_v only.  The backward halves
-    // follow each other on `stream`; the forward halves of consecutive versions go to three streams in turn, each fed
+    // follow each other on `stream`; the forward halves of consecutive versions go to kFwdStreams streams in turn, each fed
     // by a host thread of its own (the host's calls, not the device, would otherwise set the pace).
     // The operand copies of the parameters (bf16 W1, rounded W2, the biases) and the partial sums of the split forward
     // pass exist kVer times, indexed by version modulo kVer: the update of v writes the copies of v + 1 after the
@@ -1455,7 +1459,7 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
         (void)hipEventRecord(start, stream);
         // what the host threads tell each other: an event may be waited for only after the call that records it
         std::atomic<int64_t> upd_recorded{vs - 1};                 // ev_upd of every version up to here has been recorded
-        std::atomic<int64_t> fwd_recorded[3];                      // per forward stream: its newest version with ev_fwd recorded
+        std::atomic<int64_t> fwd_recorded[kFwdStreams];                      // per forward stream: its newest version with ev_fwd recorded
         for (auto& f : fwd_recorded) f.store(-1);
         std::atomic<int> thread_error{0};
         auto forward_half = [&](int k) {
@@ -1463,7 +1467,7 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             hipStream_t fs = s->fwd_stream[k];
             for (int64_t q = q0; q < n; ++q) {
                 const int64_t v = v0 + q;
-                if ((int)(v % 3) != k) continue;
+                if ((int)(v % kFwdStreams) != k) continue;
                 while (upd_recorded.load(std::memory_order_acquire) < v - 1) {
                     if (thread_error.load(std::memory_order_relaxed) != 0) return;
                 }
@@ -1486,11 +1490,11 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
                 fwd_recorded[k].store(v, std::memory_order_release);
             }
         };
-        std::thread feeders[3];
-        for (int k = 0; k < 3; ++k) feeders[k] = std::thread(forward_half, k);
+        std::thread feeders[kFwdStreams];
+        for (int k = 0; k < kFwdStreams; ++k) feeders[k] = std::thread(forward_half, k);
         int64_t waited = vs - 1;     // the contractions have waited for the forward halves of every version up to here
         auto wait_forward = [&](int64_t t) {
-            while (fwd_recorded[t % 3].load(std::memory_order_acquire) < t)
+            while (fwd_recorded[t % kFwdStreams].load(std::memory_order_acquire) < t)
                 if (thread_error.load(std::memory_order_relaxed) != 0) return;
             // (an event that has already happened needs no entry in the stream)
             if (hipEventQuery(ev_fwd(t)) != hipSuccess) {
