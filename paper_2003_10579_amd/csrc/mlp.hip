@@ -1491,7 +1491,12 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             }
         };
         std::thread feeders[kFwdStreams];
-        for (int k = 0; k < kFwdStreams; ++k) feeders[k] = std::thread(forward_half, k);
+        // (a thread that cannot be started must not throw through the C boundary above: the ones that run are told to stop)
+        try {
+            for (int k = 0; k < kFwdStreams; ++k) feeders[k] = std::thread(forward_half, k);
+        } catch (...) {
+            thread_error.store((int)hipErrorOutOfMemory);
+        }
         int64_t waited = vs - 1;     // the contractions have waited for the forward halves of every version up to here
         auto wait_forward = [&](int64_t t) {
             while (fwd_recorded[t % kFwdStreams].load(std::memory_order_acquire) < t)
@@ -1526,7 +1531,7 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
             }
             upd_recorded.store(v, std::memory_order_release);
         }
-        for (std::thread& f : feeders) f.join();
+        for (std::thread& f : feeders) if (f.joinable()) f.join();
         if (thread_error.load() == 0)
             for (int64_t t = std::max(waited + 1, vs); t < v0 + n; ++t) (void)hipStreamWaitEvent(stream, ev_fwd(t), 0);
         if (thread_error.load() != 0) {
