@@ -1479,8 +1479,12 @@ hipError_t mlp_run_segment(MlpState* const* states, int R, const Trace& tr, cons
                 // (asked for on the host until it has happened: making the stream wait for an event that has not happened yet
                 // is the most expensive call there is here, 12 us, and a waiting entry holds up the kernels of the other
                 // streams that share its hardware queue)
-                while (hipEventQuery(q == q0 ? start : ev_upd(v - 1)) != hipSuccess) {
+                for (;;) {
+                    const hipError_t qe = hipEventQuery(q == q0 ? start : ev_upd(v - 1));
+                    if (qe == hipSuccess) break;
                     (void)hipGetLastError();
+                    // anything but "not ready" is an error of the device: nobody waits for an event that will not come
+                    if (qe != hipErrorNotReady) { thread_error.store((int)qe); return; }
                     if (thread_error.load(std::memory_order_relaxed) != 0) return;
                 }
                 launch_forward(f, fs, f.nrec > 0 ? ev_fwd(v) : nullptr);
