@@ -117,7 +117,10 @@ ssgd_status ssgd_create(const ssgd_model *model, int32_t P, int32_t K, int32_t m
 /* Perform J further parameter-server updates in every replica: delays,
  * K-of-P selection, mini-batch gradients at the (possibly stale) parameters each
  * contributor read, w_{j+1} = w_j - (lr/K) sum_l g_l.  Appends to the trace.
- * Returns after the work has completed on the stream. */
+ * Returns after the work has completed on the stream.  The library may use further
+ * streams of its own (default priority; they start after the work queued on
+ * `hip_stream` and that stream waits for them) and, for one replica of SSGD_MLP2,
+ * two short-lived host threads that launch kernels during the call. */
 ssgd_status ssgd_run(ssgd_ctx *ctx, int64_t J);
 
 /* Make room in the trace for `updates` further updates now, so that later ssgd_run
