@@ -92,6 +92,26 @@ def config2_rate(ssgd, Xd, yd, replicas=40, updates=200):
             "worker_gradients_per_s": rate, "frac_of_hbm_peak": rate * 128 * (3072 + 1) * 4 / 1e9 / HBM_PEAK_GBS}
 
 
+def config4_rate(ssgd, Xd, yd, updates=4000):
+    """Config 4 (two-layer network 3072-512-10, P=256, m=64, K-async, AdaSync by plateau doubling from K=8; bf16 MFMA)
+    through the same library: updates and worker-gradients per second of a free run."""
+    import torch
+    ada = dict(mode=1, K0=8, Kmax=256, window=200, rel_tol=0.01)
+    ctx = ssgd.Context("mlp2", Xd, yd, 256, 8, 64, "k_async", ssgd.delay_dist("shifted_exp", 0.5, 1.0), 0.05, seed=0,
+                       classes=10, hidden=512, bf16=1, adasync=ada)
+    ctx.reserve_trace(updates + 400)
+    ctx.run(400)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.run(updates)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    K = ctx.trace(0, 400, updates)["K"]
+    ctx.close()
+    return {"workload": f"config 4: MLP 3072-512-10 K-async P=256 m=64 AdaSync from K=8, shifted-exp(0.5,1), {updates} updates, 1 replica",
+            "us_per_update": dt / updates * 1e6, "worker_gradients_per_s": float(K.sum()) / dt, "K_last": int(K[-1])}
+
+
 def mc_rate(ssgd):
     """Monte-Carlo runtime estimator (config 3 shape: P=128, every K, K-async chains of 8 updates, Exp(1))."""
     dist = ssgd.delay_dist("exp", 1.0)
@@ -178,6 +198,7 @@ def main():
         out["roofline"]["traffic_GBps"] = out["roofline"]["traffic"] / (kms / kn * 1e-3) / 1e9
         out["roofline"]["traffic_frac_of_stream_read"] = out["roofline"]["traffic_GBps"] / stream_gbs
     out["config"]["config2"] = config2_rate(ssgd, Xd, yd)
+    out["config"]["config4"] = config4_rate(ssgd, Xd, yd)
     out["config"]["mc_trials_per_s"] = mc_rate(ssgd)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(X, y, spec)
