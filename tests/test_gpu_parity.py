@@ -534,6 +534,23 @@ def test_mlp_kasync_training_run(ssgd, oracle, torch_cuda):
     ctx.close()
 
 
+@pytest.mark.parametrize("variant,P,K", [("k_sync", 8, 3), ("k_batch_sync", 8, 5), ("k_batch_async", 8, 3), ("k_async", 8, 6)])
+def test_mlp_long_call_takes_the_schedule_in_pieces(ssgd, oracle, torch_cuda, variant, P, K):
+    """One call of 70 updates on a single replica of the network: the schedule is written 16 updates at a time on a
+    second stream and the gradient kernels take every piece's trace rows from host copies as they arrive -- for every
+    variant, also the ones whose updates are launched one after the other (K-async with K = 6 of 8 workers consumes
+    gradients of the updating version in most updates, so it is one of them)."""
+    X, y = synth.mixture_data(1500, 256, 10, seed=12)
+    ctx, tr = _mlp_pair(ssgd, oracle, torch_cuda, X, y, P, K, 32, variant, ("shifted_exp", 0.5, 1.0), 0.05, 10, 128, seed=9)
+    ctx.run(70)
+    tr.run(70)
+    assert_trace_equal(ctx.trace(), tr.trace())
+    pr = rel(ctx.params(), tr.params())
+    assert pr <= MLP_PARAM_TOL, pr
+    assert np.allclose(ctx.trace()["loss"], tr.trace()["loss"], rtol=5e-3, atol=1e-4)
+    ctx.close()
+
+
 def test_mlp_replicas_are_independent_runs(ssgd, oracle, torch_cuda):
     """Three replicas of the network in one context (they run beside each other on streams of their own): each follows
     the oracle's run with its replica index, through a change of K by plateau doubling, and a snapshot taken half-way
