@@ -952,6 +952,30 @@ def test_mlp_snapshot_resume(ssgd, oracle, torch_cuda, variant, K):
     a.close(); b.close()
 
 
+def test_mlp_snapshot_resume_through_overlapped_updates(ssgd, torch_cuda):
+    """Snapshot and resume where a single K-async replica overlaps its updates (calls of 40 updates, 8 workers, K = 2):
+    the operand copies of the parameters that the overlapped launches keep per version are rebuilt from the
+    snapshot's parameters, and the resumed run is the original one bit by bit."""
+    torch = torch_cuda
+    X, y = synth.mixture_data(1500, 256, 10, seed=21)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    gd = ssgd.delay_dist("shifted_exp", 0.5, 1.0)
+    mk = lambda: ssgd.Context("mlp2", Xd, yd, 8, 2, 32, "k_async", gd, 0.05, seed=23, classes=10, hidden=128, bf16=1)
+    a = mk()
+    a.run(40)
+    blob = a.get_state()
+    a.run(40)
+    b = mk()
+    b.run(5)                 # a different past, replaced by the snapshot
+    b.set_state(blob)
+    b.run(40)
+    ta, tb = a.trace(), b.trace()
+    for key in ta:
+        assert np.array_equal(ta[key], tb[key]), key
+    assert np.array_equal(a.params(), b.params())
+    a.close(); b.close()
+
+
 # ------------------------------------------------------------------------------- K-batch-async
 
 @pytest.mark.parametrize("kind,P,K,m,d,classes,spec", [
