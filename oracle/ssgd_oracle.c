@@ -19,10 +19,12 @@
  *
  * Parity unpinned (nothing outside this file fixes the values; the tests pin
  * everything else against closed forms, brute force, known-answer vectors or
- * textbook special cases): the K-async inter-update times of orc_runtime_mc
- * under Pareto delays beyond the first update of a chain; the long-horizon
- * trajectory of the two-layer network (pinned only through its per-step
- * gradients, finite differences and a scaled-down run).
+ * textbook special cases): the long-horizon trajectory of the two-layer
+ * network (pinned only through its per-step gradients, finite differences and
+ * a scaled-down run).  The K-async inter-update times of orc_runtime_mc under
+ * Pareto delays beyond the first update of a chain have no closed form; they
+ * are pinned in law (renewal rate E[X]/P at K = 1, identity with K-sync at
+ * K = P, and an independent vectorised simulation for every K).
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fPIC -shared
  */
